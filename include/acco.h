@@ -1,0 +1,169 @@
+/*
+ * acco.h - C ABI of the ACCO per-shard optimizer path for AMD MI355X (gfx950).
+ *
+ * One shard owner's work between the gradient Reduce_Scatter and the parameter
+ * All_Gather of ACCO's communication stream (Alg. 1 of the paper, "Training with
+ * ACCO in parallel for a worker i"; update rule: eq. (ACCO), stages (1) and (2)):
+ *
+ *   acco_accumulate      g_i <- g_i + grad(micro-batch), N_i <- N_i + 1
+ *   acco_cast_params     fp32 -> bf16 (publish g_i to the communication buffer;
+ *                        bf16 parameter shard for the All_Gather)
+ *   acco_reduce_shards   owner's slice of sum_i g_i and the sum of the counts
+ *   acco_estimate_step   theta~(t+1) = Opt(theta(t), sum g~ / sum N~)   - nothing committed
+ *   acco_commit_step     theta(t+1)  = Opt(theta(t), (sum g + sum g~)/(sum N + sum N~))
+ *
+ * with Opt = AdamW (decoupled weight decay, bias-corrected moments, epsilon added
+ * to the bias-corrected root), fp32 sharded states theta, m, v and bf16
+ * parameters / communication buffers (experimental setup, Sec. 4.2).
+ *
+ * Conventions for every entry point
+ *   - "device" pointers address memory of the current HIP device; "host" pointers
+ *     address ordinary host memory.  The caller owns every buffer; the library
+ *     allocates nothing, frees nothing and keeps no pointer after the call.
+ *   - Arrays are flat and contiguous, element j at index j.  bf16 values are
+ *     passed as uint16_t bit patterns.  Device pointers must be 16-byte aligned.
+ *   - n is the shard length in elements, 0 <= n <= ACCO_MAX_ELEMS.  n == 0 does no
+ *     device work but still performs the host counter bookkeeping.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device work is enqueued on it and the call returns without waiting; host
+ *     counters are updated before return.
+ *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
+ *     is enqueued and no host counter is modified.
+ *   - Thread-safe; no global mutable state besides cached device properties.
+ */
+#ifndef ACCO_H
+#define ACCO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ACCO_MAX_ELEMS   ((int64_t)1 << 40)
+#define ACCO_MAX_WORKERS 64
+
+typedef enum acco_status {
+    ACCO_OK         = 0,
+    ACCO_ERR_NULL   = -1, /* a required pointer is NULL                               */
+    ACCO_ERR_SIZE   = -2, /* n < 0, n > ACCO_MAX_ELEMS, workers outside 1..64         */
+    ACCO_ERR_ALIGN  = -3, /* a device pointer is not 16-byte aligned                  */
+    ACCO_ERR_ARG    = -4, /* bad hyper-parameter, count, step, dtype or flag          */
+    ACCO_ERR_ALIAS  = -5, /* an output overlaps an input it must not overlap          */
+    ACCO_ERR_DEVICE = -6  /* the HIP runtime reported an error at launch              */
+} acco_status;
+
+typedef enum acco_dtype {
+    ACCO_BF16 = 0, /* shards are bf16 bit patterns (the paper's communication buffers) */
+    ACCO_F32  = 1  /* shards are fp32 (accumulators reduced without the bf16 publish)  */
+} acco_dtype;
+
+/* AdamW hyper-parameters (App. C, hyper-parameter tables: lr 6e-4, weight decay 0.1,
+ * betas (0.9, 0.95) for pre-training; the paper does not state epsilon).
+ * Valid: lr >= 0, 0 <= beta < 1, eps >= 0, weight_decay >= 0, all finite. */
+typedef struct acco_adamw_t {
+    double lr;
+    double beta1;
+    double beta2;
+    double eps;
+    double weight_decay;
+} acco_adamw_t;
+
+/*
+ * Gradient accumulation of the computation stream (Alg. 1: g_i <- g_i + grad F,
+ * N_i <- N_i + 1).
+ *   acc        device, fp32[n], in/out: one worker's accumulator
+ *   grad_bf16  device, bf16[n], in:     one micro-batch gradient
+ *   init       0: acc[j] += grad[j].  1: acc[j] = grad[j] (start of a new
+ *              accumulation; the old contents of acc are not read)
+ *   count      host, nullable, in/out: the worker's micro-batch counter N_i;
+ *              set to 1 when init, else incremented.
+ * Errors: NULL acc/grad, bad n, misalignment, acc overlapping grad, init not 0/1,
+ *         *count < 0 (or == INT64_MAX) when it is to be incremented.
+ */
+int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, int init, int64_t* count,
+                    void* stream);
+
+/*
+ * fp32 -> bf16, round to nearest even (NaN stays NaN, overflow goes to infinity).
+ * Used for Buffer_i <- g_i (bf16 communication buffer) and for the bf16 parameter
+ * shard handed to the All_Gather when the step kernels' fused output is not used.
+ *   out_bf16  device, bf16[n], out
+ *   src       device, fp32[n], in
+ */
+int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stream);
+
+/*
+ * The reduce half of the gradient Reduce_Scatter as the shard owner sees it
+ * (Alg. 1, communication stream), together with the All_Reduce of the counts:
+ *   accumulate == 0 (stage 1):  gsum[j]  = x_0[j] + x_1[j] + ... + x_{W-1}[j]
+ *   accumulate == 1 (stage 2):  gsum[j] += x_0[j] + ... (added one by one onto the
+ *                               retained stage-1 sum)
+ * in fp32, strictly in ascending worker order.
+ *   gsum      device, fp32[n], out (in/out when accumulate)
+ *   shards    HOST array of `workers` DEVICE pointers, each bf16[n] or fp32[n]
+ *             according to dtype; read before the call returns
+ *   workers   1 .. ACCO_MAX_WORKERS
+ *   counts    host, nullable: counts[w] = micro-batches summed in shard w (>= 0)
+ *   total     host, nullable, in/out: accumulate ? *total + sum(counts) : sum(counts).
+ *             counts and total are given together or not at all.
+ * Errors: NULLs, bad n/workers/dtype/flag, misalignment, gsum overlapping a
+ *         shard, negative count, total overflow.
+ */
+int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype, int64_t n,
+                       int accumulate, const int64_t* counts, int64_t* total, void* stream);
+
+/*
+ * Stage (1) of eq. (ACCO): the speculative parameters
+ *   theta~ = AdamW(theta, m, v; g = gsum / total_count; update index = step + 1)
+ * theta, m, v and the step counter are only read: stage (2) starts again from the
+ * same theta(t).
+ *   theta, m, v, gsum  device, fp32[n], in
+ *   theta_tilde_f32    device, fp32[n], out, nullable
+ *   theta_tilde_bf16   device, bf16[n], out, nullable  (at least one output)
+ *   step               number of updates committed so far (>= 0)
+ *   total_count        number of micro-batch gradients summed in gsum (>= 1)
+ * Errors: NULLs, bad n, misalignment, an output overlapping an input or the other
+ *         output, invalid hyper-parameters, step < 0, total_count < 1.
+ */
+int acco_estimate_step(const float* theta, const float* m, const float* v, const float* gsum,
+                       float* theta_tilde_f32, uint16_t* theta_tilde_bf16, int64_t n,
+                       const acco_adamw_t* hp, int64_t step, int64_t total_count, void* stream);
+
+/*
+ * Stage (2) of eq. (ACCO): the committed update on the full delayed gradient
+ *   (theta, m, v) <- AdamW(theta, m, v; g = gsum / total_count; update index = *step + 1)
+ * in place, then *step += 1.
+ *   theta, m, v  device, fp32[n], in/out (pairwise distinct)
+ *   gsum         device, fp32[n], in
+ *   theta_bf16   device, bf16[n], out, nullable: bf16 copy of the new theta, written
+ *                in the same pass (the All_Gather input)
+ *   step         host, in/out: updates committed so far (>= 0)
+ * Errors: as acco_estimate_step; step == NULL.
+ */
+int acco_commit_step(float* theta, float* m, float* v, const float* gsum, uint16_t* theta_bf16,
+                     int64_t n, const acco_adamw_t* hp, int64_t* step, int64_t total_count,
+                     void* stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* acco_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int acco_version(void);
+
+/*
+ * Launch shape used for subsequent calls of one entry point ("accumulate", "cast",
+ * "reduce", "estimate", "commit"): threads per workgroup (64..512, multiple of 64),
+ * 16-byte vectors each thread keeps in flight per array (1, 2 or 4), and workgroups
+ * per compute unit (0 = one workgroup per tile, > 0 = grid-stride over that many
+ * resident workgroups per CU).  Process-wide; meant for benchmarking, not required.
+ * Returns ACCO_ERR_ARG for an unknown name or an unsupported value.
+ */
+int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,
+                          int workgroups_per_cu);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ACCO_H */

@@ -142,14 +142,15 @@ ORACLE_EXPORT void oracle_reduce(float* gsum, const void* const* shards, int wor
 /* Textbook AdamW with bias correction, binary64 arithmetic, at update index
  * `step` (1-based), on the gradient sum divided by the total count. */
 static void adamw_elem_f64(float theta, float m, float v, float gsum, double count,
-                           const oracle_hyper* hp, double step, float* theta_o, float* m_o,
-                           float* v_o)
+                           const oracle_hyper* hp, double bc1, double bc2, float* theta_o,
+                           float* m_o, float* v_o)
 {
+    /* bc1 = 1 - beta1^step, bc2 = 1 - beta2^step: the same for every element of a step */
     double g     = (double)gsum / count;
     double m1    = hp->beta1 * (double)m + (1.0 - hp->beta1) * g;
     double v1    = hp->beta2 * (double)v + (1.0 - hp->beta2) * g * g;
-    double m_hat = m1 / (1.0 - pow(hp->beta1, step));
-    double v_hat = v1 / (1.0 - pow(hp->beta2, step));
+    double m_hat = m1 / bc1;
+    double v_hat = v1 / bc2;
     double th    = (double)theta;
     double t1    = th - hp->lr * hp->weight_decay * th - hp->lr * m_hat / (sqrt(v_hat) + hp->eps);
     *theta_o     = (float)t1;
@@ -211,10 +212,12 @@ ORACLE_EXPORT void oracle_estimate_f64(const float* theta, const float* m, const
                                        int64_t n, const oracle_hyper* hp, int64_t step,
                                        int64_t count)
 {
+    const double bc1 = 1.0 - pow(hp->beta1, (double)step);
+    const double bc2 = 1.0 - pow(hp->beta2, (double)step);
 #pragma omp parallel for schedule(static) num_threads(g_threads)
     for (int64_t j = 0; j < n; ++j) {
         float t1, m1, v1;
-        adamw_elem_f64(theta[j], m[j], v[j], gsum[j], (double)count, hp, (double)step, &t1, &m1,
+        adamw_elem_f64(theta[j], m[j], v[j], gsum[j], (double)count, hp, bc1, bc2, &t1, &m1,
                        &v1);
         if (out_f32) out_f32[j] = t1;
         if (out_bf16) out_bf16[j] = oracle_f32_to_bf16(t1);
@@ -243,10 +246,12 @@ ORACLE_EXPORT void oracle_commit_f64(float* theta, float* m, float* v, const flo
                                      uint16_t* out_bf16, int64_t n, const oracle_hyper* hp,
                                      int64_t step, int64_t count)
 {
+    const double bc1 = 1.0 - pow(hp->beta1, (double)step);
+    const double bc2 = 1.0 - pow(hp->beta2, (double)step);
 #pragma omp parallel for schedule(static) num_threads(g_threads)
     for (int64_t j = 0; j < n; ++j) {
         float t1, m1, v1;
-        adamw_elem_f64(theta[j], m[j], v[j], gsum[j], (double)count, hp, (double)step, &t1, &m1,
+        adamw_elem_f64(theta[j], m[j], v[j], gsum[j], (double)count, hp, bc1, bc2, &t1, &m1,
                        &v1);
         theta[j] = t1;
         m[j]     = m1;

@@ -1,0 +1,208 @@
+"""ctypes binding of ``libacco.so`` with the same names as the C ABI (include/acco.h).
+
+Argument marshalling only: tensors are checked (device, dtype, contiguity, length)
+and handed to the library as raw device pointers together with torch's current HIP
+stream.  Every step of the path runs in the library's kernels; there is no fallback
+- if the library is missing the import of this module's functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+from . import build as _build
+
+ACCO_OK = 0
+ACCO_ERR_NULL, ACCO_ERR_SIZE, ACCO_ERR_ALIGN = -1, -2, -3
+ACCO_ERR_ARG, ACCO_ERR_ALIAS, ACCO_ERR_DEVICE = -4, -5, -6
+ACCO_BF16, ACCO_F32 = 0, 1
+ACCO_MAX_WORKERS = 64
+
+EXPORTS = ("acco_accumulate", "acco_cast_params", "acco_reduce_shards", "acco_estimate_step",
+           "acco_commit_step", "acco_status_string", "acco_version", "acco_set_launch_shape")
+
+
+class AdamW(ctypes.Structure):
+    """acco_adamw_t"""
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class AccoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.ACCO_SO):
+            raise RuntimeError(
+                f"{_build.ACCO_SO} not found: build it with paper_2406_02613_amd/build.py "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(_build.ACCO_SO)
+        p, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        pi64 = ctypes.POINTER(ctypes.c_int64)
+        L.acco_accumulate.argtypes = [p, p, i64, ci, pi64, p]
+        L.acco_cast_params.argtypes = [p, p, i64, p]
+        L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, p]
+        L.acco_estimate_step.argtypes = [p, p, p, p, p, p, i64, ctypes.POINTER(AdamW), i64, i64, p]
+        L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, p]
+        L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
+        for name in EXPORTS:
+            getattr(L, name).restype = ci
+        L.acco_status_string.restype = ctypes.c_char_p
+        L.acco_status_string.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().acco_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().acco_version())
+
+
+def set_launch_shape(entry: str, threads: int, vectors_in_flight: int,
+                     workgroups_per_cu: int) -> None:
+    rc = lib().acco_set_launch_shape(entry.encode(), threads, vectors_in_flight, workgroups_per_cu)
+    if rc != ACCO_OK:
+        raise AccoError(rc, "acco_set_launch_shape")
+
+
+# ----------------------------------------------------------------------------- marshalling
+
+
+def _stream() -> ctypes.c_void_p:
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, n: int, name: str) -> int:
+    """Device pointer of a checked tensor."""
+    import torch
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch.Tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must live on the GPU")
+    if t.device.index != torch.cuda.current_device():
+        raise ValueError(f"{name}: is on {t.device}, current device is "
+                         f"{torch.cuda.current_device()}")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if t.numel() != n:
+        raise ValueError(f"{name}: has {t.numel()} elements, expected {n}")
+    return t.data_ptr()
+
+
+def _opt(t, dtype, n, name):
+    return None if t is None else _dev(t, dtype, n, name)
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != ACCO_OK:
+        raise AccoError(rc, where)
+
+
+class Counter:
+    """A host int64 the library reads and updates (micro-batch counts, totals, step)."""
+
+    def __init__(self, value: int = 0):
+        self._c = ctypes.c_int64(int(value))
+
+    @property
+    def value(self) -> int:
+        return int(self._c.value)
+
+    @value.setter
+    def value(self, x: int) -> None:
+        self._c.value = int(x)
+
+    def ref(self):
+        return ctypes.byref(self._c)
+
+    def __repr__(self) -> str:
+        return f"Counter({self.value})"
+
+
+def make_hyper(lr, beta1, beta2, eps, weight_decay) -> AdamW:
+    return AdamW(float(lr), float(beta1), float(beta2), float(eps), float(weight_decay))
+
+
+# ----------------------------------------------------------------------------- entry points
+
+
+def acco_accumulate(acc, grad_bf16, init: bool, count: Optional[Counter] = None) -> None:
+    import torch
+    n = acc.numel()
+    rc = lib().acco_accumulate(_dev(acc, torch.float32, n, "acc"),
+                               _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
+                               int(bool(init)), None if count is None else count.ref(), _stream())
+    _check(rc, "acco_accumulate")
+
+
+def acco_cast_params(out_bf16, src) -> None:
+    import torch
+    n = src.numel()
+    rc = lib().acco_cast_params(_dev(out_bf16, torch.bfloat16, n, "out_bf16"),
+                                _dev(src, torch.float32, n, "src"), n, _stream())
+    _check(rc, "acco_cast_params")
+
+
+def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
+                       counts: Optional[Sequence[int]] = None,
+                       total: Optional[Counter] = None) -> None:
+    import torch
+    n = gsum.numel()
+    W = len(shards)
+    if W < 1:
+        raise AccoError(ACCO_ERR_SIZE, "acco_reduce_shards")
+    dt = shards[0].dtype
+    if dt not in (torch.bfloat16, torch.float32):
+        raise TypeError("shards: expected bfloat16 or float32 tensors")
+    ptrs = (ctypes.c_void_p * W)(*[_dev(s, dt, n, f"shards[{i}]") for i, s in enumerate(shards)])
+    cnts = None
+    if counts is not None:
+        if len(counts) != W:
+            raise ValueError("counts: one per shard")
+        cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
+    rc = lib().acco_reduce_shards(_dev(gsum, torch.float32, n, "gsum"), ptrs, W,
+                                  ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32, n,
+                                  int(bool(accumulate)), cnts,
+                                  None if total is None else total.ref(), _stream())
+    _check(rc, "acco_reduce_shards")
+
+
+def acco_estimate_step(theta, m, v, gsum, hp: AdamW, step: int, total_count: int, *,
+                       theta_tilde_f32=None, theta_tilde_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    rc = lib().acco_estimate_step(_dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"),
+                                  _dev(v, f32, n, "v"), _dev(gsum, f32, n, "gsum"),
+                                  _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
+                                  _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"),
+                                  n, ctypes.byref(hp), int(step), int(total_count), _stream())
+    _check(rc, "acco_estimate_step")
+
+
+def acco_commit_step(theta, m, v, gsum, hp: AdamW, step: Counter, total_count: int, *,
+                     theta_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    rc = lib().acco_commit_step(_dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"),
+                                _dev(v, f32, n, "v"), _dev(gsum, f32, n, "gsum"),
+                                _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
+                                ctypes.byref(hp), step.ref(), int(total_count), _stream())
+    _check(rc, "acco_commit_step")

@@ -1,0 +1,365 @@
+// Host side of the C ABI declared in include/acco.h: argument validation, host
+// counter bookkeeping, folding of the AdamW scalars, launch geometry.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+
+#include "../../include/acco.h"
+#include "kernels.hpp"
+
+#define ACCO_API extern "C" __attribute__((visibility("default")))
+
+namespace {
+
+using namespace acco;
+
+// ------------------------------------------------------------------ launch shapes
+
+struct LaunchShape {
+    std::atomic<int> threads;
+    std::atomic<int> vectors;  // U: 16-byte vectors per thread per array in flight
+    std::atomic<int> wg_per_cu;
+};
+
+enum Entry { kAccumulate = 0, kCast, kReduce, kEstimate, kCommit, kEntries };
+
+LaunchShape g_shape[kEntries] = {
+    {{256}, {4}, {0}},  // accumulate
+    {{256}, {4}, {0}},  // cast
+    {{256}, {2}, {0}},  // reduce
+    {{256}, {2}, {0}},  // estimate
+    {{256}, {2}, {0}},  // commit
+};
+
+const char* const kEntryNames[kEntries] = {"accumulate", "cast", "reduce", "estimate", "commit"};
+
+int cu_count()
+{
+    static std::atomic<int> cached[64];
+    int                     dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int c = cached[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            c <= 0)
+            c = 256;
+        cached[dev].store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
+
+struct Geometry {
+    int     threads;
+    int     vectors;
+    int64_t tiles;
+    dim3    grid;
+};
+
+Geometry geometry(Entry e, int64_t nvec)
+{
+    Geometry g;
+    g.threads = g_shape[e].threads.load(std::memory_order_relaxed);
+    g.vectors = g_shape[e].vectors.load(std::memory_order_relaxed);
+    const int     per_cu = g_shape[e].wg_per_cu.load(std::memory_order_relaxed);
+    const int64_t tile   = (int64_t)g.threads * g.vectors;
+    g.tiles              = (nvec + tile - 1) / tile;
+    const int64_t want   = g.tiles < 1 ? 1 : g.tiles;  // the scalar tail still needs workgroup 0
+    const int64_t cap    = per_cu > 0 ? (int64_t)per_cu * cu_count() : (int64_t)1 << 30;
+    g.grid               = dim3((unsigned)(want < cap ? want : cap));
+    return g;
+}
+
+template <class Op>
+int launch(Entry e, const Op& op, int64_t n, hipStream_t stream)
+{
+    const int64_t  nvec = n / 4;
+    const Geometry g    = geometry(e, nvec);
+    switch (g.vectors) {
+        case 1:
+            hipLaunchKernelGGL((stream_kernel<1, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+                               g.tiles, n);
+            break;
+        case 2:
+            hipLaunchKernelGGL((stream_kernel<2, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+                               g.tiles, n);
+            break;
+        default:
+            hipLaunchKernelGGL((stream_kernel<4, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+                               g.tiles, n);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
+}
+
+// ------------------------------------------------------------------ validation helpers
+
+inline bool aligned16(const void* p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+inline bool overlap(const void* a, int64_t a_bytes, const void* b, int64_t b_bytes)
+{
+    if (a == nullptr || b == nullptr || a_bytes <= 0 || b_bytes <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)b_bytes && b0 < a0 + (uintptr_t)a_bytes;
+}
+
+inline int check_n(int64_t n)
+{
+    return (n < 0 || n > ACCO_MAX_ELEMS) ? ACCO_ERR_SIZE : ACCO_OK;
+}
+
+inline bool finite_nonneg(double x)
+{
+    return std::isfinite(x) && x >= 0.0;
+}
+
+int check_hyper(const acco_adamw_t* hp, int64_t step, int64_t total_count)
+{
+    if (hp == nullptr) return ACCO_ERR_NULL;
+    if (!finite_nonneg(hp->lr) || !finite_nonneg(hp->eps) || !finite_nonneg(hp->weight_decay))
+        return ACCO_ERR_ARG;
+    if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0) || !(hp->beta2 >= 0.0 && hp->beta2 < 1.0))
+        return ACCO_ERR_ARG;
+    if (step < 0 || step == std::numeric_limits<int64_t>::max() || total_count < 1)
+        return ACCO_ERR_ARG;
+    return ACCO_OK;
+}
+
+// Scalars of update number t = step + 1 on a gradient sum of total_count micro-batches.
+AdamScalars fold(const acco_adamw_t& hp, int64_t step, int64_t total_count)
+{
+    const double t   = (double)(step + 1);
+    const double bc1 = 1.0 - std::pow(hp.beta1, t);
+    const double bc2 = 1.0 - std::pow(hp.beta2, t);
+    AdamScalars  s;
+    s.grad_scale = (float)(1.0 / (double)total_count);
+    s.beta1      = (float)hp.beta1;
+    s.beta2      = (float)hp.beta2;
+    s.omb1       = (float)(1.0 - hp.beta1);
+    s.omb2       = (float)(1.0 - hp.beta2);
+    s.step_size  = (float)(hp.lr / bc1);
+    s.rsqrt_bc2  = (float)(1.0 / std::sqrt(bc2));
+    s.lrwd       = (float)(hp.lr * hp.weight_decay);
+    s.eps        = (float)hp.eps;
+    return s;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ entry points
+
+ACCO_API int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, int init,
+                             int64_t* count, void* stream)
+{
+    if (acc == nullptr || grad_bf16 == nullptr) return ACCO_ERR_NULL;
+    if (int rc = check_n(n)) return rc;
+    if (!aligned16(acc) || !aligned16(grad_bf16)) return ACCO_ERR_ALIGN;
+    if (init != 0 && init != 1) return ACCO_ERR_ARG;
+    if (count != nullptr && !init &&
+        (*count < 0 || *count == std::numeric_limits<int64_t>::max()))
+        return ACCO_ERR_ARG;
+    if (overlap(acc, n * 4, grad_bf16, n * 2)) return ACCO_ERR_ALIAS;
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (init)
+            rc = launch(kAccumulate, AccumulateOp<true>{acc, grad_bf16}, n, s);
+        else
+            rc = launch(kAccumulate, AccumulateOp<false>{acc, grad_bf16}, n, s);
+    }
+    if (rc == ACCO_OK && count != nullptr) *count = init ? 1 : *count + 1;
+    return rc;
+}
+
+ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stream)
+{
+    if (out_bf16 == nullptr || src == nullptr) return ACCO_ERR_NULL;
+    if (int rc = check_n(n)) return rc;
+    if (!aligned16(out_bf16) || !aligned16(src)) return ACCO_ERR_ALIGN;
+    if (overlap(out_bf16, n * 2, src, n * 4)) return ACCO_ERR_ALIAS;
+    if (n == 0) return ACCO_OK;
+    return launch(kCast, CastOp{out_bf16, src}, n, static_cast<hipStream_t>(stream));
+}
+
+namespace {
+
+template <bool BF16>
+int launch_reduce(float* gsum, const void* const* shards, int workers, int64_t n, bool accumulate,
+                  hipStream_t stream)
+{
+    constexpr int kChunk = kReduceChunk;
+    for (int w0 = 0; w0 < workers; w0 += kChunk) {
+        const int  cnt = workers - w0 < kChunk ? workers - w0 : kChunk;
+        const bool acc = accumulate || w0 > 0;
+        ShardPtrs  ptrs;
+        std::memset(&ptrs, 0, sizeof ptrs);
+        for (int w = 0; w < cnt; ++w) ptrs.p[w] = shards[w0 + w];
+        int rc;
+        if (acc)
+            rc = launch(kReduce, ReduceOp<kChunk, BF16, true>{gsum, ptrs, cnt}, n, stream);
+        else
+            rc = launch(kReduce, ReduceOp<kChunk, BF16, false>{gsum, ptrs, cnt}, n, stream);
+        if (rc != ACCO_OK) return rc;
+    }
+    return ACCO_OK;
+}
+
+}  // namespace
+
+ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype,
+                                int64_t n, int accumulate, const int64_t* counts, int64_t* total,
+                                void* stream)
+{
+    if (gsum == nullptr || shards == nullptr) return ACCO_ERR_NULL;
+    if (int rc = check_n(n)) return rc;
+    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
+    if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
+    if (accumulate != 0 && accumulate != 1) return ACCO_ERR_ARG;
+    if ((counts == nullptr) != (total == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(gsum)) return ACCO_ERR_ALIGN;
+    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    for (int w = 0; w < workers; ++w) {
+        if (shards[w] == nullptr) return ACCO_ERR_NULL;
+        if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
+        if (overlap(gsum, n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
+    }
+    int64_t new_total = 0;
+    if (counts != nullptr) {
+        new_total = accumulate ? *total : 0;
+        if (new_total < 0) return ACCO_ERR_ARG;
+        for (int w = 0; w < workers; ++w) {
+            if (counts[w] < 0) return ACCO_ERR_ARG;
+            if (counts[w] > std::numeric_limits<int64_t>::max() - new_total) return ACCO_ERR_ARG;
+            new_total += counts[w];
+        }
+    }
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        rc            = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, shards, workers, n, accumulate, s)
+                                           : launch_reduce<false>(gsum, shards, workers, n, accumulate, s);
+    }
+    if (rc == ACCO_OK && total != nullptr) *total = new_total;
+    return rc;
+}
+
+ACCO_API int acco_estimate_step(const float* theta, const float* m, const float* v,
+                                const float* gsum, float* theta_tilde_f32,
+                                uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
+                                int64_t step, int64_t total_count, void* stream)
+{
+    if (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr) return ACCO_ERR_NULL;
+    if (theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
+    if (int rc = check_n(n)) return rc;
+    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
+        !aligned16(theta_tilde_f32) || !aligned16(theta_tilde_bf16))
+        return ACCO_ERR_ALIGN;
+    if (int rc = check_hyper(hp, step, total_count)) return rc;
+    const void* ins[4] = {theta, m, v, gsum};
+    for (const void* in : ins) {
+        if (overlap(theta_tilde_f32, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_tilde_bf16, n * 2, in, n * 4)) return ACCO_ERR_ALIAS;
+    }
+    if (overlap(theta_tilde_f32, n * 4, theta_tilde_bf16, n * 2)) return ACCO_ERR_ALIAS;
+    if (n == 0) return ACCO_OK;
+
+    const AdamScalars sc = fold(*hp, step, total_count);
+    hipStream_t       s  = static_cast<hipStream_t>(stream);
+    if (theta_tilde_f32 != nullptr && theta_tilde_bf16 != nullptr)
+        return launch(kEstimate,
+                      AdamOp<false, true, true>{theta, m, v, gsum, nullptr, nullptr, nullptr,
+                                                theta_tilde_f32, theta_tilde_bf16, sc},
+                      n, s);
+    if (theta_tilde_f32 != nullptr)
+        return launch(kEstimate,
+                      AdamOp<false, true, false>{theta, m, v, gsum, nullptr, nullptr, nullptr,
+                                                 theta_tilde_f32, nullptr, sc},
+                      n, s);
+    return launch(kEstimate,
+                  AdamOp<false, false, true>{theta, m, v, gsum, nullptr, nullptr, nullptr, nullptr,
+                                             theta_tilde_bf16, sc},
+                  n, s);
+}
+
+ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsum,
+                              uint16_t* theta_bf16, int64_t n, const acco_adamw_t* hp,
+                              int64_t* step, int64_t total_count, void* stream)
+{
+    if (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr || step == nullptr)
+        return ACCO_ERR_NULL;
+    if (int rc = check_n(n)) return rc;
+    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
+        !aligned16(theta_bf16))
+        return ACCO_ERR_ALIGN;
+    if (int rc = check_hyper(hp, *step, total_count)) return rc;
+    const void* f32s[4] = {theta, m, v, gsum};
+    for (int a = 0; a < 4; ++a) {
+        for (int b = a + 1; b < 4; ++b)
+            if (overlap(f32s[a], n * 4, f32s[b], n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_bf16, n * 2, f32s[a], n * 4)) return ACCO_ERR_ALIAS;
+    }
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        const AdamScalars sc = fold(*hp, *step, total_count);
+        hipStream_t       s  = static_cast<hipStream_t>(stream);
+        if (theta_bf16 != nullptr)
+            rc = launch(kCommit,
+                        AdamOp<true, false, true>{theta, m, v, gsum, theta, m, v, nullptr,
+                                                  theta_bf16, sc},
+                        n, s);
+        else
+            rc = launch(kCommit,
+                        AdamOp<true, false, false>{theta, m, v, gsum, theta, m, v, nullptr, nullptr,
+                                                   sc},
+                        n, s);
+    }
+    if (rc == ACCO_OK) *step += 1;
+    return rc;
+}
+
+ACCO_API const char* acco_status_string(int status)
+{
+    switch (status) {
+        case ACCO_OK: return "ACCO_OK";
+        case ACCO_ERR_NULL: return "ACCO_ERR_NULL: a required pointer is NULL";
+        case ACCO_ERR_SIZE: return "ACCO_ERR_SIZE: element or worker count out of range";
+        case ACCO_ERR_ALIGN: return "ACCO_ERR_ALIGN: device pointer not 16-byte aligned";
+        case ACCO_ERR_ARG: return "ACCO_ERR_ARG: invalid hyper-parameter, count, step, dtype or flag";
+        case ACCO_ERR_ALIAS: return "ACCO_ERR_ALIAS: output overlaps an input";
+        case ACCO_ERR_DEVICE: return "ACCO_ERR_DEVICE: HIP runtime error at launch";
+        default: return "ACCO: unknown status";
+    }
+}
+
+ACCO_API int acco_version(void)
+{
+    return 100;  // 0.1.0
+}
+
+ACCO_API int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,
+                                   int workgroups_per_cu)
+{
+    if (entry == nullptr) return ACCO_ERR_NULL;
+    if (threads < 64 || threads > kMaxThreads || threads % 64 != 0) return ACCO_ERR_ARG;
+    if (vectors_in_flight != 1 && vectors_in_flight != 2 && vectors_in_flight != 4)
+        return ACCO_ERR_ARG;
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 64) return ACCO_ERR_ARG;
+    for (int e = 0; e < kEntries; ++e) {
+        if (std::strcmp(entry, kEntryNames[e]) == 0) {
+            g_shape[e].threads.store(threads, std::memory_order_relaxed);
+            g_shape[e].vectors.store(vectors_in_flight, std::memory_order_relaxed);
+            g_shape[e].wg_per_cu.store(workgroups_per_cu, std::memory_order_relaxed);
+            return ACCO_OK;
+        }
+    }
+    return ACCO_ERR_ARG;
+}

@@ -1,0 +1,306 @@
+// Device code of the ACCO shard path for gfx950: five streaming kernels, all
+// elementwise and HBM-bound, built on one tile loop.
+//
+// Layout: every array is flat.  A "vector" is 4 consecutive elements: 16 bytes of
+// fp32 (one dwordx4 per lane) or 8 bytes of bf16 (one dwordx2 per lane), so each
+// wavefront instruction touches 1024 (512) contiguous bytes.  A workgroup of T
+// threads owns tiles of T*U vectors; each thread issues the loads of its U vectors
+// of every input array before the first use, so U*(arrays) 16-byte requests per
+// lane are in flight while HBM latency is paid.  Tiles are taken grid-stride.
+// The last n % 4 elements are done one by one by workgroup 0.
+//
+// Arithmetic: fp32, one IEEE operation per written operation (compiled with
+// -ffp-contract=off; the fused multiply-adds below are explicit), correctly
+// rounded division and square root, denormals kept.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace acco {
+
+typedef float    f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+constexpr int kReduceChunk = 8;   // worker shards summed per launch
+constexpr int kMaxThreads = 512;  // per workgroup: leaves 256 VGPRs per lane for loads in flight
+
+// ------------------------------------------------------------------ bf16 <-> fp32
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed)
+{
+    return __uint_as_float(packed << 16);
+}
+
+__device__ __forceinline__ float bf16_hi(uint32_t packed)
+{
+    return __uint_as_float(packed & 0xFFFF0000u);
+}
+
+// round to nearest even on the upper half; NaN keeps its sign and gets the quiet bit
+__device__ __forceinline__ uint32_t to_bf16_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
+    r          = ((u & 0x7FFFFFFFu) > 0x7F800000u) ? (u | 0x00400000u) : r;
+    return r >> 16;
+}
+
+__device__ __forceinline__ u2 pack_bf16x4(f4 x)
+{
+    u2 p;
+    p.x = to_bf16_bits(x.x) | (to_bf16_bits(x.y) << 16);
+    p.y = to_bf16_bits(x.z) | (to_bf16_bits(x.w) << 16);
+    return p;
+}
+
+__device__ __forceinline__ f4 unpack_bf16x4(u2 p)
+{
+    f4 x;
+    x.x = bf16_lo(p.x);
+    x.y = bf16_hi(p.x);
+    x.z = bf16_lo(p.y);
+    x.w = bf16_hi(p.y);
+    return x;
+}
+
+// ------------------------------------------------------------------ AdamW element update
+
+// Host-folded scalars of one update (computed in double, rounded once).
+struct AdamScalars {
+    float grad_scale;  // 1 / total micro-batch count
+    float beta1, beta2;
+    float omb1, omb2;  // 1 - beta
+    float step_size;   // lr / (1 - beta1^t)
+    float rsqrt_bc2;   // 1 / sqrt(1 - beta2^t)
+    float lrwd;        // lr * weight_decay
+    float eps;
+};
+
+// AdamW with decoupled decay on theta(t), bias-corrected moments, eps added to the
+// bias-corrected root.  The decay is theta - (lr wd) theta in one fused operation
+// (a pre-rounded factor 1 - lr wd would bias theta on every step).
+__device__ __forceinline__ void adamw_elem(float theta, float m, float v, float gsum,
+                                           const AdamScalars& s, float& theta_o, float& m_o,
+                                           float& v_o)
+{
+    const float g   = gsum * s.grad_scale;
+    const float m1  = __builtin_fmaf(s.beta1, m, s.omb1 * g);
+    const float v1  = __builtin_fmaf(s.beta2, v, s.omb2 * (g * g));
+    const float den = __builtin_fmaf(__fsqrt_rn(v1), s.rsqrt_bc2, s.eps);
+    const float t0  = __builtin_fmaf(-s.lrwd, theta, theta);
+    theta_o         = __builtin_fmaf(-s.step_size, __fdiv_rn(m1, den), t0);
+    m_o             = m1;
+    v_o             = v1;
+}
+
+// ------------------------------------------------------------------ tile loop
+
+template <class T>
+__device__ __forceinline__ T ld(const T* p)
+{
+    return *p;
+}
+
+template <class T>
+__device__ __forceinline__ void st(T* p, T x)
+{
+    *p = x;
+}
+
+// Op supplies: struct In; In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
+//              void scalar(int64_t elem) const.
+template <int U, class Op>
+__global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Op op, const int64_t nvec,
+                                                             const int64_t ntiles, const int64_t n)
+{
+    const int64_t tile = (int64_t)blockDim.x * U;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t   base = t * tile + threadIdx.x;
+        typename Op::In in[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + (int64_t)u * blockDim.x;
+            if (i < nvec) in[u] = op.load(i);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + (int64_t)u * blockDim.x;
+            if (i < nvec) op.apply(i, in[u]);
+        }
+    }
+    if (blockIdx.x == 0) {
+        const int64_t j = nvec * 4 + threadIdx.x;
+        if (j < n) op.scalar(j);
+    }
+}
+
+// ------------------------------------------------------------------ accumulate
+
+template <bool INIT>
+struct AccumulateOp {
+    float*          acc;
+    const uint16_t* grad;
+    struct In {
+        f4 a;
+        u2 g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.g = ld(reinterpret_cast<const u2*>(grad) + i);
+        if (!INIT) in.a = ld(reinterpret_cast<const f4*>(acc) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        const f4 g = unpack_bf16x4(in.g);
+        st(reinterpret_cast<f4*>(acc) + i, INIT ? g : in.a + g);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        const float g = __uint_as_float((uint32_t)grad[j] << 16);
+        acc[j]        = INIT ? g : acc[j] + g;
+    }
+};
+
+// ------------------------------------------------------------------ cast
+
+struct CastOp {
+    uint16_t*    out;
+    const float* src;
+    struct In {
+        f4 x;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.x = ld(reinterpret_cast<const f4*>(src) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        st(reinterpret_cast<u2*>(out) + i, pack_bf16x4(in.x));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        out[j] = (uint16_t)to_bf16_bits(src[j]);
+    }
+};
+
+// ------------------------------------------------------------------ reduce
+
+struct ShardPtrs {
+    const void* p[kReduceChunk];
+};
+
+// Sum of up to WMAX worker shards per launch, ascending worker order.  ACC: start
+// from the value already in gsum, else from shard 0 as it is.
+template <int WMAX, bool BF16, bool ACC>
+struct ReduceOp {
+    float*    gsum;
+    ShardPtrs shards;
+    int       workers;  // 1 .. WMAX
+    struct In {
+        f4 s;
+        f4 x[BF16 ? 1 : WMAX];
+        u2 b[BF16 ? WMAX : 1];
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        if (ACC) in.s = ld(reinterpret_cast<const f4*>(gsum) + i);
+#pragma unroll
+        for (int w = 0; w < WMAX; ++w) {
+            if (w < workers) {
+                if (BF16)
+                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + i);
+                else
+                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + i);
+            }
+        }
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        f4 s = in.s;
+#pragma unroll
+        for (int w = 0; w < WMAX; ++w) {
+            if (w < workers) {
+                const f4 x = BF16 ? unpack_bf16x4(in.b[w]) : in.x[w];
+                s          = (!ACC && w == 0) ? x : s + x;
+            }
+        }
+        st(reinterpret_cast<f4*>(gsum) + i, s);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        float s = ACC ? gsum[j] : 0.0f;
+        for (int w = 0; w < workers; ++w) {
+            const float x =
+                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
+                     : static_cast<const float*>(shards.p[w])[j];
+            s = (!ACC && w == 0) ? x : s + x;
+        }
+        gsum[j] = s;
+    }
+};
+
+// ------------------------------------------------------------------ estimate / commit
+
+// COMMIT: write theta, m, v in place.  OUT_F32 / OUT_BF16: extra outputs of the new theta.
+template <bool COMMIT, bool OUT_F32, bool OUT_BF16>
+struct AdamOp {
+    const float* theta;
+    const float* m;
+    const float* v;
+    const float* gsum;
+    float*       theta_w;  // COMMIT: == theta
+    float*       m_w;
+    float*       v_w;
+    float*       out_f32;
+    uint16_t*    out_bf16;
+    AdamScalars  s;
+    struct In {
+        f4 t, m, v, g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.t = ld(reinterpret_cast<const f4*>(theta) + i);
+        in.m = ld(reinterpret_cast<const f4*>(m) + i);
+        in.v = ld(reinterpret_cast<const f4*>(v) + i);
+        in.g = ld(reinterpret_cast<const f4*>(gsum) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        float to[4], mo[4], vo[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) adamw_elem(in.t[k], in.m[k], in.v[k], in.g[k], s, to[k], mo[k], vo[k]);
+        const f4 t  = {to[0], to[1], to[2], to[3]};
+        const f4 mm = {mo[0], mo[1], mo[2], mo[3]};
+        const f4 vv = {vo[0], vo[1], vo[2], vo[3]};
+        if (COMMIT) {
+            st(reinterpret_cast<f4*>(theta_w) + i, t);
+            st(reinterpret_cast<f4*>(m_w) + i, mm);
+            st(reinterpret_cast<f4*>(v_w) + i, vv);
+        }
+        if (OUT_F32) st(reinterpret_cast<f4*>(out_f32) + i, t);
+        if (OUT_BF16) st(reinterpret_cast<u2*>(out_bf16) + i, pack_bf16x4(t));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        float t, mm, vv;
+        adamw_elem(theta[j], m[j], v[j], gsum[j], s, t, mm, vv);
+        if (COMMIT) {
+            theta_w[j] = t;
+            m_w[j]     = mm;
+            v_w[j]     = vv;
+        }
+        if (OUT_F32) out_f32[j] = t;
+        if (OUT_BF16) out_bf16[j] = (uint16_t)to_bf16_bits(t);
+    }
+};
+
+}  // namespace acco

@@ -1,0 +1,197 @@
+"""The C-ABI library on a machine without a GPU: it loads, exports what the header declares,
+validates arguments before any launch, and keeps the host counters exactly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2406_02613_amd import binding as B
+from paper_2406_02613_amd import layout
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "acco.h")
+
+A, Bp, C, D, E, F = (0x10000 * k for k in range(1, 7))   # fake, aligned "device" addresses
+NONE = None
+
+
+def vp(x):
+    return ctypes.c_void_p(x)
+
+
+def test_every_symbol_declared_in_the_header_is_exported():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(acco_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert B.version() >= 100
+    assert "ALIGN" in B.status_string(B.ACCO_ERR_ALIGN)
+    assert "unknown" in B.status_string(-99)
+
+
+def test_struct_layout_matches_the_header():
+    assert ctypes.sizeof(B.AdamW) == 5 * 8
+    assert [f[0] for f in B.AdamW._fields_] == ["lr", "beta1", "beta2", "eps", "weight_decay"]
+
+
+def test_accumulate_validation_and_counter():
+    L = B.lib()
+    c = ctypes.c_int64(0)
+    assert L.acco_accumulate(NONE, vp(Bp), 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
+    assert L.acco_accumulate(vp(A), NONE, 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
+    assert L.acco_accumulate(vp(A), vp(Bp), -1, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_SIZE
+    assert L.acco_accumulate(vp(A), vp(Bp), (1 << 40) + 1, 0, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert L.acco_accumulate(vp(A + 4), vp(Bp), 0, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert L.acco_accumulate(vp(A), vp(Bp + 2), 0, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert L.acco_accumulate(vp(A), vp(Bp), 0, 2, NONE, NONE) == B.ACCO_ERR_ARG
+    assert L.acco_accumulate(vp(A), vp(A + 16), 64, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert c.value == 0                      # errors leave the counter alone
+    # n == 0: no device work, bookkeeping still happens
+    for want in (1, 2, 3):
+        assert L.acco_accumulate(vp(A), vp(Bp), 0, int(want == 1), ctypes.byref(c), NONE) == 0
+        assert c.value == want
+    assert L.acco_accumulate(vp(A), vp(Bp), 0, 1, ctypes.byref(c), NONE) == 0 and c.value == 1
+    c.value = -3
+    assert L.acco_accumulate(vp(A), vp(Bp), 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_ARG
+    c.value = 2 ** 63 - 1
+    assert L.acco_accumulate(vp(A), vp(Bp), 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_ARG
+
+
+def test_cast_validation():
+    L = B.lib()
+    assert L.acco_cast_params(NONE, vp(A), 0, NONE) == B.ACCO_ERR_NULL
+    assert L.acco_cast_params(vp(A), vp(Bp), -5, NONE) == B.ACCO_ERR_SIZE
+    assert L.acco_cast_params(vp(A + 8), vp(Bp), 0, NONE) == B.ACCO_ERR_ALIGN
+    assert L.acco_cast_params(vp(A), vp(A), 16, NONE) == B.ACCO_ERR_ALIAS
+    assert L.acco_cast_params(vp(A), vp(Bp), 0, NONE) == 0
+
+
+def _shards(*addrs):
+    return (ctypes.c_void_p * len(addrs))(*addrs)
+
+
+def test_reduce_validation_and_count_totals():
+    L = B.lib()
+    s2 = _shards(Bp, C)
+    cnt = (ctypes.c_int64 * 2)(3, 4)
+    tot = ctypes.c_int64(100)
+    r = L.acco_reduce_shards
+    assert r(NONE, s2, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), NONE, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), s2, 0, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_SIZE
+    assert r(vp(A), s2, 65, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_SIZE
+    assert r(vp(A), s2, 2, 7, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 3, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 0, cnt, NONE, NONE) == B.ACCO_ERR_NULL      # counts w/o total
+    assert r(vp(A), s2, 2, 0, 0, 0, NONE, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), _shards(Bp, 0), 2, 0, 0, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), _shards(Bp, C + 2), 2, 0, 0, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert r(vp(A), _shards(Bp, A), 2, 0, 8, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    neg = (ctypes.c_int64 * 2)(3, -1)
+    assert r(vp(A), s2, 2, 0, 0, 0, neg, ctypes.byref(tot), NONE) == B.ACCO_ERR_ARG
+    big = (ctypes.c_int64 * 2)(2 ** 62, 2 ** 62)
+    assert r(vp(A), s2, 2, 0, 0, 0, big, ctypes.byref(tot), NONE) == B.ACCO_ERR_ARG
+    assert tot.value == 100
+    # stage 1: total = sum(counts); stage 2: total += sum(counts)
+    assert r(vp(A), s2, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == 0 and tot.value == 7
+    cnt2 = (ctypes.c_int64 * 2)(5, 6)
+    assert r(vp(A), s2, 2, 1, 0, 1, cnt2, ctypes.byref(tot), NONE) == 0 and tot.value == 18
+    # 64 workers are accepted
+    many = _shards(*[Bp + 0x1000 * k for k in range(64)])
+    assert r(vp(A), many, 64, 0, 0, 0, NONE, NONE, NONE) == 0
+
+
+GOOD = B.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+
+
+@pytest.mark.parametrize("field,value", [("lr", -1.0), ("lr", float("nan")), ("lr", float("inf")),
+                                         ("beta1", 1.0), ("beta1", -0.1), ("beta2", 1.5),
+                                         ("beta2", float("nan")), ("eps", -1e-8),
+                                         ("eps", float("inf")), ("weight_decay", -0.1),
+                                         ("weight_decay", float("nan"))])
+def test_bad_hyper_parameters_are_rejected(field, value):
+    L = B.lib()
+    hp = B.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+    setattr(hp, field, value)
+    step = ctypes.c_int64(0)
+    rc = L.acco_estimate_step(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, 0, ctypes.byref(hp), 0, 1,
+                              NONE)
+    assert rc == B.ACCO_ERR_ARG
+    rc = L.acco_commit_step(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, ctypes.byref(hp),
+                            ctypes.byref(step), 1, NONE)
+    assert rc == B.ACCO_ERR_ARG and step.value == 0
+
+
+def test_estimate_validation():
+    L = B.lib()
+    e = L.acco_estimate_step
+    hp = ctypes.byref(GOOD)
+    assert e(NONE, vp(Bp), vp(C), vp(D), vp(E), NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), NONE, NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, 0, NONE, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, -1, hp, 0, 1, NONE) == B.ACCO_ERR_SIZE
+    assert e(vp(A), vp(Bp + 4), vp(C), vp(D), vp(E), NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_ALIGN
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), vp(F + 2), 0, hp, 0, 1, NONE) == B.ACCO_ERR_ALIGN
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, 0, hp, -1, 1, NONE) == B.ACCO_ERR_ARG
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, 0, hp, 0, 0, NONE) == B.ACCO_ERR_ARG
+    # the speculative output may not land on theta, m, v or gsum
+    for alias in (A, Bp, C, D):
+        assert e(vp(A), vp(Bp), vp(C), vp(D), vp(alias), NONE, 8, hp, 0, 1, NONE) == B.ACCO_ERR_ALIAS
+        assert e(vp(A), vp(Bp), vp(C), vp(D), NONE, vp(alias), 8, hp, 0, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), vp(E), 8, hp, 0, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), vp(F), 0, hp, 5, 3, NONE) == 0
+
+
+def test_commit_validation_and_step_counter():
+    L = B.lib()
+    c = L.acco_commit_step
+    hp = ctypes.byref(GOOD)
+    step = ctypes.c_int64(0)
+    st = ctypes.byref(step)
+    assert c(vp(A), vp(Bp), vp(C), NONE, NONE, 0, hp, st, 1, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, hp, NONE, 1, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, -2, hp, st, 1, NONE) == B.ACCO_ERR_SIZE
+    assert c(vp(A + 12), vp(Bp), vp(C), vp(D), NONE, 0, hp, st, 1, NONE) == B.ACCO_ERR_ALIGN
+    assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, hp, st, 0, NONE) == B.ACCO_ERR_ARG
+    assert c(vp(A), vp(A), vp(C), vp(D), NONE, 4, hp, st, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert c(vp(A), vp(Bp), vp(C), vp(C + 16), NONE, 64, hp, st, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert c(vp(A), vp(Bp), vp(C), vp(D), vp(A), 4, hp, st, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert step.value == 0
+    for want in (1, 2, 3):
+        assert c(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, hp, st, 4, NONE) == 0
+        assert step.value == want
+    step.value = -1
+    assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, hp, st, 1, NONE) == B.ACCO_ERR_ARG
+
+
+def test_launch_shape_validation():
+    B.set_launch_shape("commit", 256, 2, 0)
+    for bad in (("commit", 100, 2, 0), ("commit", 1024, 2, 0), ("commit", 256, 3, 0),
+                ("commit", 256, 2, -1), ("nope", 256, 2, 0)):
+        with pytest.raises(B.AccoError):
+            B.set_launch_shape(*bad)
+
+
+def test_binding_rejects_host_tensors_before_touching_the_library():
+    import torch
+    t = torch.zeros(8)
+    with pytest.raises(ValueError):
+        B.acco_cast_params(torch.zeros(8, dtype=torch.bfloat16), t)
+
+
+def test_buffer_inventory_reproduces_the_papers_memory_table():
+    path = os.path.join(os.path.dirname(__file__), "golden", "memory_table.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    names = {"ACCO": "acco", "ZeRO-1": "zero1", "DDP": "ddp"}
+    assert len(rows) == 3
+    for method, _formula, printed in rows:
+        gb = layout.replica_bytes_per_param(names[method], 64) * 7.5e9 / 1e9
+        assert round(gb) == int(printed)
+    assert layout.STATE_F32 == 12
+    assert layout.BYTES_PER_ELEM["commit"] == 28 and layout.BYTES_PER_ELEM["commit_bf16"] == 30
+    assert layout.reduce_bytes_per_elem(8, True, False) == 20
+    assert layout.reduce_bytes_per_elem(8, True, True) == 24

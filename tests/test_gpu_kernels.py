@@ -1,0 +1,291 @@
+"""Element-by-element parity of each C-ABI entry point with the CPU oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from parity import (assert_bf16_close, assert_f32_close, bf16_tensor, bit_mismatches, bits_of)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SIZES = [0, 1, 3, 4, 7, 8, 9, 63, 64, 65, 1000, 4096 + 5, (1 << 20), (1 << 20) + 37]
+SHAPES = [(256, 2, 0), (64, 1, 0), (512, 4, 0), (256, 4, 2), (128, 2, 1)]
+
+
+@pytest.fixture(scope="module")
+def acco():
+    import paper_2406_02613_amd as A
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    A.binding.lib()          # fails loudly if libacco.so is missing
+    return A
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(a.copy()).cuda()
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ generator
+
+
+def test_device_generator_matches_host_generator_bit_for_bit():
+    for name in ("tiny", "gpt2s", "1b", "7b_hetero"):
+        w = synth.WORKLOADS[name]
+        for j0, n in ((0, 70_001), (w.n - 50_003, 50_003)):
+            log("generator", name, j0, n)
+            sp = w.grad_spec(2, 1, w.workers - 1, 1)
+            g = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            synth.device_grad_bf16(g, sp, j0)
+            assert np.array_equal(bits_of(g), synth.host_grad_bf16(sp, j0, n))
+            t = torch.empty(n, dtype=torch.float32, device="cuda")
+            w.device_theta(t, j0)
+            assert np.array_equal(t.cpu().numpy().view(np.uint32), w.host_theta(j0, n).view(np.uint32))
+    sp = synth.WORKLOADS["1b"].warm_spec(77)
+    g = torch.empty(4099, dtype=torch.bfloat16, device="cuda")
+    synth.device_grad_bf16(g, sp, 123_456_789)
+    assert np.array_equal(bits_of(g), synth.host_grad_bf16(sp, 123_456_789, 4099))
+
+
+# ------------------------------------------------------------------ accumulate / cast / reduce
+
+
+def _rand_bf16(rng, n, scale=1e-3):
+    x = (rng.standard_normal(n) * scale).astype(np.float32)
+    return oracle.cast(x)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_accumulate_is_bit_exact(acco, shape):
+    acco.set_launch_shape("accumulate", *shape)
+    rng = np.random.default_rng(1)
+    for n in SIZES:
+        log("accumulate", shape, n)
+        acc_h = np.full(n, 7.0, np.float32)
+        acc_d = dev(acc_h)
+        cnt = acco.Counter(0)
+        for k in range(3):
+            g = _rand_bf16(rng, n)
+            if n:
+                g[0] = 0x8000                      # -0 must survive an init
+            oracle.accumulate(acc_h, g, init=(k == 0))
+            acco.acco_accumulate(acc_d, bf16_tensor(g), k == 0, cnt)
+            assert cnt.value == k + 1
+        assert bit_mismatches(acc_d.cpu().numpy(), acc_h) == 0
+    acco.set_launch_shape("accumulate", 256, 4, 0)
+
+
+def test_cast_all_fp32_classes_bit_exact(acco):
+    # every bf16 pattern combined with low halves below / at / above the rounding tie, which
+    # covers zeros, denormals, infinities, NaNs and the overflow to infinity
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    src = (hi[:, None] | lows[None, :]).ravel().view(np.float32)
+    want = oracle.cast(src)
+    out = torch.empty(src.size, dtype=torch.bfloat16, device="cuda")
+    acco.acco_cast_params(out, dev(src))
+    got = bits_of(out)
+    nan = np.isnan(src)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x7F) != 0)
+    assert np.array_equal(got[nan], want[nan])       # same quieting as the oracle
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_cast_sizes(acco, shape):
+    acco.set_launch_shape("cast", *shape)
+    rng = np.random.default_rng(2)
+    for n in SIZES:
+        log("cast", shape, n)
+        x = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 30, n))).astype(np.float32)
+        out = torch.full((n,), 1.0, dtype=torch.bfloat16, device="cuda")
+        acco.acco_cast_params(out, dev(x))
+        assert np.array_equal(bits_of(out), oracle.cast(x))
+    acco.set_launch_shape("cast", 256, 4, 0)
+
+
+@pytest.mark.parametrize("shape", SHAPES[:3])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("W", [1, 2, 8, 9, 17])
+def test_reduce_is_bit_exact_in_worker_order(acco, shape, dtype, W):
+    acco.set_launch_shape("reduce", *shape)
+    rng = np.random.default_rng(3 + W)
+    for n in (0, 1, 5, 64, 1000, 4096 + 7, 300_003):
+        log("reduce", shape, dtype, W, n)
+        if dtype == "bf16":
+            sh_h = [_rand_bf16(rng, n, 1.0) for _ in range(W)]
+            sh_d = [bf16_tensor(s) for s in sh_h]
+        else:
+            sh_h = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+            sh_d = [dev(s) for s in sh_h]
+        if n:
+            # order-sensitive lanes: 2^24 + 1 + 1 ... only the left-to-right sum gives 2^24
+            big = np.float32(2.0 ** 24)
+            for k in range(W):
+                val = big if k == 0 else np.float32(1.0)
+                if dtype == "bf16":
+                    sh_h[k][0] = oracle.cast(np.array([val], np.float32))[0]
+                else:
+                    sh_h[k][0] = val
+            sh_d = [bf16_tensor(s) if dtype == "bf16" else dev(s) for s in sh_h]
+        g_h = np.full(n, 3.0, np.float32)
+        g_d = dev(g_h)
+        tot = acco.Counter(99)
+        counts = list(range(1, W + 1))
+        oracle.reduce(g_h, sh_h, accumulate_=False)
+        acco.acco_reduce_shards(g_d, sh_d, False, counts, tot)
+        assert tot.value == sum(counts)
+        assert bit_mismatches(g_d.cpu().numpy(), g_h) == 0
+        oracle.reduce(g_h, sh_h[::-1], accumulate_=True)
+        acco.acco_reduce_shards(g_d, sh_d[::-1], True, counts, tot)
+        assert tot.value == 2 * sum(counts)
+        assert bit_mismatches(g_d.cpu().numpy(), g_h) == 0
+    acco.set_launch_shape("reduce", 256, 2, 0)
+
+
+# ------------------------------------------------------------------ estimate / commit
+
+
+def _state(rng, n, kind):
+    theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    if kind == "cold":
+        m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    else:
+        m = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+        v = (rng.random(n) * 1e-8).astype(np.float32)
+    gsum = (rng.standard_normal(n) * 4e-4).astype(np.float32)
+    if n > 16:
+        gsum[::7] = 0.0                          # exact zeros: the pure-decay path
+        gsum[3] = 1e-30                          # g^2 underflows to a denormal / zero
+        v[5] = 1e-42                             # denormal second moment
+        theta[9] = 0.0
+        theta[11] = -0.0
+    return theta, m, v, gsum
+
+
+HYPERS = [dict(lr=6e-4, b1=0.9, b2=0.95, eps=1e-8, wd=0.1),
+          dict(lr=2e-5, b1=0.9, b2=0.95, eps=1e-8, wd=0.0),
+          dict(lr=0.0, b1=0.9, b2=0.999, eps=1e-6, wd=0.3),
+          dict(lr=1e-2, b1=0.0, b2=0.5, eps=1e-3, wd=0.01)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_commit_matches_both_oracle_forms(acco, shape):
+    acco.set_launch_shape("commit", *shape)
+    rng = np.random.default_rng(4)
+    exact = True
+    for n in SIZES:
+        for hi, h in enumerate(HYPERS):
+            for kind, step, count in (("cold", 0, 1), ("warm", 6, 32), ("warm", 1000, 37)):
+                if n > 100_000 and (hi > 1 or step == 6):
+                    continue
+                log("commit", shape, n, hi, kind, step, count)
+                theta, m, v, gsum = _state(rng, n, kind)
+                ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+                ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+                td, md, vd, gd = dev(theta), dev(m), dev(v), dev(gsum)
+                out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+                st = acco.Counter(step)
+                acco.acco_commit_step(td, md, vd, gd, ghp, st, count, theta_bf16=out)
+                assert st.value == step + 1
+                assert bit_mismatches(gd.cpu().numpy(), gsum) == 0       # input untouched
+                got = [x.cpu().numpy() for x in (td, md, vd)]
+                got_b = bits_of(out)
+                for prec in ("f64", "f32"):
+                    t2, m2, v2 = theta.copy(), m.copy(), v.copy()
+                    want_b = oracle.commit(t2, m2, v2, gsum, ohp, step + 1, count, precision=prec)
+                    assert_f32_close(got[0], t2, f"theta vs {prec}")
+                    assert_f32_close(got[1], m2, f"m vs {prec}")
+                    assert_f32_close(got[2], v2, f"v vs {prec}", abs_=1e-30)
+                    assert_bf16_close(got_b, want_b, f"bf16 theta vs {prec}")
+                    if prec == "f32":
+                        exact &= (bit_mismatches(got[0], t2) + bit_mismatches(got[1], m2)
+                                  + bit_mismatches(got[2], v2)) == 0
+                        exact &= np.array_equal(got_b, want_b)
+                # without the fused output the fp32 results are the same bits
+                td2, md2, vd2 = dev(theta), dev(m), dev(v)
+                acco.acco_commit_step(td2, md2, vd2, gd, ghp, acco.Counter(step), count)
+                assert bit_mismatches(td2.cpu().numpy(), got[0]) == 0
+                assert bit_mismatches(md2.cpu().numpy(), got[1]) == 0
+                assert bit_mismatches(vd2.cpu().numpy(), got[2]) == 0
+    log("commit bit-exact with the binary32 oracle form:", exact)
+    # same operations, same order, each correctly rounded: the binary32 form is reproduced
+    assert exact
+    acco.set_launch_shape("commit", 256, 2, 0)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_estimate_reads_only_and_matches_oracle(acco, shape):
+    acco.set_launch_shape("estimate", *shape)
+    rng = np.random.default_rng(5)
+    for n in SIZES:
+        for h in HYPERS[:2]:
+            log("estimate", shape, n, h["lr"])
+            theta, m, v, gsum = _state(rng, n, "warm")
+            ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+            ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+            td, md, vd, gd = dev(theta), dev(m), dev(v), dev(gsum)
+            o32 = torch.empty(n, dtype=torch.float32, device="cuda")
+            o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            acco.acco_estimate_step(td, md, vd, gd, ghp, 41, 12, theta_tilde_f32=o32,
+                                    theta_tilde_bf16=o16)
+            for d, h_ in ((td, theta), (md, m), (vd, v), (gd, gsum)):
+                assert bit_mismatches(d.cpu().numpy(), h_) == 0
+            for prec in ("f64", "f32"):
+                w32, w16 = oracle.estimate(theta, m, v, gsum, ohp, 42, 12, precision=prec)
+                assert_f32_close(o32.cpu().numpy(), w32, f"theta~ vs {prec}")
+                assert_bf16_close(bits_of(o16), w16, f"bf16 theta~ vs {prec}")
+            assert bit_mismatches(o32.cpu().numpy(), w32) == 0
+            assert np.array_equal(bits_of(o16), w16)
+            # single outputs give the same values
+            a32 = torch.empty_like(o32)
+            a16 = torch.empty_like(o16)
+            acco.acco_estimate_step(td, md, vd, gd, ghp, 41, 12, theta_tilde_f32=a32)
+            acco.acco_estimate_step(td, md, vd, gd, ghp, 41, 12, theta_tilde_bf16=a16)
+            assert torch.equal(a32.view(torch.int32), o32.view(torch.int32))
+            assert torch.equal(a16.view(torch.int16), o16.view(torch.int16))
+            # and the estimate is what a commit from the same state would write
+            c16 = torch.empty_like(o16)
+            acco.acco_commit_step(td, md, vd, gd, ghp, acco.Counter(41), 12, theta_bf16=c16)
+            assert torch.equal(td.view(torch.int32), o32.view(torch.int32))
+            assert torch.equal(c16.view(torch.int16), o16.view(torch.int16))
+    acco.set_launch_shape("estimate", 256, 2, 0)
+
+
+def test_non_finite_inputs_propagate_like_the_oracle(acco):
+    n = 64
+    theta = np.linspace(-1, 1, n).astype(np.float32)
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    gsum = np.ones(n, np.float32)
+    gsum[1], gsum[2], gsum[3] = np.inf, -np.inf, np.nan
+    theta[4] = np.inf
+    ohp = oracle.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+    ghp = acco.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+    td, md, vd = dev(theta), dev(m), dev(v)
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    acco.acco_commit_step(td, md, vd, dev(gsum), ghp, acco.Counter(0), 1, theta_bf16=out)
+    want_b = oracle.commit(theta, m, v, gsum, ohp, 1, 1, precision="f32")
+    for got, want in ((td, theta), (md, m), (vd, v)):
+        g = got.cpu().numpy()
+        assert np.array_equal(np.isnan(g), np.isnan(want))
+        assert np.array_equal(g[~np.isnan(want)], want[~np.isnan(want)])
+    assert_bf16_close(bits_of(out), want_b, "bf16")
+
+
+def test_errors_raise_and_leave_buffers_alone(acco):
+    a = torch.ones(64, dtype=torch.float32, device="cuda")
+    g = torch.ones(64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(acco.AccoError):
+        acco.acco_accumulate(a[1:33], g[:32], False)            # misaligned view
+    with pytest.raises(acco.AccoError):
+        acco.acco_commit_step(a, a, a, a, acco.make_hyper(1e-3, .9, .95, 1e-8, 0),
+                              acco.Counter(0), 1)                 # aliased state
+    with pytest.raises(ValueError):
+        acco.acco_accumulate(a, g[:32], False)                  # length mismatch
+    torch.cuda.synchronize()
+    assert torch.all(a == 1.0)

@@ -1,0 +1,137 @@
+"""Whole ACCO rounds on the GPU against the oracle: the five workloads (needs an MI355X).
+
+The tiny workload is compared over the whole shard.  The larger ones run at full size on the
+GPU, in the launch configuration the bench uses, and are compared element by element on
+sampled index ranges (head, ragged tail, periodic interior blocks): every operation of the
+path is elementwise and the inputs are index-addressable, so the oracle computes exactly those
+elements.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from parity import (OracleSlices, assert_bf16_close, assert_f32_close, bit_mismatches, bits_of,
+                    gather, gpu_run_stage, oracle_warm_state)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+def gpu_hyper(A, w):
+    h = w.hyper
+    return A.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay)
+
+
+def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None):
+    import paper_2406_02613_amd as A
+    slices = w.sample_slices()
+    rounds = w.rounds if rounds is None else rounds
+    log(f"workload {w.name}: n={w.n} W={w.workers} rounds={rounds} slices={len(slices)} "
+        f"({sum(b - a for a, b in slices)} elements checked)")
+    owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
+                         fused_bf16_out=fused)
+    if warm is None:
+        w.device_theta(owner.theta)
+    else:
+        owner.theta.copy_(torch.from_numpy(warm[0]))
+        owner.m.copy_(torch.from_numpy(warm[1]))
+        owner.v.copy_(torch.from_numpy(warm[2]))
+        owner.step.value = w.warm_steps
+    grad_buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    comm = "bf16" if comm_bf16 else "f32"
+    ref32 = OracleSlices(w, slices, "f32", comm, warm)
+    ref64 = OracleSlices(w, slices, "f64", comm, warm)
+    exact = True
+    for r in range(rounds):
+        for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
+            t0 = time.time()
+            gpu_run_stage(owner, w, r, stage, grad_buf)
+            torch.cuda.synchronize()
+            ref32.run_stage(r, stage)
+            ref64.run_stage(r, stage)
+            log(f"  round {r} stage {stage}: {time.time() - t0:.1f}s")
+            # integer bookkeeping is exact
+            table = [w.microbatches(r, k) for k in range(w.workers)]
+            if stage == synth.STAGE_TILDE:
+                assert owner.total.value == sum(k // 2 for k in table)
+                assert owner.step.value == ref32.shards[0].step == (w.warm_steps if warm else 0) + r
+                got = bits_of(gather(owner.theta_tilde_bf16, slices))
+                w32 = np.concatenate([s.theta_tilde_bf16 for s in ref32.shards])
+                w64 = np.concatenate([s.theta_tilde_bf16 for s in ref64.shards])
+            else:
+                assert owner.total.value == sum(table)
+                assert owner.step.value == ref32.shards[0].step == (w.warm_steps if warm else 0) + r + 1
+                got = bits_of(gather(owner.theta_bf16, slices))
+                w32 = np.concatenate([s.theta_bf16 for s in ref32.shards])
+                w64 = np.concatenate([s.theta_bf16 for s in ref64.shards])
+            assert_bf16_close(got, w32, f"{w.name} r{r} s{stage} bf16 vs f32 form")
+            assert_bf16_close(got, w64, f"{w.name} r{r} s{stage} bf16 vs f64 form")
+            exact &= np.array_equal(got, w32)
+            gs = gather(owner.gsum, slices).numpy()
+            assert bit_mismatches(gs, np.concatenate([s.gsum for s in ref32.shards])) == 0
+        for name in ("theta", "m", "v"):
+            got = gather(getattr(owner, name), slices).numpy()
+            a32 = np.concatenate([getattr(s, name) for s in ref32.shards])
+            a64 = np.concatenate([getattr(s, name) for s in ref64.shards])
+            abs_ = 1e-30 if name == "v" else 1e-9
+            assert_f32_close(got, a32, f"{w.name} r{r} {name} vs f32 form", abs_=abs_)
+            if name == "theta":
+                # independent roundings of two correct implementations add up round by round;
+                # scale the relative bound by the largest magnitude theta had
+                ref0 = np.concatenate([w.host_theta(a, b - a) for a, b in slices]) \
+                    if warm is None else np.concatenate([warm[0][a:b] for a, b in slices])
+                err = np.abs(got.astype(np.float64) - a64)
+                bound = np.maximum(1e-9 * max(1, (r + 1) / 2),
+                                   2e-6 * np.maximum(np.abs(a64), np.abs(ref0)))
+                assert np.all(err <= bound), f"{w.name} r{r} theta vs f64 form"
+            else:
+                assert_f32_close(got, a64, f"{w.name} r{r} {name} vs f64 form", abs_=abs_)
+            exact &= bit_mismatches(got, a32) == 0
+    log(f"  bit-exact with the binary32 oracle form over all rounds: {exact}")
+    assert exact
+    return owner
+
+
+def test_tiny_three_rounds_whole_shard():
+    run_workload(synth.WORKLOADS["tiny"])
+
+
+def test_tiny_variants_fp32_communication_and_unfused_cast():
+    w = synth.WORKLOADS["tiny"]
+    run_workload(w, comm_bf16=False, rounds=2)
+    run_workload(w, fused=False, rounds=2)
+
+
+def test_ragged_small_shard_with_unequal_counts():
+    w = synth.Workload(name="ragged", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
+                       k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
+    run_workload(w)
+
+
+def test_gpt2_small_scale_shard_ten_rounds():
+    run_workload(synth.WORKLOADS["gpt2s"])
+
+
+def test_one_billion_scale_shard_warm_state_ten_rounds():
+    w = synth.WORKLOADS["1b"]
+    t0 = time.time()
+    warm = oracle_warm_state(w, 0, w.n)
+    log(f"oracle warm state ({w.warm_steps} steps on {w.n} elements): {time.time() - t0:.1f}s")
+    assert np.all(warm[2] >= 0) and np.count_nonzero(warm[1]) > 0.99 * w.n
+    run_workload(w, warm=warm)
+
+
+def test_seven_billion_scale_shard_five_rounds():
+    run_workload(synth.WORKLOADS["7b"])
+
+
+def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
+    run_workload(synth.WORKLOADS["7b_hetero"])
