@@ -23,7 +23,8 @@
  *   - Arrays are flat and contiguous, element j at index j.  bf16 values are
  *     passed as uint16_t bit patterns.  Device pointers must be 16-byte aligned.
  *   - n is the shard length in elements, 0 <= n <= ACCO_MAX_ELEMS.  n == 0 does no
- *     device work but still performs the host counter bookkeeping.
+ *     device work but still performs the host counter bookkeeping; array pointers
+ *     are then not dereferenced and may be NULL (an empty tensor has no address).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on it and the call returns without waiting; host
  *     counters are updated before return.

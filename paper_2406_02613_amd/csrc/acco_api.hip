@@ -157,8 +157,8 @@ AdamScalars fold(const acco_adamw_t& hp, int64_t step, int64_t total_count)
 ACCO_API int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, int init,
                              int64_t* count, void* stream)
 {
-    if (acc == nullptr || grad_bf16 == nullptr) return ACCO_ERR_NULL;
     if (int rc = check_n(n)) return rc;
+    if (n > 0 && (acc == nullptr || grad_bf16 == nullptr)) return ACCO_ERR_NULL;
     if (!aligned16(acc) || !aligned16(grad_bf16)) return ACCO_ERR_ALIGN;
     if (init != 0 && init != 1) return ACCO_ERR_ARG;
     if (count != nullptr && !init &&
@@ -180,8 +180,8 @@ ACCO_API int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, i
 
 ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stream)
 {
-    if (out_bf16 == nullptr || src == nullptr) return ACCO_ERR_NULL;
     if (int rc = check_n(n)) return rc;
+    if (n > 0 && (out_bf16 == nullptr || src == nullptr)) return ACCO_ERR_NULL;
     if (!aligned16(out_bf16) || !aligned16(src)) return ACCO_ERR_ALIGN;
     if (overlap(out_bf16, n * 2, src, n * 4)) return ACCO_ERR_ALIAS;
     if (n == 0) return ACCO_OK;
@@ -217,8 +217,8 @@ ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int work
                                 int64_t n, int accumulate, const int64_t* counts, int64_t* total,
                                 void* stream)
 {
-    if (gsum == nullptr || shards == nullptr) return ACCO_ERR_NULL;
     if (int rc = check_n(n)) return rc;
+    if (shards == nullptr || (n > 0 && gsum == nullptr)) return ACCO_ERR_NULL;
     if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
     if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
     if (accumulate != 0 && accumulate != 1) return ACCO_ERR_ARG;
@@ -226,7 +226,7 @@ ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int work
     if (!aligned16(gsum)) return ACCO_ERR_ALIGN;
     const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
     for (int w = 0; w < workers; ++w) {
-        if (shards[w] == nullptr) return ACCO_ERR_NULL;
+        if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
         if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
         if (overlap(gsum, n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
     }
@@ -256,9 +256,10 @@ ACCO_API int acco_estimate_step(const float* theta, const float* m, const float*
                                 uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
                                 int64_t step, int64_t total_count, void* stream)
 {
-    if (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr) return ACCO_ERR_NULL;
-    if (theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
     if (int rc = check_n(n)) return rc;
+    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
+        return ACCO_ERR_NULL;
+    if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
     if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
         !aligned16(theta_tilde_f32) || !aligned16(theta_tilde_bf16))
         return ACCO_ERR_ALIGN;
@@ -293,9 +294,10 @@ ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsu
                               uint16_t* theta_bf16, int64_t n, const acco_adamw_t* hp,
                               int64_t* step, int64_t total_count, void* stream)
 {
-    if (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr || step == nullptr)
-        return ACCO_ERR_NULL;
     if (int rc = check_n(n)) return rc;
+    if (step == nullptr) return ACCO_ERR_NULL;
+    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
+        return ACCO_ERR_NULL;
     if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
         !aligned16(theta_bf16))
         return ACCO_ERR_ALIGN;

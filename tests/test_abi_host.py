@@ -41,8 +41,9 @@ def test_struct_layout_matches_the_header():
 def test_accumulate_validation_and_counter():
     L = B.lib()
     c = ctypes.c_int64(0)
-    assert L.acco_accumulate(NONE, vp(Bp), 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
-    assert L.acco_accumulate(vp(A), NONE, 0, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
+    assert L.acco_accumulate(NONE, vp(Bp), 4, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
+    assert L.acco_accumulate(vp(A), NONE, 4, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_NULL
+    assert L.acco_accumulate(NONE, NONE, 0, 1, NONE, NONE) == 0    # empty shard: no addresses
     assert L.acco_accumulate(vp(A), vp(Bp), -1, 0, ctypes.byref(c), NONE) == B.ACCO_ERR_SIZE
     assert L.acco_accumulate(vp(A), vp(Bp), (1 << 40) + 1, 0, NONE, NONE) == B.ACCO_ERR_SIZE
     assert L.acco_accumulate(vp(A + 4), vp(Bp), 0, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
@@ -63,7 +64,7 @@ def test_accumulate_validation_and_counter():
 
 def test_cast_validation():
     L = B.lib()
-    assert L.acco_cast_params(NONE, vp(A), 0, NONE) == B.ACCO_ERR_NULL
+    assert L.acco_cast_params(NONE, vp(A), 4, NONE) == B.ACCO_ERR_NULL
     assert L.acco_cast_params(vp(A), vp(Bp), -5, NONE) == B.ACCO_ERR_SIZE
     assert L.acco_cast_params(vp(A + 8), vp(Bp), 0, NONE) == B.ACCO_ERR_ALIGN
     assert L.acco_cast_params(vp(A), vp(A), 16, NONE) == B.ACCO_ERR_ALIAS
@@ -80,7 +81,7 @@ def test_reduce_validation_and_count_totals():
     cnt = (ctypes.c_int64 * 2)(3, 4)
     tot = ctypes.c_int64(100)
     r = L.acco_reduce_shards
-    assert r(NONE, s2, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
+    assert r(NONE, s2, 2, 0, 4, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
     assert r(vp(A), NONE, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
     assert r(vp(A), s2, 0, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_SIZE
     assert r(vp(A), s2, 65, 0, 0, 0, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_SIZE
@@ -88,7 +89,7 @@ def test_reduce_validation_and_count_totals():
     assert r(vp(A), s2, 2, 0, 0, 3, cnt, ctypes.byref(tot), NONE) == B.ACCO_ERR_ARG
     assert r(vp(A), s2, 2, 0, 0, 0, cnt, NONE, NONE) == B.ACCO_ERR_NULL      # counts w/o total
     assert r(vp(A), s2, 2, 0, 0, 0, NONE, ctypes.byref(tot), NONE) == B.ACCO_ERR_NULL
-    assert r(vp(A), _shards(Bp, 0), 2, 0, 0, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), _shards(Bp, 0), 2, 0, 4, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
     assert r(vp(A), _shards(Bp, C + 2), 2, 0, 0, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
     assert r(vp(A), _shards(Bp, A), 2, 0, 8, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
     neg = (ctypes.c_int64 * 2)(3, -1)
@@ -130,8 +131,8 @@ def test_estimate_validation():
     L = B.lib()
     e = L.acco_estimate_step
     hp = ctypes.byref(GOOD)
-    assert e(NONE, vp(Bp), vp(C), vp(D), vp(E), NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
-    assert e(vp(A), vp(Bp), vp(C), vp(D), NONE, NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert e(NONE, vp(Bp), vp(C), vp(D), vp(E), NONE, 4, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), NONE, NONE, 4, hp, 0, 1, NONE) == B.ACCO_ERR_NULL
     assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, 0, NONE, 0, 1, NONE) == B.ACCO_ERR_NULL
     assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), NONE, -1, hp, 0, 1, NONE) == B.ACCO_ERR_SIZE
     assert e(vp(A), vp(Bp + 4), vp(C), vp(D), vp(E), NONE, 0, hp, 0, 1, NONE) == B.ACCO_ERR_ALIGN
@@ -152,7 +153,7 @@ def test_commit_validation_and_step_counter():
     hp = ctypes.byref(GOOD)
     step = ctypes.c_int64(0)
     st = ctypes.byref(step)
-    assert c(vp(A), vp(Bp), vp(C), NONE, NONE, 0, hp, st, 1, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), vp(Bp), vp(C), NONE, NONE, 4, hp, st, 1, NONE) == B.ACCO_ERR_NULL
     assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, hp, NONE, 1, NONE) == B.ACCO_ERR_NULL
     assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, -2, hp, st, 1, NONE) == B.ACCO_ERR_SIZE
     assert c(vp(A + 12), vp(Bp), vp(C), vp(D), NONE, 0, hp, st, 1, NONE) == B.ACCO_ERR_ALIGN

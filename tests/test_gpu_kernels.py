@@ -155,8 +155,10 @@ def _state(rng, n, kind):
     if kind == "cold":
         m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
     else:
+        # a state Adam can be in: |m| / sqrt(v) stays of order one, so steps are of order lr
         m = (rng.standard_normal(n) * 1e-4).astype(np.float32)
-        v = (rng.random(n) * 1e-8).astype(np.float32)
+        v = (m.astype(np.float64) ** 2 * rng.uniform(0.5, 4.0, n) + 1e-12 * rng.random(n)).astype(
+            np.float32)
     gsum = (rng.standard_normal(n) * 4e-4).astype(np.float32)
     if n > 16:
         gsum[::7] = 0.0                          # exact zeros: the pure-decay path
@@ -195,6 +197,8 @@ def test_commit_matches_both_oracle_forms(acco, shape):
                 assert bit_mismatches(gd.cpu().numpy(), gsum) == 0       # input untouched
                 got = [x.cpu().numpy() for x in (td, md, vd)]
                 got_b = bits_of(out)
+                # the bf16 copy is the RNE rounding of the fp32 theta the kernel itself wrote
+                assert np.array_equal(got_b, oracle.cast(got[0]))
                 for prec in ("f64", "f32"):
                     t2, m2, v2 = theta.copy(), m.copy(), v.copy()
                     want_b = oracle.commit(t2, m2, v2, gsum, ohp, step + 1, count, precision=prec)
