@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the ACCO per-shard optimizer path on one MI355X.
+
+A step is one ACCO round of one shard owner: every micro-batch gradient of every
+simulated worker is accumulated (fp32), each worker's sum is published to its bf16
+communication buffer, the owner reduces the W buffers, runs the speculative estimate
+step, then accumulates / publishes / reduces the second half onto the retained sum
+and runs the committed AdamW step with the fused bf16 parameter output.  All inputs
+(parameters, optimizer state, every micro-batch gradient of the round) are resident
+in HBM before the timed region starts.
+
+Prints ONE JSON line (see README/DESIGN for the fields).  `roofline` is the committed
+step kernel, timed with HIP events on the launching stream inside the timed region;
+`kernels` carries the same figures for every entry point; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="7b",
+                    help="tiny | gpt2s | 1b | 7b | 7b_hetero (default: the 875M-element shard)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the shard (fp32, n elements read and "
+                         "n written) so that a counter run has a kernel of known traffic")
+    ap.add_argument("--unfused-cast", action="store_true",
+                    help="commit without the fused bf16 output, then acco_cast_params")
+    return ap.parse_args()
+
+
+class EventLog:
+    """HIP event pairs on torch's current stream (the stream every kernel is launched on)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}      # name -> list of (start, end)
+        self.enabled = False
+
+    def timed(self, name, fn, *a, **kw):
+        if not self.enabled:
+            return fn(*a, **kw)
+        s = self.torch.cuda.Event(enable_timing=True)
+        e = self.torch.cuda.Event(enable_timing=True)
+        s.record()
+        out = fn(*a, **kw)
+        e.record()
+        self.pairs.setdefault(name, []).append((s, e))
+        return out
+
+    def summary(self):
+        return {k: [s.elapsed_time(e) for s, e in v] for k, v in self.pairs.items()}
+
+
+def run_round(A, owner, w, rnd, grads, log, fused=True):
+    """One ACCO round through the C ABI; grads[stage][worker][mb] are resident bf16 tensors."""
+    import synth
+    B = A.binding
+    for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
+        first = stage == synth.STAGE_TILDE
+        for wk in range(w.workers):
+            for mb, g in enumerate(grads[stage][wk]):
+                init = mb == 0
+                log.timed("accumulate_init" if init else "accumulate", B.acco_accumulate,
+                          owner.acc[wk], g, init, owner.count[wk])
+        for wk in range(w.workers):
+            log.timed("cast", B.acco_cast_params, owner.comm[wk], owner.acc[wk])
+        counts = [c.value for c in owner.count]
+        log.timed("reduce_init" if first else "reduce_accumulate", B.acco_reduce_shards,
+                  owner.gsum, owner.comm, not first, counts, owner.total)
+        if first:
+            log.timed("estimate", B.acco_estimate_step, owner.theta, owner.m, owner.v, owner.gsum,
+                      owner.hp, owner.step.value, owner.total.value,
+                      theta_tilde_bf16=owner.theta_tilde_bf16)
+        elif fused:
+            log.timed("commit_bf16", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
+                      owner.hp, owner.step, owner.total.value, theta_bf16=owner.theta_bf16)
+        else:
+            log.timed("commit", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
+                      owner.hp, owner.step, owner.total.value)
+            log.timed("cast", B.acco_cast_params, owner.theta_bf16, owner.theta)
+
+
+def kernel_bytes_per_elem(name, workers):
+    from paper_2406_02613_amd import layout
+    if name == "reduce_init":
+        return layout.reduce_bytes_per_elem(workers, True, False)
+    if name == "reduce_accumulate":
+        return layout.reduce_bytes_per_elem(workers, True, True)
+    return layout.BYTES_PER_ELEM[name]
+
+
+def cpu_baseline(w, target_seconds):
+    """The oracle (as it stands) on the first S elements of the same workload, one round."""
+    import numpy as np
+    import oracle
+    import synth
+    cores = min(oracle.usable_cores(), 64)
+    oracle.set_threads(cores)
+    h = w.hyper
+    hp = oracle.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay)
+
+    def rounds(S, R):
+        """R rounds on the first S elements; inputs are generated outside the timed region."""
+        grads = {st: [[synth.host_grad_bf16(w.grad_spec(0, st, wk, mb), 0, S)
+                       for mb in range(w.stage_counts(0, st)[wk])] for wk in range(w.workers)]
+                 for st in (synth.STAGE_TILDE, synth.STAGE_FULL)}
+        sh = oracle.OracleShard(w.host_theta(0, S), w.workers, hp, precision="f64")
+        t0 = time.perf_counter()
+        for _ in range(R):
+            for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
+                for wk in range(w.workers):
+                    for g in grads[st][wk]:
+                        sh.add_microbatch(wk, g)
+                if st == synth.STAGE_TILDE:
+                    sh.stage1()
+                else:
+                    sh.stage2()
+        return time.perf_counter() - t0
+
+    S = int(min(w.n, 1 << 24))            # ~100 host bytes per sampled element
+    rounds(min(S, 1 << 18), 1)            # page in, start the thread pool
+    t1 = rounds(S, 1)
+    R = int(max(1, min(200, round(target_seconds / max(t1, 1e-6)))))
+    t = rounds(S, R)
+    return {"value": S * R / t, "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "sample": f"{R} full rounds of workload '{w.name}' on its first {S} shard elements "
+                      f"(binary64 form, {cores} OpenMP threads, {t:.1f} s)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this path is measured on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives are part of this build).", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2406_02613_amd as A
+    import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    A.binding.lib()
+    w = synth.WORKLOADS[args.workload]
+    h = w.hyper
+    owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
+                                                      h.weight_decay))
+    w.device_theta(owner.theta)
+
+    # every micro-batch gradient of one round, resident in HBM
+    grads = {}
+    n_bufs = 0
+    for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
+        grads[st] = []
+        for wk in range(w.workers):
+            row = []
+            for mb in range(w.stage_counts(0, st)[wk]):
+                g = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+                synth.device_grad_bf16(g, w.grad_spec(0, st, wk, mb), 0)
+                row.append(g)
+                n_bufs += 1
+            grads[st].append(row)
+    torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        owner.gsum.copy_(owner.theta)          # 4n bytes read, 4n bytes written
+        torch.cuda.synchronize()
+
+    log = EventLog(torch)
+    fused = not args.unfused_cast
+    for r in range(args.warmup):
+        run_round(A, owner, w, r, grads, log, fused)
+    torch.cuda.synchronize()
+
+    log.enabled = True
+    t_start = torch.cuda.Event(enable_timing=True)
+    t_end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    t_start.record()
+    for r in range(args.steps):
+        run_round(A, owner, w, args.warmup + r, grads, log, fused)
+    t_end.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_total = t_start.elapsed_time(t_end)
+    ms_per_step = ms_total / args.steps
+
+    kernels = {}
+    for name, times in log.summary().items():
+        avg_ms = sum(times) / len(times)
+        bpe = kernel_bytes_per_elem(name, w.workers)
+        gbs = bpe * w.n / (avg_ms * 1e-3) / 1e9
+        kernels[name] = {"calls_per_step": len(times) / args.steps, "avg_ms": round(avg_ms, 4),
+                         "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
+                         "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "elements/s": w.n / (avg_ms * 1e-3)}
+
+    head = "commit_bf16" if fused else "commit"
+    k = kernels[head]
+    roofline = {"kernel": "acco_commit_step" + (" (fused bf16 output)" if fused else ""),
+                "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": k["frac_of_peak"], "traffic": None,
+                "bytes_per_launch": k["bytes_per_elem"] * w.n, "avg_ms": k["avg_ms"]}
+
+    out = {
+        "metric": "shard optimizer-step elements/s (one full ACCO round of one shard owner)",
+        "value": w.n / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n}-element fp32 shard (theta, m, v), W={w.workers} "
+                               f"simulated workers, {sum(w.microbatches(0, k) for k in range(w.workers))} "
+                               f"bf16 micro-batch gradients per round, AdamW lr={h.lr} "
+                               f"betas=({h.beta1},{h.beta2}) eps={h.eps} wd={h.weight_decay}",
+                   "resident_gradient_buffers": n_bufs,
+                   "fused_bf16_output": fused,
+                   "host_wall_ms_per_step": wall * 1e3 / args.steps},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        del grads
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

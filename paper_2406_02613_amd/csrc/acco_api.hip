@@ -28,11 +28,11 @@ struct LaunchShape {
 enum Entry { kAccumulate = 0, kCast, kReduce, kEstimate, kCommit, kEntries };
 
 LaunchShape g_shape[kEntries] = {
-    {{256}, {4}, {0}},  // accumulate
-    {{256}, {4}, {0}},  // cast
-    {{256}, {2}, {0}},  // reduce
-    {{256}, {2}, {0}},  // estimate
-    {{256}, {2}, {0}},  // commit
+    {{256}, {1}, {0}},  // accumulate
+    {{256}, {1}, {0}},  // cast
+    {{256}, {1}, {0}},  // reduce
+    {{256}, {1}, {0}},  // estimate
+    {{256}, {1}, {0}},  // commit
 };
 
 const char* const kEntryNames[kEntries] = {"accumulate", "cast", "reduce", "estimate", "commit"};
@@ -78,6 +78,10 @@ int launch(Entry e, const Op& op, int64_t n, hipStream_t stream)
 {
     const int64_t  nvec = n / 4;
     const Geometry g    = geometry(e, nvec);
+    if (g.vectors == 1 && (int64_t)g.grid.x >= g.tiles) {
+        hipLaunchKernelGGL((flat_kernel<Op>), g.grid, dim3(g.threads), 0, stream, op, nvec, n);
+        return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
+    }
     switch (g.vectors) {
         case 1:
             hipLaunchKernelGGL((stream_kernel<1, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,

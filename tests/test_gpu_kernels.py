@@ -11,7 +11,8 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 SIZES = [0, 1, 3, 4, 7, 8, 9, 63, 64, 65, 1000, 4096 + 5, (1 << 20), (1 << 20) + 37]
-SHAPES = [(256, 2, 0), (64, 1, 0), (512, 4, 0), (256, 4, 2), (128, 2, 1)]
+DEFAULT_SHAPE = (256, 1, 0)      # the library's default: one 16-byte vector per thread, no loop
+SHAPES = [DEFAULT_SHAPE, (64, 1, 0), (256, 2, 0), (512, 4, 0), (256, 4, 2), (128, 2, 1)]
 
 
 @pytest.fixture(scope="module")
@@ -76,7 +77,7 @@ def test_accumulate_is_bit_exact(acco, shape):
             acco.acco_accumulate(acc_d, bf16_tensor(g), k == 0, cnt)
             assert cnt.value == k + 1
         assert bit_mismatches(acc_d.cpu().numpy(), acc_h) == 0
-    acco.set_launch_shape("accumulate", 256, 4, 0)
+    acco.set_launch_shape("accumulate", *DEFAULT_SHAPE)
 
 
 def test_cast_all_fp32_classes_bit_exact(acco):
@@ -105,10 +106,10 @@ def test_cast_sizes(acco, shape):
         out = torch.full((n,), 1.0, dtype=torch.bfloat16, device="cuda")
         acco.acco_cast_params(out, dev(x))
         assert np.array_equal(bits_of(out), oracle.cast(x))
-    acco.set_launch_shape("cast", 256, 4, 0)
+    acco.set_launch_shape("cast", *DEFAULT_SHAPE)
 
 
-@pytest.mark.parametrize("shape", SHAPES[:3])
+@pytest.mark.parametrize("shape", SHAPES[:4])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("W", [1, 2, 8, 9, 17])
 def test_reduce_is_bit_exact_in_worker_order(acco, shape, dtype, W):
@@ -144,7 +145,7 @@ def test_reduce_is_bit_exact_in_worker_order(acco, shape, dtype, W):
         acco.acco_reduce_shards(g_d, sh_d[::-1], True, counts, tot)
         assert tot.value == 2 * sum(counts)
         assert bit_mismatches(g_d.cpu().numpy(), g_h) == 0
-    acco.set_launch_shape("reduce", 256, 2, 0)
+    acco.set_launch_shape("reduce", *DEFAULT_SHAPE)
 
 
 # ------------------------------------------------------------------ estimate / commit
@@ -219,7 +220,7 @@ def test_commit_matches_both_oracle_forms(acco, shape):
     log("commit bit-exact with the binary32 oracle form:", exact)
     # same operations, same order, each correctly rounded: the binary32 form is reproduced
     assert exact
-    acco.set_launch_shape("commit", 256, 2, 0)
+    acco.set_launch_shape("commit", *DEFAULT_SHAPE)
 
 
 @pytest.mark.parametrize("shape", SHAPES)
@@ -257,7 +258,7 @@ def test_estimate_reads_only_and_matches_oracle(acco, shape):
             acco.acco_commit_step(td, md, vd, gd, ghp, acco.Counter(41), 12, theta_bf16=c16)
             assert torch.equal(td.view(torch.int32), o32.view(torch.int32))
             assert torch.equal(c16.view(torch.int16), o16.view(torch.int16))
-    acco.set_launch_shape("estimate", 256, 2, 0)
+    acco.set_launch_shape("estimate", *DEFAULT_SHAPE)
 
 
 def test_non_finite_inputs_propagate_like_the_oracle(acco):
