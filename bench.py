@@ -28,6 +28,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 
+# HBM bytes per element per launch measured with rocprofv3 counters (FETCH_SIZE x 2.0 +
+# WRITE_SIZE x 1.0, factors from a plain copy of known size in the same run) on workload '7b';
+# the commands and the raw figures are in profiles/bench_7b_hbm_traffic.txt.
+MEASURED_TRAFFIC_B_PER_ELEM = {
+    "7b": {"accumulate_init": 6.0, "accumulate": 10.0, "cast": 6.0, "reduce_init": 20.0,
+           "reduce_accumulate": 24.0, "estimate": 18.0, "commit_bf16": 30.0},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -219,7 +227,9 @@ def main():
     k = kernels[head]
     roofline = {"kernel": "acco_commit_step" + (" (fused bf16 output)" if fused else ""),
                 "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": k["frac_of_peak"], "traffic": None,
+                "frac": k["frac_of_peak"],
+                "traffic": (MEASURED_TRAFFIC_B_PER_ELEM.get(w.name, {}).get(head) or 0) * w.n
+                or None,
                 "bytes_per_launch": k["bytes_per_elem"] * w.n, "avg_ms": k["avg_ms"]}
 
     out = {
