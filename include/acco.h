@@ -86,6 +86,20 @@ int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, int init, 
                     void* stream);
 
 /*
+ * acco_accumulate for the LAST micro-batch of an accumulation, fused with the publish
+ * to the bf16 communication buffer (Alg. 1: g_i <- g_i + grad F, then Buffer_i <- g_i):
+ *   s = init ? grad[j] : acc[j] + grad[j];   comm_bf16[j] = bf16_rne(s);
+ *   keep_acc != 0: acc[j] = s as well.  keep_acc == 0: acc is left as it was (it no longer
+ *   holds the sum; the next accumulation into it must start with init = 1) - this saves the
+ *   4-byte store per element.
+ * Same values as acco_accumulate followed by acco_cast_params.
+ *   comm_bf16  device, bf16[n], out.  Other arguments and errors as acco_accumulate; acc may be
+ *   NULL when init != 0 and keep_acc == 0; comm_bf16 must not overlap acc or grad_bf16.
+ */
+int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* comm_bf16, int64_t n,
+                            int init, int keep_acc, int64_t* count, void* stream);
+
+/*
  * fp32 -> bf16, round to nearest even (NaN stays NaN, overflow goes to infinity).
  * Used for Buffer_i <- g_i (bf16 communication buffer) and for the bf16 parameter
  * shard handed to the All_Gather when the step kernels' fused output is not used.
@@ -146,6 +160,37 @@ int acco_commit_step(float* theta, float* m, float* v, const float* gsum, uint16
                      int64_t n, const acco_adamw_t* hp, int64_t* step, int64_t total_count,
                      void* stream);
 
+/*
+ * acco_reduce_shards(accumulate = 0) fused with acco_estimate_step: stage 1 of the
+ * communication stream in one pass.  The sum over the worker shards is formed in registers in
+ * ascending worker order, stored to gsum (stage 2 adds onto it) and used at once for
+ *   theta~ = AdamW(theta, m, v; g = gsum / *total; update index = step + 1).
+ * Same values as the two separate calls; saves re-reading gsum.
+ *   gsum    device, fp32[n], out
+ *   counts  host, int64[workers], required;  total  host, out, required: sum(counts) >= 1
+ * Other arguments and errors as acco_reduce_shards and acco_estimate_step.
+ */
+int acco_reduce_estimate_step(const float* theta, const float* m, const float* v, float* gsum,
+                              const void* const* shards, int workers, int dtype,
+                              const int64_t* counts, int64_t* total, float* theta_tilde_f32,
+                              uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
+                              int64_t step, void* stream);
+
+/*
+ * acco_reduce_shards(accumulate = 1) fused with acco_commit_step: stage 2 in one pass.
+ *   g = ((gsum + x_0) + x_1) + ... ;  *total += sum(counts);
+ *   (theta, m, v) <- AdamW(theta, m, v; g / *total; update index = *step + 1);  *step += 1.
+ * Same values as the two separate calls; saves writing and re-reading gsum.
+ *   gsum    device, fp32[n], in/out: the retained stage-1 sum.  With workers <= 8 it is not
+ *           written; with more workers it receives the partial sum over all but the last
+ *           (up to 8) shards.  Its contents are not needed after this call.
+ *   counts  host, required;  total  host, in/out, required.
+ */
+int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
+                            const void* const* shards, int workers, int dtype,
+                            const int64_t* counts, int64_t* total, uint16_t* theta_bf16, int64_t n,
+                            const acco_adamw_t* hp, int64_t* step, void* stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* acco_status_string(int status);
 
@@ -154,7 +199,8 @@ int acco_version(void);
 
 /*
  * Launch shape used for subsequent calls of one entry point ("accumulate", "cast",
- * "reduce", "estimate", "commit"): threads per workgroup (64..512, multiple of 64),
+ * "reduce", "estimate", "commit", "accumulate_publish", "reduce_estimate", "reduce_commit"):
+ * threads per workgroup (64..512, multiple of 64),
  * 16-byte vectors each thread keeps in flight per array (1, 2 or 4), and workgroups
  * per compute unit (0 = one workgroup per tile, > 0 = grid-stride over that many
  * resident workgroups per CU).  Process-wide; meant for benchmarking, not required.

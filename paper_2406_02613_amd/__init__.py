@@ -1,10 +1,13 @@
 """ACCO per-shard optimizer path for AMD MI355X: HIP kernels behind a C ABI, and a thin binding."""
 from .binding import (ACCO_BF16, ACCO_F32, AccoError, AdamW, Counter, acco_accumulate,
-                      acco_cast_params, acco_commit_step, acco_estimate_step, acco_reduce_shards,
+                      acco_accumulate_publish, acco_cast_params, acco_commit_step,
+                      acco_estimate_step, acco_reduce_commit_step, acco_reduce_estimate_step,
+                      acco_reduce_shards,
                       make_hyper, set_launch_shape, status_string, version)
 from .shard import ShardOwner
 from . import layout
 
 __all__ = ["ACCO_BF16", "ACCO_F32", "AccoError", "AdamW", "Counter", "acco_accumulate",
-           "acco_cast_params", "acco_commit_step", "acco_estimate_step", "acco_reduce_shards",
+           "acco_accumulate_publish", "acco_cast_params", "acco_commit_step", "acco_estimate_step",
+           "acco_reduce_commit_step", "acco_reduce_estimate_step", "acco_reduce_shards",
            "make_hyper", "set_launch_shape", "status_string", "version", "ShardOwner", "layout"]

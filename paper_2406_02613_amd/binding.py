@@ -19,8 +19,10 @@ ACCO_ERR_ARG, ACCO_ERR_ALIAS, ACCO_ERR_DEVICE = -4, -5, -6
 ACCO_BF16, ACCO_F32 = 0, 1
 ACCO_MAX_WORKERS = 64
 
-EXPORTS = ("acco_accumulate", "acco_cast_params", "acco_reduce_shards", "acco_estimate_step",
-           "acco_commit_step", "acco_status_string", "acco_version", "acco_set_launch_shape")
+EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_cast_params", "acco_reduce_shards",
+           "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
+           "acco_reduce_commit_step", "acco_status_string", "acco_version",
+           "acco_set_launch_shape")
 
 
 class AdamW(ctypes.Structure):
@@ -54,6 +56,11 @@ def lib() -> ctypes.CDLL:
         L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, p]
         L.acco_estimate_step.argtypes = [p, p, p, p, p, p, i64, ctypes.POINTER(AdamW), i64, i64, p]
         L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, p]
+        L.acco_accumulate_publish.argtypes = [p, p, p, i64, ci, ci, pi64, p]
+        L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
+                                                p, p, i64, ctypes.POINTER(AdamW), i64, p]
+        L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
+                                              i64, ctypes.POINTER(AdamW), pi64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
@@ -151,6 +158,18 @@ def acco_accumulate(acc, grad_bf16, init: bool, count: Optional[Counter] = None)
     _check(rc, "acco_accumulate")
 
 
+def acco_accumulate_publish(acc, grad_bf16, comm_bf16, init: bool, keep_acc: bool = False,
+                            count: Optional[Counter] = None) -> None:
+    import torch
+    n = grad_bf16.numel()
+    acc_ptr = None if (acc is None) else _dev(acc, torch.float32, n, "acc")
+    rc = lib().acco_accumulate_publish(acc_ptr, _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"),
+                                       _dev(comm_bf16, torch.bfloat16, n, "comm_bf16"), n,
+                                       int(bool(init)), int(bool(keep_acc)),
+                                       None if count is None else count.ref(), _stream())
+    _check(rc, "acco_accumulate_publish")
+
+
 def acco_cast_params(out_bf16, src) -> None:
     import torch
     n = src.numel()
@@ -181,6 +200,51 @@ def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
                                   int(bool(accumulate)), cnts,
                                   None if total is None else total.ref(), _stream())
     _check(rc, "acco_reduce_shards")
+
+
+def _shard_args(shards: Sequence, n: int, counts: Sequence[int], where: str):
+    import torch
+    W = len(shards)
+    if W < 1:
+        raise AccoError(ACCO_ERR_SIZE, where)
+    dt = shards[0].dtype
+    if dt not in (torch.bfloat16, torch.float32):
+        raise TypeError("shards: expected bfloat16 or float32 tensors")
+    if len(counts) != W:
+        raise ValueError("counts: one per shard")
+    ptrs = (ctypes.c_void_p * W)(*[_dev(s, dt, n, f"shards[{i}]") for i, s in enumerate(shards)])
+    cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
+    return ptrs, cnts, W, (ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32)
+
+
+def acco_reduce_estimate_step(theta, m, v, gsum, shards: Sequence, counts: Sequence[int],
+                              total: Counter, hp: AdamW, step: int, *, theta_tilde_f32=None,
+                              theta_tilde_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_estimate_step")
+    rc = lib().acco_reduce_estimate_step(
+        _dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"), _dev(v, f32, n, "v"),
+        _dev(gsum, f32, n, "gsum"), ptrs, W, dt, cnts, total.ref(),
+        _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
+        _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"), n, ctypes.byref(hp),
+        int(step), _stream())
+    _check(rc, "acco_reduce_estimate_step")
+
+
+def acco_reduce_commit_step(theta, m, v, gsum, shards: Sequence, counts: Sequence[int],
+                            total: Counter, hp: AdamW, step: Counter, *, theta_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_commit_step")
+    rc = lib().acco_reduce_commit_step(
+        _dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"), _dev(v, f32, n, "v"),
+        _dev(gsum, f32, n, "gsum"), ptrs, W, dt, cnts, total.ref(),
+        _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n, ctypes.byref(hp), step.ref(),
+        _stream())
+    _check(rc, "acco_reduce_commit_step")
 
 
 def acco_estimate_step(theta, m, v, gsum, hp: AdamW, step: int, total_count: int, *,

@@ -25,7 +25,17 @@ struct LaunchShape {
     std::atomic<int> wg_per_cu;
 };
 
-enum Entry { kAccumulate = 0, kCast, kReduce, kEstimate, kCommit, kEntries };
+enum Entry {
+    kAccumulate = 0,
+    kCast,
+    kReduce,
+    kEstimate,
+    kCommit,
+    kAccumulatePublish,
+    kReduceEstimate,
+    kReduceCommit,
+    kEntries
+};
 
 LaunchShape g_shape[kEntries] = {
     {{256}, {1}, {0}},  // accumulate
@@ -33,9 +43,14 @@ LaunchShape g_shape[kEntries] = {
     {{256}, {1}, {0}},  // reduce
     {{256}, {1}, {0}},  // estimate
     {{256}, {1}, {0}},  // commit
+    {{256}, {1}, {0}},  // accumulate_publish
+    {{256}, {1}, {0}},  // reduce_estimate
+    {{256}, {1}, {0}},  // reduce_commit
 };
 
-const char* const kEntryNames[kEntries] = {"accumulate", "cast", "reduce", "estimate", "commit"};
+const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
+                                           "estimate",           "commit",          "accumulate_publish",
+                                           "reduce_estimate",    "reduce_commit"};
 
 int cu_count()
 {
@@ -132,6 +147,34 @@ int check_hyper(const acco_adamw_t* hp, int64_t step, int64_t total_count)
         return ACCO_ERR_ARG;
     if (step < 0 || step == std::numeric_limits<int64_t>::max() || total_count < 1)
         return ACCO_ERR_ARG;
+    return ACCO_OK;
+}
+
+// shards[]: non-NULL (when n > 0), aligned, not overlapping `out` (n fp32)
+int check_shards(const void* const* shards, int workers, int dtype, int64_t n, const void* out)
+{
+    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
+    if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
+    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    for (int w = 0; w < workers; ++w) {
+        if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
+        if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
+        if (overlap(out, n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
+    }
+    return ACCO_OK;
+}
+
+// base + sum(counts) with overflow and sign checks
+int sum_counts(const int64_t* counts, int workers, int64_t base, int64_t* out)
+{
+    if (base < 0) return ACCO_ERR_ARG;
+    int64_t t = base;
+    for (int w = 0; w < workers; ++w) {
+        if (counts[w] < 0) return ACCO_ERR_ARG;
+        if (counts[w] > std::numeric_limits<int64_t>::max() - t) return ACCO_ERR_ARG;
+        t += counts[w];
+    }
+    *out = t;
     return ACCO_OK;
 }
 
@@ -329,6 +372,206 @@ ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsu
                         n, s);
     }
     if (rc == ACCO_OK) *step += 1;
+    return rc;
+}
+
+ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* comm_bf16,
+                                     int64_t n, int init, int keep_acc, int64_t* count,
+                                     void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (init != 0 && init != 1) return ACCO_ERR_ARG;
+    if (keep_acc != 0 && keep_acc != 1) return ACCO_ERR_ARG;
+    const bool needs_acc = !init || keep_acc;
+    if (n > 0 && (grad_bf16 == nullptr || comm_bf16 == nullptr || (needs_acc && acc == nullptr)))
+        return ACCO_ERR_NULL;
+    if (!aligned16(acc) || !aligned16(grad_bf16) || !aligned16(comm_bf16)) return ACCO_ERR_ALIGN;
+    if (count != nullptr && !init &&
+        (*count < 0 || *count == std::numeric_limits<int64_t>::max()))
+        return ACCO_ERR_ARG;
+    if (overlap(acc, n * 4, grad_bf16, n * 2) || overlap(comm_bf16, n * 2, grad_bf16, n * 2) ||
+        overlap(comm_bf16, n * 2, acc, n * 4))
+        return ACCO_ERR_ALIAS;
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (init && keep_acc)
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, true>{acc, grad_bf16, comm_bf16}, n, s);
+        else if (init)
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, false>{acc, grad_bf16, comm_bf16}, n, s);
+        else if (keep_acc)
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, true>{acc, grad_bf16, comm_bf16}, n, s);
+        else
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, false>{acc, grad_bf16, comm_bf16}, n, s);
+    }
+    if (rc == ACCO_OK && count != nullptr) *count = init ? 1 : *count + 1;
+    return rc;
+}
+
+namespace {
+
+// Leading chunks of more than kReduceChunk shards go through the plain reduction; the last
+// chunk is what the fused kernel reads.  Returns the first shard index of that last chunk.
+template <bool BF16>
+int reduce_leading_chunks(float* gsum, const void* const* shards, int workers, int64_t n,
+                          bool accumulate, hipStream_t stream, int* last_begin)
+{
+    const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
+    *last_begin    = lead;
+    if (lead == 0 || n == 0) return ACCO_OK;
+    return launch_reduce<BF16>(gsum, shards, lead, n, accumulate, stream);
+}
+
+ShardPtrs last_chunk(const void* const* shards, int begin, int workers)
+{
+    ShardPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof ptrs);
+    for (int w = begin; w < workers; ++w) ptrs.p[w - begin] = shards[w];
+    return ptrs;
+}
+
+template <bool BF16, bool ACC>
+int launch_reduce_estimate(const float* theta, const float* m, const float* v, float* gsum,
+                           const ShardPtrs& ptrs, int cnt, float* o32, uint16_t* o16, int64_t n,
+                           const AdamScalars& sc, hipStream_t s)
+{
+    if (o32 != nullptr && o16 != nullptr)
+        return launch(kReduceEstimate,
+                      ReduceAdamOp<false, BF16, ACC, true, true, true>{
+                          theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc},
+                      n, s);
+    if (o32 != nullptr)
+        return launch(kReduceEstimate,
+                      ReduceAdamOp<false, BF16, ACC, true, true, false>{
+                          theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc},
+                      n, s);
+    return launch(kReduceEstimate,
+                  ReduceAdamOp<false, BF16, ACC, true, false, true>{
+                      theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc},
+                  n, s);
+}
+
+template <bool BF16>
+int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const ShardPtrs& ptrs,
+                         int cnt, uint16_t* o16, int64_t n, const AdamScalars& sc, hipStream_t s)
+{
+    if (o16 != nullptr)
+        return launch(kReduceCommit,
+                      ReduceAdamOp<true, BF16, true, false, false, true>{
+                          theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc},
+                      n, s);
+    return launch(kReduceCommit,
+                  ReduceAdamOp<true, BF16, true, false, false, false>{
+                      theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc},
+                  n, s);
+}
+
+}  // namespace
+
+ACCO_API int acco_reduce_estimate_step(const float* theta, const float* m, const float* v,
+                                       float* gsum, const void* const* shards, int workers,
+                                       int dtype, const int64_t* counts, int64_t* total,
+                                       float* theta_tilde_f32, uint16_t* theta_tilde_bf16,
+                                       int64_t n, const acco_adamw_t* hp, int64_t step,
+                                       void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (shards == nullptr || counts == nullptr || total == nullptr) return ACCO_ERR_NULL;
+    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
+        return ACCO_ERR_NULL;
+    if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
+    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
+        !aligned16(theta_tilde_f32) || !aligned16(theta_tilde_bf16))
+        return ACCO_ERR_ALIGN;
+    if (int rc = check_shards(shards, workers, dtype, n, gsum)) return rc;
+    int64_t new_total = 0;
+    if (int rc = sum_counts(counts, workers, 0, &new_total)) return rc;
+    if (int rc = check_hyper(hp, step, new_total)) return rc;
+    const int64_t esz   = dtype == ACCO_BF16 ? 2 : 4;
+    const void*   st[3] = {theta, m, v};
+    for (const void* in : st) {
+        if (overlap(gsum, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_tilde_f32, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_tilde_bf16, n * 2, in, n * 4)) return ACCO_ERR_ALIAS;
+    }
+    if (overlap(theta_tilde_f32, n * 4, gsum, n * 4) ||
+        overlap(theta_tilde_bf16, n * 2, gsum, n * 4) ||
+        overlap(theta_tilde_f32, n * 4, theta_tilde_bf16, n * 2))
+        return ACCO_ERR_ALIAS;
+    for (int w = 0; w < workers; ++w)
+        if (overlap(theta_tilde_f32, n * 4, shards[w], n * esz) ||
+            overlap(theta_tilde_bf16, n * 2, shards[w], n * esz))
+            return ACCO_ERR_ALIAS;
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t       s  = static_cast<hipStream_t>(stream);
+        const AdamScalars sc = fold(*hp, step, new_total);
+        int               begin = 0;
+        rc = dtype == ACCO_BF16 ? reduce_leading_chunks<true>(gsum, shards, workers, n, false, s, &begin)
+                                : reduce_leading_chunks<false>(gsum, shards, workers, n, false, s, &begin);
+        if (rc != ACCO_OK) return rc;
+        const ShardPtrs ptrs = last_chunk(shards, begin, workers);
+        const int       cnt  = workers - begin;
+        if (dtype == ACCO_BF16)
+            rc = begin > 0 ? launch_reduce_estimate<true, true>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
+                           : launch_reduce_estimate<true, false>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
+        else
+            rc = begin > 0 ? launch_reduce_estimate<false, true>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
+                           : launch_reduce_estimate<false, false>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
+    }
+    if (rc == ACCO_OK) *total = new_total;
+    return rc;
+}
+
+ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
+                                     const void* const* shards, int workers, int dtype,
+                                     const int64_t* counts, int64_t* total, uint16_t* theta_bf16,
+                                     int64_t n, const acco_adamw_t* hp, int64_t* step,
+                                     void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (shards == nullptr || counts == nullptr || total == nullptr || step == nullptr)
+        return ACCO_ERR_NULL;
+    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
+        return ACCO_ERR_NULL;
+    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
+        !aligned16(theta_bf16))
+        return ACCO_ERR_ALIGN;
+    if (int rc = check_shards(shards, workers, dtype, n, gsum)) return rc;
+    int64_t new_total = 0;
+    if (int rc = sum_counts(counts, workers, *total, &new_total)) return rc;
+    if (int rc = check_hyper(hp, *step, new_total)) return rc;
+    const int64_t esz     = dtype == ACCO_BF16 ? 2 : 4;
+    const void*   f32s[4] = {theta, m, v, gsum};
+    for (int a = 0; a < 4; ++a) {
+        for (int b = a + 1; b < 4; ++b)
+            if (overlap(f32s[a], n * 4, f32s[b], n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_bf16, n * 2, f32s[a], n * 4)) return ACCO_ERR_ALIAS;
+        for (int w = 0; w < workers; ++w)
+            if (overlap(f32s[a], n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
+    }
+    for (int w = 0; w < workers; ++w)
+        if (overlap(theta_bf16, n * 2, shards[w], n * esz)) return ACCO_ERR_ALIAS;
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t       s  = static_cast<hipStream_t>(stream);
+        const AdamScalars sc = fold(*hp, *step, new_total);
+        int               begin = 0;
+        rc = dtype == ACCO_BF16 ? reduce_leading_chunks<true>(gsum, shards, workers, n, true, s, &begin)
+                                : reduce_leading_chunks<false>(gsum, shards, workers, n, true, s, &begin);
+        if (rc != ACCO_OK) return rc;
+        const ShardPtrs ptrs = last_chunk(shards, begin, workers);
+        const int       cnt  = workers - begin;
+        rc = dtype == ACCO_BF16 ? launch_reduce_commit<true>(theta, m, v, gsum, ptrs, cnt, theta_bf16, n, sc, s)
+                                : launch_reduce_commit<false>(theta, m, v, gsum, ptrs, cnt, theta_bf16, n, sc, s);
+    }
+    if (rc == ACCO_OK) {
+        *total = new_total;
+        *step += 1;
+    }
     return rc;
 }
 

@@ -182,6 +182,40 @@ struct AccumulateOp {
     }
 };
 
+// Last micro-batch of an accumulation fused with the publish: comm = bf16(acc + grad)
+// (INIT: comm = bf16(grad)).  KEEP also stores the fp32 sum back to acc.
+template <bool INIT, bool KEEP>
+struct AccumulatePublishOp {
+    float*          acc;
+    const uint16_t* grad;
+    uint16_t*       comm;
+    struct In {
+        f4 a;
+        u2 g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.g = ld(reinterpret_cast<const u2*>(grad) + i);
+        if (!INIT) in.a = ld(reinterpret_cast<const f4*>(acc) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        const f4 g = unpack_bf16x4(in.g);
+        const f4 s = INIT ? g : in.a + g;
+        if (KEEP) st(reinterpret_cast<f4*>(acc) + i, s);
+        st(reinterpret_cast<u2*>(comm) + i, pack_bf16x4(s));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        const float g = __uint_as_float((uint32_t)grad[j] << 16);
+        const float s = INIT ? g : acc[j] + g;
+        if (KEEP) acc[j] = s;
+        comm[j] = (uint16_t)to_bf16_bits(s);
+    }
+};
+
 // ------------------------------------------------------------------ cast
 
 struct CastOp {
@@ -311,6 +345,95 @@ struct AdamOp {
     {
         float t, mm, vv;
         adamw_elem(theta[j], m[j], v[j], gsum[j], s, t, mm, vv);
+        if (COMMIT) {
+            theta_w[j] = t;
+            m_w[j]     = mm;
+            v_w[j]     = vv;
+        }
+        if (OUT_F32) out_f32[j] = t;
+        if (OUT_BF16) out_bf16[j] = (uint16_t)to_bf16_bits(t);
+    }
+};
+
+// ------------------------------------------------------------------ reduce fused with the step
+
+// The owner-side reduction of up to kReduceChunk worker shards folded into the AdamW step:
+// the gradient sum is formed in registers (same order as ReduceOp), optionally stored to
+// gsum (stage 1 keeps it for stage 2), and consumed by the update in the same pass.
+template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16>
+struct ReduceAdamOp {
+    const float* theta;
+    const float* m;
+    const float* v;
+    float*       gsum;  // read when ACC, written when WRITE_GSUM
+    ShardPtrs    shards;
+    int          workers;
+    float*       theta_w;
+    float*       m_w;
+    float*       v_w;
+    float*       out_f32;
+    uint16_t*    out_bf16;
+    AdamScalars  s;
+    struct In {
+        f4 t, m, v, g;
+        f4 x[BF16 ? 1 : kReduceChunk];
+        u2 b[BF16 ? kReduceChunk : 1];
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.t = ld(reinterpret_cast<const f4*>(theta) + i);
+        in.m = ld(reinterpret_cast<const f4*>(m) + i);
+        in.v = ld(reinterpret_cast<const f4*>(v) + i);
+        if (ACC) in.g = ld(reinterpret_cast<const f4*>(gsum) + i);
+#pragma unroll
+        for (int w = 0; w < kReduceChunk; ++w) {
+            if (w < workers) {
+                if (BF16)
+                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + i);
+                else
+                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + i);
+            }
+        }
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        f4 g = in.g;
+#pragma unroll
+        for (int w = 0; w < kReduceChunk; ++w) {
+            if (w < workers) {
+                const f4 x = BF16 ? unpack_bf16x4(in.b[w]) : in.x[w];
+                g          = (!ACC && w == 0) ? x : g + x;
+            }
+        }
+        if (WRITE_GSUM) st(reinterpret_cast<f4*>(gsum) + i, g);
+        float to[4], mo[4], vo[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) adamw_elem(in.t[k], in.m[k], in.v[k], g[k], s, to[k], mo[k], vo[k]);
+        const f4 t  = {to[0], to[1], to[2], to[3]};
+        const f4 mm = {mo[0], mo[1], mo[2], mo[3]};
+        const f4 vv = {vo[0], vo[1], vo[2], vo[3]};
+        if (COMMIT) {
+            st(reinterpret_cast<f4*>(theta_w) + i, t);
+            st(reinterpret_cast<f4*>(m_w) + i, mm);
+            st(reinterpret_cast<f4*>(v_w) + i, vv);
+        }
+        if (OUT_F32) st(reinterpret_cast<f4*>(out_f32) + i, t);
+        if (OUT_BF16) st(reinterpret_cast<u2*>(out_bf16) + i, pack_bf16x4(t));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        float g = ACC ? gsum[j] : 0.0f;
+        for (int w = 0; w < workers; ++w) {
+            const float x =
+                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
+                     : static_cast<const float*>(shards.p[w])[j];
+            g = (!ACC && w == 0) ? x : g + x;
+        }
+        if (WRITE_GSUM) gsum[j] = g;
+        float t, mm, vv;
+        adamw_elem(theta[j], m[j], v[j], g, s, t, mm, vv);
         if (COMMIT) {
             theta_w[j] = t;
             m_w[j]     = mm;

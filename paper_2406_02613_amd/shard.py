@@ -12,22 +12,32 @@ GPU's memory:
   stage 2  publish       acco_cast_params
            reduce        acco_reduce_shards(accumulate onto the stage-1 sum)
            commit        acco_commit_step           (theta, m, v, step; fused bf16 theta)
+
+Two fusions give the same values with fewer passes over HBM:
+  fused_publish  the last micro-batch of a stage goes through acco_accumulate_publish,
+                 which writes the bf16 communication buffer directly (the caller says which
+                 micro-batch is the last one: ``last=True``);
+  fused_reduce   reduce + estimate and reduce + commit each run as one kernel
+                 (acco_reduce_estimate_step / acco_reduce_commit_step).
 """
 from __future__ import annotations
 
-from typing import List, Optional
+from typing import List
 
 from . import binding as B
 
 
 class ShardOwner:
     def __init__(self, n: int, workers: int, hp: B.AdamW, *, device="cuda", comm_bf16: bool = True,
-                 fused_bf16_out: bool = True):
+                 fused_bf16_out: bool = True, fused_publish: bool = False,
+                 fused_reduce: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
         self.comm_bf16 = comm_bf16
         self.fused_bf16_out = fused_bf16_out
+        self.fused_publish = fused_publish and comm_bf16
+        self.fused_reduce = fused_reduce
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self.theta = torch.empty(n, dtype=f32, device=dev)
@@ -43,36 +53,60 @@ class ShardOwner:
         self.total = B.Counter(0)                             # micro-batches summed in gsum
         self.step = B.Counter(0)                              # committed updates
         self._fresh = [True] * workers                        # next accumulate starts a new sum
+        self._published = [False] * workers                   # comm[w] already written this stage
 
     # computation stream
-    def add_microbatch(self, worker: int, grad_bf16) -> None:
-        B.acco_accumulate(self.acc[worker], grad_bf16, self._fresh[worker], self.count[worker])
+    def add_microbatch(self, worker: int, grad_bf16, last: bool = False) -> None:
+        """Accumulate one micro-batch gradient.  ``last`` marks the final micro-batch of the
+        stage for this worker (used only with fused_publish)."""
+        if last and self.fused_publish:
+            B.acco_accumulate_publish(self.acc[worker], grad_bf16, self.comm[worker],
+                                      self._fresh[worker], False, self.count[worker])
+            self._published[worker] = True
+        else:
+            B.acco_accumulate(self.acc[worker], grad_bf16, self._fresh[worker],
+                              self.count[worker])
         self._fresh[worker] = False
 
     def _publish(self):
         if not self.comm_bf16:
             return self.acc
         for w in range(self.W):
-            B.acco_cast_params(self.comm[w], self.acc[w])
+            if not self._published[w]:
+                B.acco_cast_params(self.comm[w], self.acc[w])
         return self.comm
 
     def _counts(self) -> List[int]:
         return [c.value for c in self.count]
 
+    def _end_stage(self) -> None:
+        self._fresh = [True] * self.W
+        self._published = [False] * self.W
+
     # communication stream
     def stage1(self) -> None:
-        B.acco_reduce_shards(self.gsum, self._publish(), False, self._counts(), self.total)
-        B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step.value,
-                             self.total.value, theta_tilde_bf16=self.theta_tilde_bf16)
-        self._fresh = [True] * self.W
+        shards = self._publish()
+        if self.fused_reduce:
+            B.acco_reduce_estimate_step(self.theta, self.m, self.v, self.gsum, shards,
+                                        self._counts(), self.total, self.hp, self.step.value,
+                                        theta_tilde_bf16=self.theta_tilde_bf16)
+        else:
+            B.acco_reduce_shards(self.gsum, shards, False, self._counts(), self.total)
+            B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step.value,
+                                 self.total.value, theta_tilde_bf16=self.theta_tilde_bf16)
+        self._end_stage()
 
     def stage2(self) -> None:
-        B.acco_reduce_shards(self.gsum, self._publish(), True, self._counts(), self.total)
-        if self.fused_bf16_out:
-            B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step,
-                               self.total.value, theta_bf16=self.theta_bf16)
+        shards = self._publish()
+        out = self.theta_bf16 if self.fused_bf16_out else None
+        if self.fused_reduce:
+            B.acco_reduce_commit_step(self.theta, self.m, self.v, self.gsum, shards,
+                                      self._counts(), self.total, self.hp, self.step,
+                                      theta_bf16=out)
         else:
+            B.acco_reduce_shards(self.gsum, shards, True, self._counts(), self.total)
             B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step,
-                               self.total.value)
+                               self.total.value, theta_bf16=out)
+        if not self.fused_bf16_out:
             B.acco_cast_params(self.theta_bf16, self.theta)
-        self._fresh = [True] * self.W
+        self._end_stage()

@@ -138,7 +138,7 @@ def gpu_run_stage(owner, w: synth.Workload, rnd: int, stage: int, grad_buf) -> N
     for wk in range(w.workers):
         for mb in range(counts[wk]):
             synth.device_grad_bf16(grad_buf, w.grad_spec(rnd, stage, wk, mb), 0)
-            owner.add_microbatch(wk, grad_buf)
+            owner.add_microbatch(wk, grad_buf, last=(mb == counts[wk] - 1))
     if stage == synth.STAGE_TILDE:
         owner.stage1()
     else:

@@ -196,3 +196,62 @@ def test_buffer_inventory_reproduces_the_papers_memory_table():
     assert layout.BYTES_PER_ELEM["commit"] == 28 and layout.BYTES_PER_ELEM["commit_bf16"] == 30
     assert layout.reduce_bytes_per_elem(8, True, False) == 20
     assert layout.reduce_bytes_per_elem(8, True, True) == 24
+
+
+def test_accumulate_publish_validation_and_counter():
+    L = B.lib()
+    f = L.acco_accumulate_publish
+    c = ctypes.c_int64(4)
+    cr = ctypes.byref(c)
+    assert f(vp(A), NONE, vp(C), 4, 0, 0, cr, NONE) == B.ACCO_ERR_NULL
+    assert f(vp(A), vp(Bp), NONE, 4, 0, 0, cr, NONE) == B.ACCO_ERR_NULL
+    assert f(NONE, vp(Bp), vp(C), 4, 0, 0, cr, NONE) == B.ACCO_ERR_NULL      # needs acc to add to
+    assert f(NONE, vp(Bp), vp(C), 4, 1, 1, cr, NONE) == B.ACCO_ERR_NULL      # needs acc to keep
+    assert f(vp(A), vp(Bp), vp(C), 4, 2, 0, cr, NONE) == B.ACCO_ERR_ARG
+    assert f(vp(A), vp(Bp), vp(C), 4, 0, 5, cr, NONE) == B.ACCO_ERR_ARG
+    assert f(vp(A), vp(Bp), vp(C + 6), 4, 0, 0, cr, NONE) == B.ACCO_ERR_ALIGN
+    assert f(vp(A), vp(Bp), vp(Bp), 8, 0, 0, cr, NONE) == B.ACCO_ERR_ALIAS
+    assert f(vp(A), vp(Bp), vp(A + 16), 64, 0, 0, cr, NONE) == B.ACCO_ERR_ALIAS
+    assert f(vp(A), vp(Bp), vp(C), -1, 0, 0, cr, NONE) == B.ACCO_ERR_SIZE
+    assert c.value == 4
+    assert f(vp(A), vp(Bp), vp(C), 0, 0, 0, cr, NONE) == 0 and c.value == 5
+    assert f(NONE, vp(Bp), vp(C), 0, 1, 0, cr, NONE) == 0 and c.value == 1
+
+
+def test_fused_reduce_steps_validation_and_counters():
+    L = B.lib()
+    hp = ctypes.byref(GOOD)
+    s2 = _shards(E, F)
+    cnt = (ctypes.c_int64 * 2)(3, 4)
+    tot = ctypes.c_int64(50)
+    tr = ctypes.byref(tot)
+    est, com = L.acco_reduce_estimate_step, L.acco_reduce_commit_step
+    G, H = 0x70000, 0x80000
+    # estimate
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), NONE, 0, hp, 0, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, NONE, vp(G), NONE, 0, hp, 0, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), NONE, s2, 2, 0, cnt, tr, vp(G), NONE, 4, hp, 0, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, NONE, NONE, 4, hp, 0, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 0, 0, cnt, tr, vp(G), NONE, 0, hp, 0, NONE) == B.ACCO_ERR_SIZE
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 3, cnt, tr, vp(G), NONE, 0, hp, 0, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), NONE, 0, hp, -1, NONE) == B.ACCO_ERR_ARG
+    zero = (ctypes.c_int64 * 2)(0, 0)
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, zero, tr, vp(G), NONE, 0, hp, 0, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(C), vp(A), s2, 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), NONE, 8, hp, 0, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C), vp(D), _shards(E, D), 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE) == B.ACCO_ERR_ALIAS
+    assert tot.value == 50
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), vp(H), 0, hp, 0, NONE) == 0
+    assert tot.value == 7                     # stage 1: the total starts afresh
+    # commit
+    step = ctypes.c_int64(9)
+    sr = ctypes.byref(step)
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, NONE, NONE) == B.ACCO_ERR_NULL
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), 0, hp, sr, NONE) == B.ACCO_ERR_NULL
+    assert com(vp(A), vp(Bp), vp(A), vp(D), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D), _shards(E, Bp), 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), 8, hp, sr, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D + 4), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE) == B.ACCO_ERR_ALIGN
+    assert tot.value == 7 and step.value == 9
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, sr, NONE) == 0
+    assert tot.value == 14 and step.value == 10      # stage 2 adds onto the stage-1 total

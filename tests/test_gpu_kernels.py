@@ -294,3 +294,101 @@ def test_errors_raise_and_leave_buffers_alone(acco):
         acco.acco_accumulate(a, g[:32], False)                  # length mismatch
     torch.cuda.synchronize()
     assert torch.all(a == 1.0)
+
+
+# ------------------------------------------------------------------ fused entry points
+
+
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 2, 1), (512, 4, 0)])
+def test_accumulate_publish_equals_accumulate_then_cast(acco, shape):
+    acco.set_launch_shape("accumulate_publish", *shape)
+    rng = np.random.default_rng(11)
+    for n in SIZES:
+        for init in (False, True):
+            for keep in (False, True):
+                log("accumulate_publish", shape, n, init, keep)
+                acc0 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+                g = _rand_bf16(rng, n)
+                acc_h = acc0.copy()
+                oracle.accumulate(acc_h, g, init=init)
+                want_comm = oracle.cast(acc_h)
+                acc_d = dev(acc0)
+                comm = torch.full((n,), 3.0, dtype=torch.bfloat16, device="cuda")
+                cnt = acco.Counter(5)
+                acco.acco_accumulate_publish(acc_d, bf16_tensor(g), comm, init, keep, cnt)
+                assert cnt.value == (1 if init else 6)
+                assert np.array_equal(bits_of(comm), want_comm)
+                assert bit_mismatches(acc_d.cpu().numpy(), acc_h if keep else acc0) == 0
+    # a first-and-only micro-batch needs no accumulator at all
+    g = _rand_bf16(rng, 1001)
+    comm = torch.empty(1001, dtype=torch.bfloat16, device="cuda")
+    acco.acco_accumulate_publish(None, bf16_tensor(g), comm, True, False)
+    assert np.array_equal(bits_of(comm), g)
+    acco.set_launch_shape("accumulate_publish", *DEFAULT_SHAPE)
+
+
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 2, 1), (512, 4, 0)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("W", [1, 3, 8, 9, 20])
+def test_fused_reduce_steps_equal_the_separate_calls_and_the_oracle(acco, shape, dtype, W):
+    acco.set_launch_shape("reduce_estimate", *shape)
+    acco.set_launch_shape("reduce_commit", *shape)
+    rng = np.random.default_rng(12 + W)
+    h = HYPERS[0]
+    ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    for n in (0, 1, 5, 64, 1000, 4096 + 7, 200_003):
+        log("fused reduce+step", shape, dtype, W, n)
+        theta, m, v, _ = _state(rng, n, "warm")
+        if dtype == "bf16":
+            s1 = [_rand_bf16(rng, n, 2e-4) for _ in range(W)]
+            s2 = [_rand_bf16(rng, n, 2e-4) for _ in range(W)]
+            d1, d2 = [bf16_tensor(s) for s in s1], [bf16_tensor(s) for s in s2]
+        else:
+            s1 = [(rng.standard_normal(n) * 2e-4).astype(np.float32) for _ in range(W)]
+            s2 = [(rng.standard_normal(n) * 2e-4).astype(np.float32) for _ in range(W)]
+            d1, d2 = [dev(s) for s in s1], [dev(s) for s in s2]
+        c1, c2 = list(range(1, W + 1)), list(range(2, W + 2))
+        # oracle: stage 1 then stage 2
+        g_h = np.empty(n, np.float32)
+        oracle.reduce(g_h, s1, accumulate_=False)
+        e32, e16 = oracle.estimate(theta, m, v, g_h, ohp, 8, sum(c1), precision="f32")
+        g1_h = g_h.copy()
+        oracle.reduce(g_h, s2, accumulate_=True)
+        t_h, m_h, v_h = theta.copy(), m.copy(), v.copy()
+        b16 = oracle.commit(t_h, m_h, v_h, g_h, ohp, 8, sum(c1) + sum(c2), precision="f32")
+        # GPU fused
+        td, md, vd = dev(theta), dev(m), dev(v)
+        gd = torch.full((n,), 9.0, dtype=torch.float32, device="cuda")
+        o32 = torch.empty(n, dtype=torch.float32, device="cuda")
+        o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        tot, step = acco.Counter(123), acco.Counter(7)
+        acco.acco_reduce_estimate_step(td, md, vd, gd, d1, c1, tot, ghp, step.value,
+                                       theta_tilde_f32=o32, theta_tilde_bf16=o16)
+        assert tot.value == sum(c1) and step.value == 7
+        assert bit_mismatches(gd.cpu().numpy(), g1_h) == 0          # the retained stage-1 sum
+        assert bit_mismatches(o32.cpu().numpy(), e32) == 0
+        assert np.array_equal(bits_of(o16), e16)
+        for d, h_ in ((td, theta), (md, m), (vd, v)):
+            assert bit_mismatches(d.cpu().numpy(), h_) == 0         # estimate commits nothing
+        only16 = torch.empty_like(o16)
+        acco.acco_reduce_estimate_step(td, md, vd, gd, d1, c1, acco.Counter(0), ghp, 7,
+                                       theta_tilde_bf16=only16)
+        assert torch.equal(only16.view(torch.int16), o16.view(torch.int16))
+        c16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        acco.acco_reduce_commit_step(td, md, vd, gd, d2, c2, tot, ghp, step, theta_bf16=c16)
+        assert tot.value == sum(c1) + sum(c2) and step.value == 8
+        assert bit_mismatches(td.cpu().numpy(), t_h) == 0
+        assert bit_mismatches(md.cpu().numpy(), m_h) == 0
+        assert bit_mismatches(vd.cpu().numpy(), v_h) == 0
+        assert np.array_equal(bits_of(c16), b16)
+        if W <= 8:
+            assert bit_mismatches(gd.cpu().numpy(), g1_h) == 0      # gsum only read
+        # against the binary64 form too
+        t64, m64, v64 = theta.copy(), m.copy(), v.copy()
+        oracle.commit(t64, m64, v64, g_h, ohp, 8, sum(c1) + sum(c2), precision="f64")
+        assert_f32_close(td.cpu().numpy(), t64, "theta vs f64")
+        assert_f32_close(md.cpu().numpy(), m64, "m vs f64")
+        assert_f32_close(vd.cpu().numpy(), v64, "v vs f64", abs_=1e-30)
+    acco.set_launch_shape("reduce_estimate", *DEFAULT_SHAPE)
+    acco.set_launch_shape("reduce_commit", *DEFAULT_SHAPE)

@@ -30,14 +30,16 @@ def gpu_hyper(A, w):
     return A.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay)
 
 
-def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None):
+def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
+                 fused_publish=False, fused_reduce=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
     log(f"workload {w.name}: n={w.n} W={w.workers} rounds={rounds} slices={len(slices)} "
         f"({sum(b - a for a, b in slices)} elements checked)")
     owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
-                         fused_bf16_out=fused)
+                         fused_bf16_out=fused, fused_publish=fused_publish,
+                         fused_reduce=fused_reduce)
     if warm is None:
         w.device_theta(owner.theta)
     else:
@@ -75,8 +77,9 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
             assert_bf16_close(got, w32, f"{w.name} r{r} s{stage} bf16 vs f32 form")
             assert_bf16_close(got, w64, f"{w.name} r{r} s{stage} bf16 vs f64 form")
             exact &= np.array_equal(got, w32)
-            gs = gather(owner.gsum, slices).numpy()
-            assert bit_mismatches(gs, np.concatenate([s.gsum for s in ref32.shards])) == 0
+            if not (fused_reduce and stage == synth.STAGE_FULL):   # fused commit only reads gsum
+                gs = gather(owner.gsum, slices).numpy()
+                assert bit_mismatches(gs, np.concatenate([s.gsum for s in ref32.shards])) == 0
         for name in ("theta", "m", "v"):
             got = gather(getattr(owner, name), slices).numpy()
             a32 = np.concatenate([getattr(s, name) for s in ref32.shards])
@@ -110,10 +113,19 @@ def test_tiny_variants_fp32_communication_and_unfused_cast():
     run_workload(w, fused=False, rounds=2)
 
 
+def test_tiny_with_fused_publish_and_fused_reduce():
+    w = synth.WORKLOADS["tiny"]
+    run_workload(w, fused_publish=True)
+    run_workload(w, fused_reduce=True)
+    run_workload(w, fused_publish=True, fused_reduce=True)
+    run_workload(w, comm_bf16=False, fused_reduce=True, rounds=2)
+
+
 def test_ragged_small_shard_with_unequal_counts():
     w = synth.Workload(name="ragged", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
                        k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
     run_workload(w)
+    run_workload(w, fused_publish=True, fused_reduce=True)
 
 
 def test_gpt2_small_scale_shard_ten_rounds():
@@ -135,3 +147,8 @@ def test_seven_billion_scale_shard_five_rounds():
 
 def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
     run_workload(synth.WORKLOADS["7b_hetero"])
+
+
+def test_seven_billion_scale_shard_fused_path_as_benched():
+    # the configuration bench.py times by default: fused publish, fused reduce + step
+    run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, rounds=3)
