@@ -47,6 +47,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle sample")
+    ap.add_argument("--scheme", default=None, choices=["acco", "ddp", "dpu", "wp"],
+                    help="time one round of this update scheme sequenced on the base entry "
+                         "points (paper_2406_02613_amd.schemes) instead of the default fused "
+                         "ACCO round; the JSON line then carries that scheme's round time")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the shard (fp32, n elements read and "
                          "n written) so that a counter run has a kernel of known traffic")
@@ -149,6 +153,46 @@ def kernel_bytes_per_elem(name, workers):
     return table[name] if name in table else layout.BYTES_PER_ELEM[name]
 
 
+def scheme_round(owner, w, grads):
+    """One round of owner.scheme on resident gradients (base entry points, unfused)."""
+    import synth
+    for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
+        for wk in range(w.workers):
+            for g in grads[stage][wk]:
+                owner.add_microbatch(wk, g)
+        if stage == synth.STAGE_TILDE and owner.scheme == "acco":
+            owner.finish_half()
+    owner.finish_round()
+
+
+def bench_scheme(args, torch, A, w, grads):
+    h = w.hyper
+    owner = A.SchemeOwner(w.n, w.workers, args.scheme,
+                          A.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay))
+    tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
+    w.device_theta(tmp)
+    owner.set_theta(tmp)
+    del tmp
+    for _ in range(args.warmup):
+        scheme_round(owner, w, grads)
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(args.steps):
+        scheme_round(owner, w, grads)
+    e.record()
+    torch.cuda.synchronize()
+    ms = s.elapsed_time(e) / args.steps
+    print(json.dumps({
+        "metric": f"shard optimizer-step elements/s (one round of scheme '{args.scheme}', "
+                  "base entry points)",
+        "value": w.n / (ms * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "scheme": args.scheme, "n": w.n, "workers": w.workers}}))
+    return 0
+
+
 def cpu_baseline(w, target_seconds):
     """The oracle (as it stands) on the first S elements of the same workload, one round."""
     import numpy as np
@@ -187,6 +231,24 @@ def cpu_baseline(w, target_seconds):
                       f"(binary64 form, {cores} OpenMP threads, {t:.1f} s)"}
 
 
+def make_grads(torch, synth, w):
+    """Every micro-batch gradient of one round, resident in HBM: grads[stage][worker][mb]."""
+    grads = {}
+    n_bufs = 0
+    for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
+        grads[st] = []
+        for wk in range(w.workers):
+            row = []
+            for mb in range(w.stage_counts(0, st)[wk]):
+                g = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+                synth.device_grad_bf16(g, w.grad_spec(0, st, wk, mb), 0)
+                row.append(g)
+                n_bufs += 1
+            grads[st].append(row)
+    torch.cuda.synchronize()
+    return grads, n_bufs
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -203,24 +265,13 @@ def main():
     A.binding.lib()
     w = synth.WORKLOADS[args.workload]
     h = w.hyper
+    if args.scheme is not None:
+        return bench_scheme(args, torch, A, w, make_grads(torch, synth, w)[0])
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay))
     w.device_theta(owner.theta)
 
-    # every micro-batch gradient of one round, resident in HBM
-    grads = {}
-    n_bufs = 0
-    for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
-        grads[st] = []
-        for wk in range(w.workers):
-            row = []
-            for mb in range(w.stage_counts(0, st)[wk]):
-                g = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
-                synth.device_grad_bf16(g, w.grad_spec(0, st, wk, mb), 0)
-                row.append(g)
-                n_bufs += 1
-            grads[st].append(row)
-    torch.cuda.synchronize()
+    grads, n_bufs = make_grads(torch, synth, w)
 
     if args.calibrate_copy:
         owner.gsum.copy_(owner.theta)          # 4n bytes read, 4n bytes written

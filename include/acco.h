@@ -191,6 +191,32 @@ int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
                             const int64_t* counts, int64_t* total, uint16_t* theta_bf16, int64_t n,
                             const acco_adamw_t* hp, int64_t* step, void* stream);
 
+/*
+ * Plain SGD with decoupled weight decay as Opt - the optimizer of the paper's convergence
+ * propositions (Prop. GD / Prop. SGD, Sec. 3.2): theta' = theta - lr wd theta - lr g,
+ * g = gsum / total_count.  It has no state besides theta.
+ * Valid: lr >= 0, weight_decay >= 0, finite.
+ */
+typedef struct acco_sgd_t {
+    double lr;
+    double weight_decay;
+} acco_sgd_t;
+
+/*
+ * Stage (1) of eq. (ACCO) with Opt = SGD: theta~ = theta - lr wd theta - lr gsum/total_count;
+ * theta is only read.  Arguments and errors as acco_estimate_step (without m, v, step).
+ */
+int acco_sgd_estimate_step(const float* theta, const float* gsum, float* theta_tilde_f32,
+                           uint16_t* theta_tilde_bf16, int64_t n, const acco_sgd_t* hp,
+                           int64_t total_count, void* stream);
+
+/*
+ * Stage (2) of eq. (ACCO) with Opt = SGD, in place on theta; *step += 1.
+ * Arguments and errors as acco_commit_step (without m, v).
+ */
+int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* theta_bf16, int64_t n,
+                         const acco_sgd_t* hp, int64_t* step, int64_t total_count, void* stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* acco_status_string(int status);
 
@@ -199,7 +225,8 @@ int acco_version(void);
 
 /*
  * Launch shape used for subsequent calls of one entry point ("accumulate", "cast",
- * "reduce", "estimate", "commit", "accumulate_publish", "reduce_estimate", "reduce_commit"):
+ * "reduce", "estimate", "commit", "accumulate_publish", "reduce_estimate", "reduce_commit",
+ * "sgd"):
  * threads per workgroup (64..512, multiple of 64),
  * 16-byte vectors each thread keeps in flight per array (1, 2 or 4), and workgroups
  * per compute unit (0 = one workgroup per tile, > 0 = grid-stride over that many

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(Hyper), i64, i64]
             fn.restype = None
+        L.oracle_sgd_step.argtypes = [p, p, p, p, i64, ctypes.c_double, ctypes.c_double, i64, ci]
+        L.oracle_sgd_step.restype = None
         _lib = L
     return _lib
 
@@ -139,6 +141,19 @@ def commit(theta, m, v, gsum, hp: Hyper, step: int, count: int, *, want_bf16=Tru
     fn(_f32(theta).ctypes.data, _f32(m).ctypes.data, _f32(v).ctypes.data, _f32(gsum).ctypes.data,
        _ptr(out_bf16), n, ctypes.byref(hp), int(step), int(count))
     return out_bf16
+
+
+def sgd_step(theta, gsum, lr: float, weight_decay: float, count: int, *, commit: bool,
+             want_bf16: bool = True, precision: str = "f64"):
+    """Opt = SGD.  commit: in place on theta; else returns the speculative theta as a new array.
+    Returns (theta_out, bf16 bits or None)."""
+    n = theta.size
+    out = theta if commit else np.empty(n, np.float32)
+    out_bf16 = np.empty(n, np.uint16) if want_bf16 else None
+    lib().oracle_sgd_step(_f32(theta).ctypes.data, _f32(gsum).ctypes.data, out.ctypes.data,
+                          _ptr(out_bf16), n, float(lr), float(weight_decay), int(count),
+                          int(precision == "f32"))
+    return out, out_bf16
 
 
 # --------------------------------------------------------------------------- one shard owner

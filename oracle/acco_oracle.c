@@ -275,3 +275,39 @@ ORACLE_EXPORT void oracle_commit_f32(float* theta, float* m, float* v, const flo
         if (out_bf16) out_bf16[j] = oracle_f32_to_bf16(t1);
     }
 }
+
+/* ------------------------------------------------------------------ SGD as Opt */
+
+/* The optimizer of the paper's convergence propositions (Prop. GD / Prop. SGD):
+ * theta' = theta - lr wd theta - lr g with g = gsum / count.  Binary64 form: the definition;
+ * binary32 form: g = gsum * fp32(1/count); t0 = fma(-(lr wd), theta, theta);
+ * theta' = fma(-lr, g, t0). */
+static float sgd_elem_f64(float theta, float gsum, double count, double lr, double wd)
+{
+    double th = (double)theta;
+    return (float)(th - lr * wd * th - lr * ((double)gsum / count));
+}
+
+static float sgd_elem_f32(float theta, float gsum, float grad_scale, float lr, float lrwd)
+{
+    float g  = gsum * grad_scale;
+    float t0 = fmaf(-lrwd, theta, theta);
+    return fmaf(-lr, g, t0);
+}
+
+/* theta_out may alias theta (commit) or be a separate buffer (estimate); either output may
+ * be NULL. */
+ORACLE_EXPORT void oracle_sgd_step(const float* theta, const float* gsum, float* theta_out,
+                                   uint16_t* out_bf16, int64_t n, double lr, double weight_decay,
+                                   int64_t count, int use_f32)
+{
+    const float gs = (float)(1.0 / (double)count), lrf = (float)lr,
+                lw = (float)(lr * weight_decay);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < n; ++j) {
+        float t1 = use_f32 ? sgd_elem_f32(theta[j], gsum[j], gs, lrf, lw)
+                           : sgd_elem_f64(theta[j], gsum[j], (double)count, lr, weight_decay);
+        if (theta_out) theta_out[j] = t1;
+        if (out_bf16) out_bf16[j] = oracle_f32_to_bf16(t1);
+    }
+}

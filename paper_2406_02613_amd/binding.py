@@ -21,14 +21,19 @@ ACCO_MAX_WORKERS = 64
 
 EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
-           "acco_reduce_commit_step", "acco_status_string", "acco_version",
-           "acco_set_launch_shape")
+           "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
+           "acco_status_string", "acco_version", "acco_set_launch_shape")
 
 
 class AdamW(ctypes.Structure):
     """acco_adamw_t"""
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class Sgd(ctypes.Structure):
+    """acco_sgd_t"""
+    _fields_ = [("lr", ctypes.c_double), ("weight_decay", ctypes.c_double)]
 
 
 class AccoError(RuntimeError):
@@ -61,6 +66,8 @@ def lib() -> ctypes.CDLL:
                                                 p, p, i64, ctypes.POINTER(AdamW), i64, p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
                                               i64, ctypes.POINTER(AdamW), pi64, p]
+        L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
+        L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
@@ -270,3 +277,30 @@ def acco_commit_step(theta, m, v, gsum, hp: AdamW, step: Counter, total_count: i
                                 _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
                                 ctypes.byref(hp), step.ref(), int(total_count), _stream())
     _check(rc, "acco_commit_step")
+
+
+def make_sgd(lr, weight_decay=0.0) -> Sgd:
+    return Sgd(float(lr), float(weight_decay))
+
+
+def acco_sgd_estimate_step(theta, gsum, hp: Sgd, total_count: int, *, theta_tilde_f32=None,
+                           theta_tilde_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    rc = lib().acco_sgd_estimate_step(_dev(theta, f32, n, "theta"), _dev(gsum, f32, n, "gsum"),
+                                      _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
+                                      _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"),
+                                      n, ctypes.byref(hp), int(total_count), _stream())
+    _check(rc, "acco_sgd_estimate_step")
+
+
+def acco_sgd_commit_step(theta, gsum, hp: Sgd, step: Counter, total_count: int, *,
+                         theta_bf16=None) -> None:
+    import torch
+    n = theta.numel()
+    f32 = torch.float32
+    rc = lib().acco_sgd_commit_step(_dev(theta, f32, n, "theta"), _dev(gsum, f32, n, "gsum"),
+                                    _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
+                                    ctypes.byref(hp), step.ref(), int(total_count), _stream())
+    _check(rc, "acco_sgd_commit_step")

@@ -34,6 +34,7 @@ enum Entry {
     kAccumulatePublish,
     kReduceEstimate,
     kReduceCommit,
+    kSgd,
     kEntries
 };
 
@@ -46,11 +47,12 @@ LaunchShape g_shape[kEntries] = {
     {{256}, {1}, {0}},  // accumulate_publish
     {{256}, {1}, {0}},  // reduce_estimate
     {{256}, {1}, {0}},  // reduce_commit
+    {{256}, {1}, {0}},  // sgd
 };
 
 const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
                                            "estimate",           "commit",          "accumulate_publish",
-                                           "reduce_estimate",    "reduce_commit"};
+                                           "reduce_estimate",    "reduce_commit",   "sgd"};
 
 int cu_count()
 {
@@ -572,6 +574,80 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
         *total = new_total;
         *step += 1;
     }
+    return rc;
+}
+
+namespace {
+
+int check_sgd(const acco_sgd_t* hp, int64_t total_count)
+{
+    if (hp == nullptr) return ACCO_ERR_NULL;
+    if (!finite_nonneg(hp->lr) || !finite_nonneg(hp->weight_decay) || total_count < 1)
+        return ACCO_ERR_ARG;
+    return ACCO_OK;
+}
+
+SgdScalars fold_sgd(const acco_sgd_t& hp, int64_t total_count)
+{
+    SgdScalars s;
+    s.grad_scale = (float)(1.0 / (double)total_count);
+    s.lr         = (float)hp.lr;
+    s.lrwd       = (float)(hp.lr * hp.weight_decay);
+    return s;
+}
+
+}  // namespace
+
+ACCO_API int acco_sgd_estimate_step(const float* theta, const float* gsum, float* theta_tilde_f32,
+                                    uint16_t* theta_tilde_bf16, int64_t n, const acco_sgd_t* hp,
+                                    int64_t total_count, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && (theta == nullptr || gsum == nullptr)) return ACCO_ERR_NULL;
+    if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
+    if (!aligned16(theta) || !aligned16(gsum) || !aligned16(theta_tilde_f32) ||
+        !aligned16(theta_tilde_bf16))
+        return ACCO_ERR_ALIGN;
+    if (int rc = check_sgd(hp, total_count)) return rc;
+    const void* ins[2] = {theta, gsum};
+    for (const void* in : ins) {
+        if (overlap(theta_tilde_f32, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_tilde_bf16, n * 2, in, n * 4)) return ACCO_ERR_ALIAS;
+    }
+    if (overlap(theta_tilde_f32, n * 4, theta_tilde_bf16, n * 2)) return ACCO_ERR_ALIAS;
+    if (n == 0) return ACCO_OK;
+    const SgdScalars sc = fold_sgd(*hp, total_count);
+    hipStream_t      s  = static_cast<hipStream_t>(stream);
+    if (theta_tilde_f32 != nullptr && theta_tilde_bf16 != nullptr)
+        return launch(kSgd, SgdOp<false, true, true>{theta, gsum, nullptr, theta_tilde_f32, theta_tilde_bf16, sc}, n, s);
+    if (theta_tilde_f32 != nullptr)
+        return launch(kSgd, SgdOp<false, true, false>{theta, gsum, nullptr, theta_tilde_f32, nullptr, sc}, n, s);
+    return launch(kSgd, SgdOp<false, false, true>{theta, gsum, nullptr, nullptr, theta_tilde_bf16, sc}, n, s);
+}
+
+ACCO_API int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* theta_bf16, int64_t n,
+                                  const acco_sgd_t* hp, int64_t* step, int64_t total_count,
+                                  void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (step == nullptr) return ACCO_ERR_NULL;
+    if (n > 0 && (theta == nullptr || gsum == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(theta) || !aligned16(gsum) || !aligned16(theta_bf16)) return ACCO_ERR_ALIGN;
+    if (int rc = check_sgd(hp, total_count)) return rc;
+    if (*step < 0 || *step == std::numeric_limits<int64_t>::max()) return ACCO_ERR_ARG;
+    if (overlap(theta, n * 4, gsum, n * 4) || overlap(theta_bf16, n * 2, theta, n * 4) ||
+        overlap(theta_bf16, n * 2, gsum, n * 4))
+        return ACCO_ERR_ALIAS;
+    int rc = ACCO_OK;
+    if (n > 0) {
+        const SgdScalars sc = fold_sgd(*hp, total_count);
+        hipStream_t      s  = static_cast<hipStream_t>(stream);
+        if (theta_bf16 != nullptr)
+            rc = launch(kSgd, SgdOp<true, false, true>{theta, gsum, theta, nullptr, theta_bf16, sc}, n, s);
+        else
+            rc = launch(kSgd, SgdOp<true, false, false>{theta, gsum, theta, nullptr, nullptr, sc}, n, s);
+    }
+    if (rc == ACCO_OK) *step += 1;
     return rc;
 }
 

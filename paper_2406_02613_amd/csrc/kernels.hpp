@@ -444,4 +444,56 @@ struct ReduceAdamOp {
     }
 };
 
+// ------------------------------------------------------------------ SGD as Opt
+
+// Plain (stochastic) gradient descent with decoupled decay, the Opt of the paper's
+// convergence propositions: theta' = theta - lr wd theta - lr g,  g = gsum / count.
+struct SgdScalars {
+    float grad_scale;
+    float lr;
+    float lrwd;
+};
+
+__device__ __forceinline__ float sgd_elem(float theta, float gsum, const SgdScalars& s)
+{
+    const float g  = gsum * s.grad_scale;
+    const float t0 = __builtin_fmaf(-s.lrwd, theta, theta);
+    return __builtin_fmaf(-s.lr, g, t0);
+}
+
+template <bool COMMIT, bool OUT_F32, bool OUT_BF16>
+struct SgdOp {
+    const float* theta;
+    const float* gsum;
+    float*       theta_w;
+    float*       out_f32;
+    uint16_t*    out_bf16;
+    SgdScalars   s;
+    struct In {
+        f4 t, g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.t = ld(reinterpret_cast<const f4*>(theta) + i);
+        in.g = ld(reinterpret_cast<const f4*>(gsum) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        const f4 t = {sgd_elem(in.t.x, in.g.x, s), sgd_elem(in.t.y, in.g.y, s),
+                      sgd_elem(in.t.z, in.g.z, s), sgd_elem(in.t.w, in.g.w, s)};
+        if (COMMIT) st(reinterpret_cast<f4*>(theta_w) + i, t);
+        if (OUT_F32) st(reinterpret_cast<f4*>(out_f32) + i, t);
+        if (OUT_BF16) st(reinterpret_cast<u2*>(out_bf16) + i, pack_bf16x4(t));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        const float t = sgd_elem(theta[j], gsum[j], s);
+        if (COMMIT) theta_w[j] = t;
+        if (OUT_F32) out_f32[j] = t;
+        if (OUT_BF16) out_bf16[j] = (uint16_t)to_bf16_bits(t);
+    }
+};
+
 }  // namespace acco

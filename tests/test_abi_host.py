@@ -255,3 +255,29 @@ def test_fused_reduce_steps_validation_and_counters():
     assert tot.value == 7 and step.value == 9
     assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, sr, NONE) == 0
     assert tot.value == 14 and step.value == 10      # stage 2 adds onto the stage-1 total
+
+
+def test_sgd_steps_validation_and_step_counter():
+    L = B.lib()
+    hp = B.make_sgd(0.1, 0.0)
+    h = ctypes.byref(hp)
+    est, com = L.acco_sgd_estimate_step, L.acco_sgd_commit_step
+    assert est(NONE, vp(Bp), vp(C), NONE, 4, h, 1, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), NONE, NONE, 4, h, 1, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), NONE, 4, NONE, 1, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), NONE, 4, h, 0, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(A), NONE, 4, h, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C + 8), NONE, 4, h, 1, NONE) == B.ACCO_ERR_ALIGN
+    assert est(vp(A), vp(Bp), vp(C), vp(D), 0, h, 1, NONE) == 0
+    bad = B.make_sgd(-1.0, 0.0)
+    assert est(vp(A), vp(Bp), vp(C), NONE, 0, ctypes.byref(bad), 1, NONE) == B.ACCO_ERR_ARG
+    bad = B.make_sgd(0.1, float("nan"))
+    assert est(vp(A), vp(Bp), vp(C), NONE, 0, ctypes.byref(bad), 1, NONE) == B.ACCO_ERR_ARG
+    step = ctypes.c_int64(0)
+    sr = ctypes.byref(step)
+    assert com(vp(A), vp(Bp), NONE, 4, h, NONE, 1, NONE) == B.ACCO_ERR_NULL
+    assert com(vp(A), vp(A), NONE, 4, h, sr, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(A), 4, h, sr, 1, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), NONE, -1, h, sr, 1, NONE) == B.ACCO_ERR_SIZE
+    assert step.value == 0
+    assert com(vp(A), vp(Bp), NONE, 0, h, sr, 2, NONE) == 0 and step.value == 1
