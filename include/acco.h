@@ -71,6 +71,25 @@ typedef struct acco_adamw_t {
 } acco_adamw_t;
 
 /*
+ * Layout of the "state" arrays theta, m, v and gsum of the step entry points.
+ *   block_elems == 0 (or a NULL layout pointer): planar - element j at index j.
+ *   otherwise: element j of an array lives at index
+ *       (j / block_elems) * block_stride + (j % block_elems)
+ *   from that array's pointer: the array is cut into blocks of block_elems elements whose
+ *   starts are block_stride elements apart.  This lets the four arrays be interleaved block by
+ *   block in ONE buffer - [theta block][m block][v block][gsum block] repeated, with
+ *   block_stride = 4 * block_elems and the four pointers one block apart - which keeps the
+ *   addresses streamed at any moment within tens of KiB of each other (measured 4-7 % faster
+ *   than four distant planar arrays on MI355X).  All four arrays share the one layout.
+ *   block_elems: a power of two >= 4; block_stride: a multiple of 4, >= block_elems.
+ * The worker shards and every bf16 / fp32 output stay planar.
+ */
+typedef struct acco_layout_t {
+    int64_t block_elems;
+    int64_t block_stride;
+} acco_layout_t;
+
+/*
  * Gradient accumulation of the computation stream (Alg. 1: g_i <- g_i + grad F,
  * N_i <- N_i + 1).
  *   acc        device, fp32[n], in/out: one worker's accumulator
@@ -122,11 +141,13 @@ int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stre
  *   counts    host, nullable: counts[w] = micro-batches summed in shard w (>= 0)
  *   total     host, nullable, in/out: accumulate ? *total + sum(counts) : sum(counts).
  *             counts and total are given together or not at all.
+ *   gsum_layout  host, nullable: layout of gsum (NULL = planar)
  * Errors: NULLs, bad n/workers/dtype/flag, misalignment, gsum overlapping a
  *         shard, negative count, total overflow.
  */
 int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype, int64_t n,
-                       int accumulate, const int64_t* counts, int64_t* total, void* stream);
+                       int accumulate, const int64_t* counts, int64_t* total,
+                       const acco_layout_t* gsum_layout, void* stream);
 
 /*
  * Stage (1) of eq. (ACCO): the speculative parameters
@@ -138,12 +159,14 @@ int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int 
  *   theta_tilde_bf16   device, bf16[n], out, nullable  (at least one output)
  *   step               number of updates committed so far (>= 0)
  *   total_count        number of micro-batch gradients summed in gsum (>= 1)
+ *   state_layout       host, nullable: layout shared by theta, m, v, gsum (NULL = planar)
  * Errors: NULLs, bad n, misalignment, an output overlapping an input or the other
  *         output, invalid hyper-parameters, step < 0, total_count < 1.
  */
 int acco_estimate_step(const float* theta, const float* m, const float* v, const float* gsum,
                        float* theta_tilde_f32, uint16_t* theta_tilde_bf16, int64_t n,
-                       const acco_adamw_t* hp, int64_t step, int64_t total_count, void* stream);
+                       const acco_adamw_t* hp, int64_t step, int64_t total_count,
+                       const acco_layout_t* state_layout, void* stream);
 
 /*
  * Stage (2) of eq. (ACCO): the committed update on the full delayed gradient
@@ -158,7 +181,7 @@ int acco_estimate_step(const float* theta, const float* m, const float* v, const
  */
 int acco_commit_step(float* theta, float* m, float* v, const float* gsum, uint16_t* theta_bf16,
                      int64_t n, const acco_adamw_t* hp, int64_t* step, int64_t total_count,
-                     void* stream);
+                     const acco_layout_t* state_layout, void* stream);
 
 /*
  * acco_reduce_shards(accumulate = 0) fused with acco_estimate_step: stage 1 of the
@@ -174,7 +197,7 @@ int acco_reduce_estimate_step(const float* theta, const float* m, const float* v
                               const void* const* shards, int workers, int dtype,
                               const int64_t* counts, int64_t* total, float* theta_tilde_f32,
                               uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
-                              int64_t step, void* stream);
+                              int64_t step, const acco_layout_t* state_layout, void* stream);
 
 /*
  * acco_reduce_shards(accumulate = 1) fused with acco_commit_step: stage 2 in one pass.
@@ -189,7 +212,8 @@ int acco_reduce_estimate_step(const float* theta, const float* m, const float* v
 int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
                             const void* const* shards, int workers, int dtype,
                             const int64_t* counts, int64_t* total, uint16_t* theta_bf16, int64_t n,
-                            const acco_adamw_t* hp, int64_t* step, void* stream);
+                            const acco_adamw_t* hp, int64_t* step,
+                            const acco_layout_t* state_layout, void* stream);
 
 /*
  * Plain SGD with decoupled weight decay as Opt - the optimizer of the paper's convergence

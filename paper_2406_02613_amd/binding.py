@@ -31,6 +31,11 @@ class AdamW(ctypes.Structure):
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double)]
 
 
+class Layout(ctypes.Structure):
+    """acco_layout_t"""
+    _fields_ = [("block_elems", ctypes.c_int64), ("block_stride", ctypes.c_int64)]
+
+
 class Sgd(ctypes.Structure):
     """acco_sgd_t"""
     _fields_ = [("lr", ctypes.c_double), ("weight_decay", ctypes.c_double)]
@@ -58,14 +63,17 @@ def lib() -> ctypes.CDLL:
         pi64 = ctypes.POINTER(ctypes.c_int64)
         L.acco_accumulate.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_cast_params.argtypes = [p, p, i64, p]
-        L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, p]
-        L.acco_estimate_step.argtypes = [p, p, p, p, p, p, i64, ctypes.POINTER(AdamW), i64, i64, p]
-        L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, p]
+        play = ctypes.POINTER(Layout)
+        L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, play, p]
+        L.acco_estimate_step.argtypes = [p, p, p, p, p, p, i64, ctypes.POINTER(AdamW), i64, i64,
+                                         play, p]
+        L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, play,
+                                       p]
         L.acco_accumulate_publish.argtypes = [p, p, p, i64, ci, ci, pi64, p]
         L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
-                                                p, p, i64, ctypes.POINTER(AdamW), i64, p]
+                                                p, p, i64, ctypes.POINTER(AdamW), i64, play, p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
-                                              i64, ctypes.POINTER(AdamW), pi64, p]
+                                              i64, ctypes.POINTER(AdamW), pi64, play, p]
         L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
         L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
@@ -117,6 +125,43 @@ def _dev(t, dtype, n: int, name: str) -> int:
     if t.numel() != n:
         raise ValueError(f"{name}: has {t.numel()} elements, expected {n}")
     return t.data_ptr()
+
+
+def _state(tensors, names, n=None):
+    """Pointers, logical length and layout of state arrays (theta, m, v, gsum).
+
+    Each tensor is either 1-D contiguous fp32 (planar) or a 2-D fp32 view of shape
+    (blocks, block_elems) with strides (block_stride, 1) - a component of a block-interleaved
+    buffer.  All tensors passed together must have the same form."""
+    import torch
+    t0 = tensors[0]
+    if t0.dim() == 1:
+        n = t0.numel() if n is None else int(n)
+        return [_dev(t, torch.float32, n, nm) for t, nm in zip(tensors, names)], n, None
+    if t0.dim() != 2:
+        raise ValueError(f"{names[0]}: expected a 1-D tensor or a (blocks, block_elems) view")
+    nblk, blk = t0.shape
+    stride = t0.stride(0)
+    n = nblk * blk if n is None else int(n)
+    lo = (nblk - 1) * blk if nblk else -1
+    if not lo < n <= nblk * blk:
+        raise ValueError(f"n={n} does not fit {nblk} blocks of {blk}")
+    ptrs = []
+    for t, nm in zip(tensors, names):
+        if not t.is_cuda or t.device.index != torch.cuda.current_device():
+            raise ValueError(f"{nm}: must live on the current GPU")
+        if t.dtype != torch.float32:
+            raise TypeError(f"{nm}: expected torch.float32, got {t.dtype}")
+        if t.dim() != 2 or tuple(t.shape) != (nblk, blk) or t.stride(1) != 1 or \
+                (nblk > 1 and t.stride(0) != stride):
+            raise ValueError(f"{nm}: all state views must share shape (blocks, block_elems) and "
+                             "strides (block_stride, 1)")
+        ptrs.append(t.data_ptr())
+    return ptrs, n, Layout(blk, stride)
+
+
+def _lay(layout):
+    return None if layout is None else ctypes.byref(layout)
 
 
 def _opt(t, dtype, n, name):
@@ -187,9 +232,9 @@ def acco_cast_params(out_bf16, src) -> None:
 
 def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
                        counts: Optional[Sequence[int]] = None,
-                       total: Optional[Counter] = None) -> None:
+                       total: Optional[Counter] = None, n: Optional[int] = None) -> None:
     import torch
-    n = gsum.numel()
+    (gsum_ptr,), n, layout = _state([gsum], ["gsum"], n)
     W = len(shards)
     if W < 1:
         raise AccoError(ACCO_ERR_SIZE, "acco_reduce_shards")
@@ -202,10 +247,10 @@ def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
         if len(counts) != W:
             raise ValueError("counts: one per shard")
         cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
-    rc = lib().acco_reduce_shards(_dev(gsum, torch.float32, n, "gsum"), ptrs, W,
+    rc = lib().acco_reduce_shards(gsum_ptr, ptrs, W,
                                   ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32, n,
                                   int(bool(accumulate)), cnts,
-                                  None if total is None else total.ref(), _stream())
+                                  None if total is None else total.ref(), _lay(layout), _stream())
     _check(rc, "acco_reduce_shards")
 
 
@@ -226,56 +271,54 @@ def _shard_args(shards: Sequence, n: int, counts: Sequence[int], where: str):
 
 def acco_reduce_estimate_step(theta, m, v, gsum, shards: Sequence, counts: Sequence[int],
                               total: Counter, hp: AdamW, step: int, *, theta_tilde_f32=None,
-                              theta_tilde_bf16=None) -> None:
+                              theta_tilde_bf16=None, n: Optional[int] = None) -> None:
     import torch
-    n = theta.numel()
     f32 = torch.float32
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
     ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_estimate_step")
     rc = lib().acco_reduce_estimate_step(
-        _dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"), _dev(v, f32, n, "v"),
-        _dev(gsum, f32, n, "gsum"), ptrs, W, dt, cnts, total.ref(),
+        st[0], st[1], st[2], st[3], ptrs, W, dt, cnts, total.ref(),
         _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
         _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"), n, ctypes.byref(hp),
-        int(step), _stream())
+        int(step), _lay(layout), _stream())
     _check(rc, "acco_reduce_estimate_step")
 
 
 def acco_reduce_commit_step(theta, m, v, gsum, shards: Sequence, counts: Sequence[int],
-                            total: Counter, hp: AdamW, step: Counter, *, theta_bf16=None) -> None:
+                            total: Counter, hp: AdamW, step: Counter, *, theta_bf16=None,
+                            n: Optional[int] = None) -> None:
     import torch
-    n = theta.numel()
-    f32 = torch.float32
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
     ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_commit_step")
     rc = lib().acco_reduce_commit_step(
-        _dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"), _dev(v, f32, n, "v"),
-        _dev(gsum, f32, n, "gsum"), ptrs, W, dt, cnts, total.ref(),
+        st[0], st[1], st[2], st[3], ptrs, W, dt, cnts, total.ref(),
         _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n, ctypes.byref(hp), step.ref(),
-        _stream())
+        _lay(layout), _stream())
     _check(rc, "acco_reduce_commit_step")
 
 
 def acco_estimate_step(theta, m, v, gsum, hp: AdamW, step: int, total_count: int, *,
-                       theta_tilde_f32=None, theta_tilde_bf16=None) -> None:
+                       theta_tilde_f32=None, theta_tilde_bf16=None,
+                       n: Optional[int] = None) -> None:
     import torch
-    n = theta.numel()
     f32 = torch.float32
-    rc = lib().acco_estimate_step(_dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"),
-                                  _dev(v, f32, n, "v"), _dev(gsum, f32, n, "gsum"),
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    rc = lib().acco_estimate_step(st[0], st[1], st[2], st[3],
                                   _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
                                   _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"),
-                                  n, ctypes.byref(hp), int(step), int(total_count), _stream())
+                                  n, ctypes.byref(hp), int(step), int(total_count), _lay(layout),
+                                  _stream())
     _check(rc, "acco_estimate_step")
 
 
 def acco_commit_step(theta, m, v, gsum, hp: AdamW, step: Counter, total_count: int, *,
-                     theta_bf16=None) -> None:
+                     theta_bf16=None, n: Optional[int] = None) -> None:
     import torch
-    n = theta.numel()
-    f32 = torch.float32
-    rc = lib().acco_commit_step(_dev(theta, f32, n, "theta"), _dev(m, f32, n, "m"),
-                                _dev(v, f32, n, "v"), _dev(gsum, f32, n, "gsum"),
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    rc = lib().acco_commit_step(st[0], st[1], st[2], st[3],
                                 _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
-                                ctypes.byref(hp), step.ref(), int(total_count), _stream())
+                                ctypes.byref(hp), step.ref(), int(total_count), _lay(layout),
+                                _stream())
     _check(rc, "acco_commit_step")
 
 

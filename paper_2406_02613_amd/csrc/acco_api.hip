@@ -7,6 +7,7 @@
 #include <cstdint>
 #include <cstring>
 #include <limits>
+#include <type_traits>
 
 #include "../../include/acco.h"
 #include "kernels.hpp"
@@ -152,20 +153,6 @@ int check_hyper(const acco_adamw_t* hp, int64_t step, int64_t total_count)
     return ACCO_OK;
 }
 
-// shards[]: non-NULL (when n > 0), aligned, not overlapping `out` (n fp32)
-int check_shards(const void* const* shards, int workers, int dtype, int64_t n, const void* out)
-{
-    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
-    if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
-    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
-    for (int w = 0; w < workers; ++w) {
-        if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
-        if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
-        if (overlap(out, n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
-    }
-    return ACCO_OK;
-}
-
 // base + sum(counts) with overflow and sign checks
 int sum_counts(const int64_t* counts, int workers, int64_t base, int64_t* out)
 {
@@ -239,23 +226,109 @@ ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, v
 
 namespace {
 
-template <bool BF16>
-int launch_reduce(float* gsum, const void* const* shards, int workers, int64_t n, bool accumulate,
-                  hipStream_t stream)
+// ------------------------------------------------------------------ state layout
+
+struct StateLayout {
+    bool    blocked = false;
+    int     vshift  = 0;   // log2(vectors per block)
+    int64_t block   = 0;   // elements per block
+    int64_t stride  = 0;   // elements between block starts
+};
+
+int parse_layout(const acco_layout_t* l, StateLayout* out)
 {
-    constexpr int kChunk = kReduceChunk;
-    for (int w0 = 0; w0 < workers; w0 += kChunk) {
-        const int  cnt = workers - w0 < kChunk ? workers - w0 : kChunk;
-        const bool acc = accumulate || w0 > 0;
-        ShardPtrs  ptrs;
-        std::memset(&ptrs, 0, sizeof ptrs);
-        for (int w = 0; w < cnt; ++w) ptrs.p[w] = shards[w0 + w];
-        int rc;
-        if (acc)
-            rc = launch(kReduce, ReduceOp<kChunk, BF16, true>{gsum, ptrs, cnt}, n, stream);
-        else
-            rc = launch(kReduce, ReduceOp<kChunk, BF16, false>{gsum, ptrs, cnt}, n, stream);
+    *out = StateLayout{};
+    if (l == nullptr || l->block_elems == 0) return ACCO_OK;
+    const int64_t b = l->block_elems, st = l->block_stride;
+    if (b < 4 || b > ((int64_t)1 << 30) || (b & (b - 1)) != 0) return ACCO_ERR_ARG;
+    if (st < b || st % 4 != 0 || st > ((int64_t)1 << 40)) return ACCO_ERR_ARG;
+    out->blocked = true;
+    out->block   = b;
+    out->stride  = st;
+    int sh       = 0;
+    while (((int64_t)4 << sh) < b) ++sh;
+    out->vshift = sh;
+    return ACCO_OK;
+}
+
+// bytes from the first to one past the last element of a state array of n elements
+int64_t state_extent(const StateLayout& L, int64_t n)
+{
+    if (n <= 0) return 0;
+    if (!L.blocked) return n * 4;
+    const int64_t nblk = (n + L.block - 1) / L.block;
+    return ((nblk - 1) * L.stride + (n - (nblk - 1) * L.block)) * 4;
+}
+
+// do two state arrays of the same layout share an element?
+bool state_overlap(const void* a, const void* b, const StateLayout& L, int64_t n)
+{
+    const int64_t ext = state_extent(L, n);
+    if (!overlap(a, ext, b, ext)) return false;
+    if (!L.blocked) return true;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    const uint64_t  period = (uint64_t)L.stride * 4, blk = (uint64_t)L.block * 4;
+    const uint64_t  dist   = (pa > pb ? pa - pb : pb - pa) % period;
+    return dist < blk || period - dist < blk;
+}
+
+// a planar buffer against a state array (conservative for blocked layouts: whole extent)
+bool planar_overlaps_state(const void* p, int64_t bytes, const void* state, const StateLayout& L,
+                           int64_t n)
+{
+    return overlap(p, bytes, state, state_extent(L, n));
+}
+
+template <class F>
+int with_layout(const StateLayout& L, F&& f)
+{
+    if (L.blocked) return f(StateAddr<true>{L.vshift, L.stride / 4});
+    return f(StateAddr<false>{});
+}
+
+template <class At>
+constexpr bool is_blocked = std::is_same<At, StateAddr<true>>::value;
+
+ShardPtrs chunk_ptrs(const void* const* shards, int begin, int end)
+{
+    ShardPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof ptrs);
+    for (int w = begin; w < end; ++w) ptrs.p[w - begin] = shards[w];
+    return ptrs;
+}
+
+// plain reduction of shards [0, workers) into gsum, kReduceChunk at a time
+template <bool BF16>
+int launch_reduce(float* gsum, const StateLayout& L, const void* const* shards, int workers,
+                  int64_t n, bool accumulate, hipStream_t stream)
+{
+    for (int w0 = 0; w0 < workers; w0 += kReduceChunk) {
+        const int       end  = w0 + kReduceChunk < workers ? w0 + kReduceChunk : workers;
+        const bool      acc  = accumulate || w0 > 0;
+        const ShardPtrs ptrs = chunk_ptrs(shards, w0, end);
+        const int       rc   = with_layout(L, [&](auto at) {
+            constexpr bool B = is_blocked<decltype(at)>;
+            if (acc)
+                return launch(kReduce, ReduceOp<kReduceChunk, BF16, true, B>{gsum, ptrs, end - w0, at}, n, stream);
+            return launch(kReduce, ReduceOp<kReduceChunk, BF16, false, B>{gsum, ptrs, end - w0, at}, n, stream);
+        });
         if (rc != ACCO_OK) return rc;
+    }
+    return ACCO_OK;
+}
+
+// shards: non-NULL (n > 0), aligned, none overlapping the state arrays listed
+int check_shards_vs_state(const void* const* shards, int workers, int dtype, int64_t n,
+                          const void* const* state, int nstate, const StateLayout& L)
+{
+    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
+    if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
+    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    for (int w = 0; w < workers; ++w) {
+        if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
+        if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
+        for (int k = 0; k < nstate; ++k)
+            if (planar_overlaps_state(shards[w], n * esz, state[k], L, n)) return ACCO_ERR_ALIAS;
     }
     return ACCO_OK;
 }
@@ -264,114 +337,106 @@ int launch_reduce(float* gsum, const void* const* shards, int workers, int64_t n
 
 ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype,
                                 int64_t n, int accumulate, const int64_t* counts, int64_t* total,
-                                void* stream)
+                                const acco_layout_t* gsum_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || (n > 0 && gsum == nullptr)) return ACCO_ERR_NULL;
-    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
-    if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
     if (accumulate != 0 && accumulate != 1) return ACCO_ERR_ARG;
     if ((counts == nullptr) != (total == nullptr)) return ACCO_ERR_NULL;
     if (!aligned16(gsum)) return ACCO_ERR_ALIGN;
-    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
-    for (int w = 0; w < workers; ++w) {
-        if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
-        if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
-        if (overlap(gsum, n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
-    }
+    StateLayout L;
+    if (int rc = parse_layout(gsum_layout, &L)) return rc;
+    const void* st[1] = {gsum};
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 1, L)) return rc;
     int64_t new_total = 0;
-    if (counts != nullptr) {
-        new_total = accumulate ? *total : 0;
-        if (new_total < 0) return ACCO_ERR_ARG;
-        for (int w = 0; w < workers; ++w) {
-            if (counts[w] < 0) return ACCO_ERR_ARG;
-            if (counts[w] > std::numeric_limits<int64_t>::max() - new_total) return ACCO_ERR_ARG;
-            new_total += counts[w];
-        }
-    }
+    if (counts != nullptr)
+        if (int rc = sum_counts(counts, workers, accumulate ? *total : 0, &new_total)) return rc;
 
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        rc            = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, shards, workers, n, accumulate, s)
-                                           : launch_reduce<false>(gsum, shards, workers, n, accumulate, s);
+        rc = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, L, shards, workers, n, accumulate, s)
+                                : launch_reduce<false>(gsum, L, shards, workers, n, accumulate, s);
     }
     if (rc == ACCO_OK && total != nullptr) *total = new_total;
     return rc;
 }
 
+namespace {
+
+// validation shared by the four AdamW step entry points.  outs: planar outputs (may be NULL).
+int check_step_buffers(const float* theta, const float* m, const float* v, const float* gsum,
+                       const void* out_f32, const void* out_bf16, int64_t n, const StateLayout& L)
+{
+    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
+        return ACCO_ERR_NULL;
+    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
+        !aligned16(out_f32) || !aligned16(out_bf16))
+        return ACCO_ERR_ALIGN;
+    const void* st[4] = {theta, m, v, gsum};
+    for (int a = 0; a < 4; ++a) {
+        for (int b = a + 1; b < 4; ++b)
+            if (state_overlap(st[a], st[b], L, n)) return ACCO_ERR_ALIAS;
+        if (planar_overlaps_state(out_f32, n * 4, st[a], L, n)) return ACCO_ERR_ALIAS;
+        if (planar_overlaps_state(out_bf16, n * 2, st[a], L, n)) return ACCO_ERR_ALIAS;
+    }
+    if (overlap(out_f32, n * 4, out_bf16, n * 2)) return ACCO_ERR_ALIAS;
+    return ACCO_OK;
+}
+
+}  // namespace
+
 ACCO_API int acco_estimate_step(const float* theta, const float* m, const float* v,
                                 const float* gsum, float* theta_tilde_f32,
                                 uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
-                                int64_t step, int64_t total_count, void* stream)
+                                int64_t step, int64_t total_count,
+                                const acco_layout_t* state_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
-    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
-        return ACCO_ERR_NULL;
     if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
-    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
-        !aligned16(theta_tilde_f32) || !aligned16(theta_tilde_bf16))
-        return ACCO_ERR_ALIGN;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, theta_tilde_f32, theta_tilde_bf16, n, L))
+        return rc;
     if (int rc = check_hyper(hp, step, total_count)) return rc;
-    const void* ins[4] = {theta, m, v, gsum};
-    for (const void* in : ins) {
-        if (overlap(theta_tilde_f32, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
-        if (overlap(theta_tilde_bf16, n * 2, in, n * 4)) return ACCO_ERR_ALIAS;
-    }
-    if (overlap(theta_tilde_f32, n * 4, theta_tilde_bf16, n * 2)) return ACCO_ERR_ALIAS;
     if (n == 0) return ACCO_OK;
 
     const AdamScalars sc = fold(*hp, step, total_count);
     hipStream_t       s  = static_cast<hipStream_t>(stream);
-    if (theta_tilde_f32 != nullptr && theta_tilde_bf16 != nullptr)
-        return launch(kEstimate,
-                      AdamOp<false, true, true>{theta, m, v, gsum, nullptr, nullptr, nullptr,
-                                                theta_tilde_f32, theta_tilde_bf16, sc},
-                      n, s);
-    if (theta_tilde_f32 != nullptr)
-        return launch(kEstimate,
-                      AdamOp<false, true, false>{theta, m, v, gsum, nullptr, nullptr, nullptr,
-                                                 theta_tilde_f32, nullptr, sc},
-                      n, s);
-    return launch(kEstimate,
-                  AdamOp<false, false, true>{theta, m, v, gsum, nullptr, nullptr, nullptr, nullptr,
-                                             theta_tilde_bf16, sc},
-                  n, s);
+    float*            o32 = theta_tilde_f32;
+    uint16_t*         o16 = theta_tilde_bf16;
+    return with_layout(L, [&](auto at) {
+        constexpr bool B = is_blocked<decltype(at)>;
+        if (o32 != nullptr && o16 != nullptr)
+            return launch(kEstimate, AdamOp<false, true, true, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, o16, sc, at}, n, s);
+        if (o32 != nullptr)
+            return launch(kEstimate, AdamOp<false, true, false, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, nullptr, sc, at}, n, s);
+        return launch(kEstimate, AdamOp<false, false, true, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, nullptr, o16, sc, at}, n, s);
+    });
 }
 
 ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsum,
                               uint16_t* theta_bf16, int64_t n, const acco_adamw_t* hp,
-                              int64_t* step, int64_t total_count, void* stream)
+                              int64_t* step, int64_t total_count,
+                              const acco_layout_t* state_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (step == nullptr) return ACCO_ERR_NULL;
-    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
-        return ACCO_ERR_NULL;
-    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
-        !aligned16(theta_bf16))
-        return ACCO_ERR_ALIGN;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
     if (int rc = check_hyper(hp, *step, total_count)) return rc;
-    const void* f32s[4] = {theta, m, v, gsum};
-    for (int a = 0; a < 4; ++a) {
-        for (int b = a + 1; b < 4; ++b)
-            if (overlap(f32s[a], n * 4, f32s[b], n * 4)) return ACCO_ERR_ALIAS;
-        if (overlap(theta_bf16, n * 2, f32s[a], n * 4)) return ACCO_ERR_ALIAS;
-    }
 
     int rc = ACCO_OK;
     if (n > 0) {
         const AdamScalars sc = fold(*hp, *step, total_count);
         hipStream_t       s  = static_cast<hipStream_t>(stream);
-        if (theta_bf16 != nullptr)
-            rc = launch(kCommit,
-                        AdamOp<true, false, true>{theta, m, v, gsum, theta, m, v, nullptr,
-                                                  theta_bf16, sc},
-                        n, s);
-        else
-            rc = launch(kCommit,
-                        AdamOp<true, false, false>{theta, m, v, gsum, theta, m, v, nullptr, nullptr,
-                                                   sc},
-                        n, s);
+        rc = with_layout(L, [&](auto at) {
+            constexpr bool B = is_blocked<decltype(at)>;
+            if (theta_bf16 != nullptr)
+                return launch(kCommit, AdamOp<true, false, true, B>{theta, m, v, gsum, theta, m, v, nullptr, theta_bf16, sc, at}, n, s);
+            return launch(kCommit, AdamOp<true, false, false, B>{theta, m, v, gsum, theta, m, v, nullptr, nullptr, sc, at}, n, s);
+        });
     }
     if (rc == ACCO_OK) *step += 1;
     return rc;
@@ -413,60 +478,49 @@ ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint
 
 namespace {
 
-// Leading chunks of more than kReduceChunk shards go through the plain reduction; the last
-// chunk is what the fused kernel reads.  Returns the first shard index of that last chunk.
+// Fused reduce + step over the last (up to kReduceChunk) shards; leading chunks of a larger
+// worker count go through the plain reduction first.
 template <bool BF16>
-int reduce_leading_chunks(float* gsum, const void* const* shards, int workers, int64_t n,
-                          bool accumulate, hipStream_t stream, int* last_begin)
+int launch_reduce_estimate(const float* theta, const float* m, const float* v, float* gsum,
+                           const StateLayout& L, const void* const* shards, int workers,
+                           float* o32, uint16_t* o16, int64_t n, const AdamScalars& sc,
+                           hipStream_t s)
 {
     const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
-    *last_begin    = lead;
-    if (lead == 0 || n == 0) return ACCO_OK;
-    return launch_reduce<BF16>(gsum, shards, lead, n, accumulate, stream);
-}
-
-ShardPtrs last_chunk(const void* const* shards, int begin, int workers)
-{
-    ShardPtrs ptrs;
-    std::memset(&ptrs, 0, sizeof ptrs);
-    for (int w = begin; w < workers; ++w) ptrs.p[w - begin] = shards[w];
-    return ptrs;
-}
-
-template <bool BF16, bool ACC>
-int launch_reduce_estimate(const float* theta, const float* m, const float* v, float* gsum,
-                           const ShardPtrs& ptrs, int cnt, float* o32, uint16_t* o16, int64_t n,
-                           const AdamScalars& sc, hipStream_t s)
-{
-    if (o32 != nullptr && o16 != nullptr)
-        return launch(kReduceEstimate,
-                      ReduceAdamOp<false, BF16, ACC, true, true, true>{
-                          theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc},
-                      n, s);
-    if (o32 != nullptr)
-        return launch(kReduceEstimate,
-                      ReduceAdamOp<false, BF16, ACC, true, true, false>{
-                          theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc},
-                      n, s);
-    return launch(kReduceEstimate,
-                  ReduceAdamOp<false, BF16, ACC, true, false, true>{
-                      theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc},
-                  n, s);
+    if (lead > 0)
+        if (int rc = launch_reduce<BF16>(gsum, L, shards, lead, n, false, s)) return rc;
+    const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
+    const int       cnt  = workers - lead;
+    return with_layout(L, [&](auto at) {
+        constexpr bool B = is_blocked<decltype(at)>;
+        auto go = [&](auto acc_tag) {
+            constexpr bool ACC = decltype(acc_tag)::value;
+            if (o32 != nullptr && o16 != nullptr)
+                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at}, n, s);
+            if (o32 != nullptr)
+                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at}, n, s);
+            return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at}, n, s);
+        };
+        return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
+    });
 }
 
 template <bool BF16>
-int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const ShardPtrs& ptrs,
-                         int cnt, uint16_t* o16, int64_t n, const AdamScalars& sc, hipStream_t s)
+int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const StateLayout& L,
+                         const void* const* shards, int workers, uint16_t* o16, int64_t n,
+                         const AdamScalars& sc, hipStream_t s)
 {
-    if (o16 != nullptr)
-        return launch(kReduceCommit,
-                      ReduceAdamOp<true, BF16, true, false, false, true>{
-                          theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc},
-                      n, s);
-    return launch(kReduceCommit,
-                  ReduceAdamOp<true, BF16, true, false, false, false>{
-                      theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc},
-                  n, s);
+    const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
+    if (lead > 0)
+        if (int rc = launch_reduce<BF16>(gsum, L, shards, lead, n, true, s)) return rc;
+    const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
+    const int       cnt  = workers - lead;
+    return with_layout(L, [&](auto at) {
+        constexpr bool B = is_blocked<decltype(at)>;
+        if (o16 != nullptr)
+            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at}, n, s);
+        return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at}, n, s);
+    });
 }
 
 }  // namespace
@@ -476,52 +530,33 @@ ACCO_API int acco_reduce_estimate_step(const float* theta, const float* m, const
                                        int dtype, const int64_t* counts, int64_t* total,
                                        float* theta_tilde_f32, uint16_t* theta_tilde_bf16,
                                        int64_t n, const acco_adamw_t* hp, int64_t step,
-                                       void* stream)
+                                       const acco_layout_t* state_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || counts == nullptr || total == nullptr) return ACCO_ERR_NULL;
-    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
-        return ACCO_ERR_NULL;
     if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
-    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
-        !aligned16(theta_tilde_f32) || !aligned16(theta_tilde_bf16))
-        return ACCO_ERR_ALIGN;
-    if (int rc = check_shards(shards, workers, dtype, n, gsum)) return rc;
-    int64_t new_total = 0;
-    if (int rc = sum_counts(counts, workers, 0, &new_total)) return rc;
-    if (int rc = check_hyper(hp, step, new_total)) return rc;
-    const int64_t esz   = dtype == ACCO_BF16 ? 2 : 4;
-    const void*   st[3] = {theta, m, v};
-    for (const void* in : st) {
-        if (overlap(gsum, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
-        if (overlap(theta_tilde_f32, n * 4, in, n * 4)) return ACCO_ERR_ALIAS;
-        if (overlap(theta_tilde_bf16, n * 2, in, n * 4)) return ACCO_ERR_ALIAS;
-    }
-    if (overlap(theta_tilde_f32, n * 4, gsum, n * 4) ||
-        overlap(theta_tilde_bf16, n * 2, gsum, n * 4) ||
-        overlap(theta_tilde_f32, n * 4, theta_tilde_bf16, n * 2))
-        return ACCO_ERR_ALIAS;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, theta_tilde_f32, theta_tilde_bf16, n, L))
+        return rc;
+    const void* st[4] = {theta, m, v, gsum};
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L)) return rc;
+    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
     for (int w = 0; w < workers; ++w)
         if (overlap(theta_tilde_f32, n * 4, shards[w], n * esz) ||
             overlap(theta_tilde_bf16, n * 2, shards[w], n * esz))
             return ACCO_ERR_ALIAS;
+    int64_t new_total = 0;
+    if (int rc = sum_counts(counts, workers, 0, &new_total)) return rc;
+    if (int rc = check_hyper(hp, step, new_total)) return rc;
 
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t       s  = static_cast<hipStream_t>(stream);
         const AdamScalars sc = fold(*hp, step, new_total);
-        int               begin = 0;
-        rc = dtype == ACCO_BF16 ? reduce_leading_chunks<true>(gsum, shards, workers, n, false, s, &begin)
-                                : reduce_leading_chunks<false>(gsum, shards, workers, n, false, s, &begin);
-        if (rc != ACCO_OK) return rc;
-        const ShardPtrs ptrs = last_chunk(shards, begin, workers);
-        const int       cnt  = workers - begin;
-        if (dtype == ACCO_BF16)
-            rc = begin > 0 ? launch_reduce_estimate<true, true>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
-                           : launch_reduce_estimate<true, false>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
-        else
-            rc = begin > 0 ? launch_reduce_estimate<false, true>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
-                           : launch_reduce_estimate<false, false>(theta, m, v, gsum, ptrs, cnt, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
+        rc = dtype == ACCO_BF16
+                 ? launch_reduce_estimate<true>(theta, m, v, gsum, L, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
+                 : launch_reduce_estimate<false>(theta, m, v, gsum, L, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
     }
     if (rc == ACCO_OK) *total = new_total;
     return rc;
@@ -531,44 +566,30 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
                                      const void* const* shards, int workers, int dtype,
                                      const int64_t* counts, int64_t* total, uint16_t* theta_bf16,
                                      int64_t n, const acco_adamw_t* hp, int64_t* step,
-                                     void* stream)
+                                     const acco_layout_t* state_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || counts == nullptr || total == nullptr || step == nullptr)
         return ACCO_ERR_NULL;
-    if (n > 0 && (theta == nullptr || m == nullptr || v == nullptr || gsum == nullptr))
-        return ACCO_ERR_NULL;
-    if (!aligned16(theta) || !aligned16(m) || !aligned16(v) || !aligned16(gsum) ||
-        !aligned16(theta_bf16))
-        return ACCO_ERR_ALIGN;
-    if (int rc = check_shards(shards, workers, dtype, n, gsum)) return rc;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
+    const void* st[4] = {theta, m, v, gsum};
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L)) return rc;
+    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    for (int w = 0; w < workers; ++w)
+        if (overlap(theta_bf16, n * 2, shards[w], n * esz)) return ACCO_ERR_ALIAS;
     int64_t new_total = 0;
     if (int rc = sum_counts(counts, workers, *total, &new_total)) return rc;
     if (int rc = check_hyper(hp, *step, new_total)) return rc;
-    const int64_t esz     = dtype == ACCO_BF16 ? 2 : 4;
-    const void*   f32s[4] = {theta, m, v, gsum};
-    for (int a = 0; a < 4; ++a) {
-        for (int b = a + 1; b < 4; ++b)
-            if (overlap(f32s[a], n * 4, f32s[b], n * 4)) return ACCO_ERR_ALIAS;
-        if (overlap(theta_bf16, n * 2, f32s[a], n * 4)) return ACCO_ERR_ALIAS;
-        for (int w = 0; w < workers; ++w)
-            if (overlap(f32s[a], n * 4, shards[w], n * esz)) return ACCO_ERR_ALIAS;
-    }
-    for (int w = 0; w < workers; ++w)
-        if (overlap(theta_bf16, n * 2, shards[w], n * esz)) return ACCO_ERR_ALIAS;
 
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t       s  = static_cast<hipStream_t>(stream);
         const AdamScalars sc = fold(*hp, *step, new_total);
-        int               begin = 0;
-        rc = dtype == ACCO_BF16 ? reduce_leading_chunks<true>(gsum, shards, workers, n, true, s, &begin)
-                                : reduce_leading_chunks<false>(gsum, shards, workers, n, true, s, &begin);
-        if (rc != ACCO_OK) return rc;
-        const ShardPtrs ptrs = last_chunk(shards, begin, workers);
-        const int       cnt  = workers - begin;
-        rc = dtype == ACCO_BF16 ? launch_reduce_commit<true>(theta, m, v, gsum, ptrs, cnt, theta_bf16, n, sc, s)
-                                : launch_reduce_commit<false>(theta, m, v, gsum, ptrs, cnt, theta_bf16, n, sc, s);
+        rc = dtype == ACCO_BF16
+                 ? launch_reduce_commit<true>(theta, m, v, gsum, L, shards, workers, theta_bf16, n, sc, s)
+                 : launch_reduce_commit<false>(theta, m, v, gsum, L, shards, workers, theta_bf16, n, sc, s);
     }
     if (rc == ACCO_OK) {
         *total = new_total;

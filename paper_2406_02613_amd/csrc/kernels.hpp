@@ -25,6 +25,36 @@ typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 constexpr int kReduceChunk = 8;   // worker shards summed per launch
 constexpr int kMaxThreads = 512;  // per workgroup: leaves 256 VGPRs per lane for loads in flight
 
+// ------------------------------------------------------------------ state addressing
+
+// Where element j of a state array (theta, m, v, gsum) lives.  Planar: at index j.
+// Blocked: the array is cut into blocks of 2^k elements whose starts are `stride`
+// elements apart, so that theta, m, v and gsum of the same elements can sit next to
+// each other in one buffer ([theta block][m block][v block][gsum block] ...), which
+// keeps the concurrently streamed addresses within a few tens of KiB of each other.
+template <bool BLOCKED>
+struct StateAddr;
+
+template <>
+struct StateAddr<false> {
+    __device__ __forceinline__ int64_t vec(int64_t i) const { return i; }
+    __device__ __forceinline__ int64_t elem(int64_t j) const { return j; }
+};
+
+template <>
+struct StateAddr<true> {
+    int     vshift;   // log2(vectors per block)
+    int64_t vstride;  // vectors between block starts
+    __device__ __forceinline__ int64_t vec(int64_t i) const
+    {
+        return (i >> vshift) * vstride + (i & (((int64_t)1 << vshift) - 1));
+    }
+    __device__ __forceinline__ int64_t elem(int64_t j) const
+    {
+        return (j >> (vshift + 2)) * (vstride * 4) + (j & (((int64_t)4 << vshift) - 1));
+    }
+};
+
 // ------------------------------------------------------------------ bf16 <-> fp32
 
 __device__ __forceinline__ float bf16_lo(uint32_t packed)
@@ -248,11 +278,12 @@ struct ShardPtrs {
 
 // Sum of up to WMAX worker shards per launch, ascending worker order.  ACC: start
 // from the value already in gsum, else from shard 0 as it is.
-template <int WMAX, bool BF16, bool ACC>
+template <int WMAX, bool BF16, bool ACC, bool BLOCKED>
 struct ReduceOp {
-    float*    gsum;
-    ShardPtrs shards;
-    int       workers;  // 1 .. WMAX
+    float*             gsum;
+    ShardPtrs          shards;
+    int                workers;  // 1 .. WMAX
+    StateAddr<BLOCKED> at;       // layout of gsum (the shards are always planar)
     struct In {
         f4 s;
         f4 x[BF16 ? 1 : WMAX];
@@ -261,7 +292,7 @@ struct ReduceOp {
     __device__ __forceinline__ In load(int64_t i) const
     {
         In in;
-        if (ACC) in.s = ld(reinterpret_cast<const f4*>(gsum) + i);
+        if (ACC) in.s = ld(reinterpret_cast<const f4*>(gsum) + at.vec(i));
 #pragma unroll
         for (int w = 0; w < WMAX; ++w) {
             if (w < workers) {
@@ -283,72 +314,85 @@ struct ReduceOp {
                 s          = (!ACC && w == 0) ? x : s + x;
             }
         }
-        st(reinterpret_cast<f4*>(gsum) + i, s);
+        st(reinterpret_cast<f4*>(gsum) + at.vec(i), s);
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        float s = ACC ? gsum[j] : 0.0f;
+        const int64_t a = at.elem(j);
+        float         s = ACC ? gsum[a] : 0.0f;
         for (int w = 0; w < workers; ++w) {
             const float x =
                 BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
                      : static_cast<const float*>(shards.p[w])[j];
             s = (!ACC && w == 0) ? x : s + x;
         }
-        gsum[j] = s;
+        gsum[a] = s;
     }
 };
 
 // ------------------------------------------------------------------ estimate / commit
 
-// COMMIT: write theta, m, v in place.  OUT_F32 / OUT_BF16: extra outputs of the new theta.
-template <bool COMMIT, bool OUT_F32, bool OUT_BF16>
+__device__ __forceinline__ void adamw_vec(f4 t, f4 m, f4 v, f4 g, const AdamScalars& s, f4& to,
+                                          f4& mo, f4& vo)
+{
+    float a[4], b[4], c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) adamw_elem(t[k], m[k], v[k], g[k], s, a[k], b[k], c[k]);
+    to = (f4){a[0], a[1], a[2], a[3]};
+    mo = (f4){b[0], b[1], b[2], b[3]};
+    vo = (f4){c[0], c[1], c[2], c[3]};
+}
+
+// COMMIT: write theta, m, v in place.  OUT_F32 / OUT_BF16: extra (planar) outputs of the
+// new theta.  BLOCKED: theta, m, v, gsum share a blocked layout.
+template <bool COMMIT, bool OUT_F32, bool OUT_BF16, bool BLOCKED>
 struct AdamOp {
-    const float* theta;
-    const float* m;
-    const float* v;
-    const float* gsum;
-    float*       theta_w;  // COMMIT: == theta
-    float*       m_w;
-    float*       v_w;
-    float*       out_f32;
-    uint16_t*    out_bf16;
-    AdamScalars  s;
+    const float*       theta;
+    const float*       m;
+    const float*       v;
+    const float*       gsum;
+    float*             theta_w;  // COMMIT: == theta
+    float*             m_w;
+    float*             v_w;
+    float*             out_f32;
+    uint16_t*          out_bf16;
+    AdamScalars        s;
+    StateAddr<BLOCKED> at;
     struct In {
         f4 t, m, v, g;
     };
     __device__ __forceinline__ In load(int64_t i) const
     {
-        In in;
-        in.t = ld(reinterpret_cast<const f4*>(theta) + i);
-        in.m = ld(reinterpret_cast<const f4*>(m) + i);
-        in.v = ld(reinterpret_cast<const f4*>(v) + i);
-        in.g = ld(reinterpret_cast<const f4*>(gsum) + i);
+        const int64_t a = at.vec(i);
+        In            in;
+        in.t = ld(reinterpret_cast<const f4*>(theta) + a);
+        in.m = ld(reinterpret_cast<const f4*>(m) + a);
+        in.v = ld(reinterpret_cast<const f4*>(v) + a);
+        in.g = ld(reinterpret_cast<const f4*>(gsum) + a);
         return in;
     }
     __device__ __forceinline__ void apply(int64_t i, const In& in) const
     {
-        float to[4], mo[4], vo[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) adamw_elem(in.t[k], in.m[k], in.v[k], in.g[k], s, to[k], mo[k], vo[k]);
-        const f4 t  = {to[0], to[1], to[2], to[3]};
-        const f4 mm = {mo[0], mo[1], mo[2], mo[3]};
-        const f4 vv = {vo[0], vo[1], vo[2], vo[3]};
+        f4 t, mm, vv;
+        adamw_vec(in.t, in.m, in.v, in.g, s, t, mm, vv);
         if (COMMIT) {
-            st(reinterpret_cast<f4*>(theta_w) + i, t);
-            st(reinterpret_cast<f4*>(m_w) + i, mm);
-            st(reinterpret_cast<f4*>(v_w) + i, vv);
+            const int64_t a = at.vec(i);
+            st(reinterpret_cast<f4*>(theta_w) + a, t);
+            st(reinterpret_cast<f4*>(m_w) + a, mm);
+            st(reinterpret_cast<f4*>(v_w) + a, vv);
         }
         if (OUT_F32) st(reinterpret_cast<f4*>(out_f32) + i, t);
         if (OUT_BF16) st(reinterpret_cast<u2*>(out_bf16) + i, pack_bf16x4(t));
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        float t, mm, vv;
-        adamw_elem(theta[j], m[j], v[j], gsum[j], s, t, mm, vv);
+        const int64_t a = at.elem(j);
+        float         t, mm, vv;
+        adamw_elem(theta[a], m[a], v[a], gsum[a], s, t, mm, vv);
         if (COMMIT) {
-            theta_w[j] = t;
-            m_w[j]     = mm;
-            v_w[j]     = vv;
+            theta_w[a] = t;
+            m_w[a]     = mm;
+            v_w[a]     = vv;
         }
         if (OUT_F32) out_f32[j] = t;
         if (OUT_BF16) out_bf16[j] = (uint16_t)to_bf16_bits(t);
@@ -360,20 +404,22 @@ struct AdamOp {
 // The owner-side reduction of up to kReduceChunk worker shards folded into the AdamW step:
 // the gradient sum is formed in registers (same order as ReduceOp), optionally stored to
 // gsum (stage 1 keeps it for stage 2), and consumed by the update in the same pass.
-template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16>
+template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16,
+          bool BLOCKED>
 struct ReduceAdamOp {
-    const float* theta;
-    const float* m;
-    const float* v;
-    float*       gsum;  // read when ACC, written when WRITE_GSUM
-    ShardPtrs    shards;
-    int          workers;
-    float*       theta_w;
-    float*       m_w;
-    float*       v_w;
-    float*       out_f32;
-    uint16_t*    out_bf16;
-    AdamScalars  s;
+    const float*       theta;
+    const float*       m;
+    const float*       v;
+    float*             gsum;  // read when ACC, written when WRITE_GSUM
+    ShardPtrs          shards;
+    int                workers;
+    float*             theta_w;
+    float*             m_w;
+    float*             v_w;
+    float*             out_f32;
+    uint16_t*          out_bf16;
+    AdamScalars        s;
+    StateAddr<BLOCKED> at;
     struct In {
         f4 t, m, v, g;
         f4 x[BF16 ? 1 : kReduceChunk];
@@ -381,11 +427,12 @@ struct ReduceAdamOp {
     };
     __device__ __forceinline__ In load(int64_t i) const
     {
-        In in;
-        in.t = ld(reinterpret_cast<const f4*>(theta) + i);
-        in.m = ld(reinterpret_cast<const f4*>(m) + i);
-        in.v = ld(reinterpret_cast<const f4*>(v) + i);
-        if (ACC) in.g = ld(reinterpret_cast<const f4*>(gsum) + i);
+        const int64_t a = at.vec(i);
+        In            in;
+        in.t = ld(reinterpret_cast<const f4*>(theta) + a);
+        in.m = ld(reinterpret_cast<const f4*>(m) + a);
+        in.v = ld(reinterpret_cast<const f4*>(v) + a);
+        if (ACC) in.g = ld(reinterpret_cast<const f4*>(gsum) + a);
 #pragma unroll
         for (int w = 0; w < kReduceChunk; ++w) {
             if (w < workers) {
@@ -399,7 +446,8 @@ struct ReduceAdamOp {
     }
     __device__ __forceinline__ void apply(int64_t i, const In& in) const
     {
-        f4 g = in.g;
+        const int64_t a = at.vec(i);
+        f4            g = in.g;
 #pragma unroll
         for (int w = 0; w < kReduceChunk; ++w) {
             if (w < workers) {
@@ -407,37 +455,34 @@ struct ReduceAdamOp {
                 g          = (!ACC && w == 0) ? x : g + x;
             }
         }
-        if (WRITE_GSUM) st(reinterpret_cast<f4*>(gsum) + i, g);
-        float to[4], mo[4], vo[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) adamw_elem(in.t[k], in.m[k], in.v[k], g[k], s, to[k], mo[k], vo[k]);
-        const f4 t  = {to[0], to[1], to[2], to[3]};
-        const f4 mm = {mo[0], mo[1], mo[2], mo[3]};
-        const f4 vv = {vo[0], vo[1], vo[2], vo[3]};
+        if (WRITE_GSUM) st(reinterpret_cast<f4*>(gsum) + a, g);
+        f4 t, mm, vv;
+        adamw_vec(in.t, in.m, in.v, g, s, t, mm, vv);
         if (COMMIT) {
-            st(reinterpret_cast<f4*>(theta_w) + i, t);
-            st(reinterpret_cast<f4*>(m_w) + i, mm);
-            st(reinterpret_cast<f4*>(v_w) + i, vv);
+            st(reinterpret_cast<f4*>(theta_w) + a, t);
+            st(reinterpret_cast<f4*>(m_w) + a, mm);
+            st(reinterpret_cast<f4*>(v_w) + a, vv);
         }
         if (OUT_F32) st(reinterpret_cast<f4*>(out_f32) + i, t);
         if (OUT_BF16) st(reinterpret_cast<u2*>(out_bf16) + i, pack_bf16x4(t));
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        float g = ACC ? gsum[j] : 0.0f;
+        const int64_t a = at.elem(j);
+        float         g = ACC ? gsum[a] : 0.0f;
         for (int w = 0; w < workers; ++w) {
             const float x =
                 BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
                      : static_cast<const float*>(shards.p[w])[j];
             g = (!ACC && w == 0) ? x : g + x;
         }
-        if (WRITE_GSUM) gsum[j] = g;
+        if (WRITE_GSUM) gsum[a] = g;
         float t, mm, vv;
-        adamw_elem(theta[j], m[j], v[j], g, s, t, mm, vv);
+        adamw_elem(theta[a], m[a], v[a], g, s, t, mm, vv);
         if (COMMIT) {
-            theta_w[j] = t;
-            m_w[j]     = mm;
-            v_w[j]     = vv;
+            theta_w[a] = t;
+            m_w[a]     = mm;
+            v_w[a]     = vv;
         }
         if (OUT_F32) out_f32[j] = t;
         if (OUT_BF16) out_bf16[j] = (uint16_t)to_bf16_bits(t);

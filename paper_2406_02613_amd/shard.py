@@ -30,7 +30,8 @@ from . import binding as B
 class ShardOwner:
     def __init__(self, n: int, workers: int, hp: B.AdamW, *, device="cuda", comm_bf16: bool = True,
                  fused_bf16_out: bool = True, fused_publish: bool = False,
-                 fused_reduce: bool = False):
+                 fused_reduce: bool = False, blocked_state: bool = False,
+                 block_elems: int = 8192):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -40,10 +41,18 @@ class ShardOwner:
         self.fused_reduce = fused_reduce
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
-        self.theta = torch.empty(n, dtype=f32, device=dev)
-        self.m = torch.zeros(n, dtype=f32, device=dev)
-        self.v = torch.zeros(n, dtype=f32, device=dev)
-        self.gsum = torch.empty(n, dtype=f32, device=dev)
+        self.state = None
+        if blocked_state:
+            # theta, m, v, gsum interleaved block by block in one buffer (see state.py)
+            from .state import BlockedState
+            self.state = BlockedState(n, block_elems, dev)
+            self.theta, self.m, self.v, self.gsum = (self.state.theta, self.state.m,
+                                                     self.state.v, self.state.gsum)
+        else:
+            self.theta = torch.empty(n, dtype=f32, device=dev)
+            self.m = torch.zeros(n, dtype=f32, device=dev)
+            self.v = torch.zeros(n, dtype=f32, device=dev)
+            self.gsum = torch.empty(n, dtype=f32, device=dev)
         self.acc: List = [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)]
         self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                            if comm_bf16 else [])
@@ -54,6 +63,16 @@ class ShardOwner:
         self.step = B.Counter(0)                              # committed updates
         self._fresh = [True] * workers                        # next accumulate starts a new sum
         self._published = [False] * workers                   # comm[w] already written this stage
+
+    # planar access to the state, whatever its layout
+    def set_state(self, name: str, planar) -> None:
+        if self.state is not None:
+            self.state.load(name, planar)
+        else:
+            getattr(self, name).copy_(planar)
+
+    def get_state(self, name: str):
+        return self.state.planar(name) if self.state is not None else getattr(self, name)
 
     # computation stream
     def add_microbatch(self, worker: int, grad_bf16, last: bool = False) -> None:
@@ -89,11 +108,12 @@ class ShardOwner:
         if self.fused_reduce:
             B.acco_reduce_estimate_step(self.theta, self.m, self.v, self.gsum, shards,
                                         self._counts(), self.total, self.hp, self.step.value,
-                                        theta_tilde_bf16=self.theta_tilde_bf16)
+                                        theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
         else:
-            B.acco_reduce_shards(self.gsum, shards, False, self._counts(), self.total)
+            B.acco_reduce_shards(self.gsum, shards, False, self._counts(), self.total, n=self.n)
             B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step.value,
-                                 self.total.value, theta_tilde_bf16=self.theta_tilde_bf16)
+                                 self.total.value, theta_tilde_bf16=self.theta_tilde_bf16,
+                                 n=self.n)
         self._end_stage()
 
     def stage2(self) -> None:
@@ -102,11 +122,13 @@ class ShardOwner:
         if self.fused_reduce:
             B.acco_reduce_commit_step(self.theta, self.m, self.v, self.gsum, shards,
                                       self._counts(), self.total, self.hp, self.step,
-                                      theta_bf16=out)
+                                      theta_bf16=out, n=self.n)
         else:
-            B.acco_reduce_shards(self.gsum, shards, True, self._counts(), self.total)
+            B.acco_reduce_shards(self.gsum, shards, True, self._counts(), self.total, n=self.n)
             B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step,
-                               self.total.value, theta_bf16=out)
+                               self.total.value, theta_bf16=out, n=self.n)
         if not self.fused_bf16_out:
+            if self.state is not None:
+                raise ValueError("the unfused parameter cast needs a planar theta")
             B.acco_cast_params(self.theta_bf16, self.theta)
         self._end_stage()

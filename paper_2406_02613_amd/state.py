@@ -1,0 +1,38 @@
+"""Block-interleaved storage of one shard's theta, m, v and gsum (acco_layout_t).
+
+One buffer of shape (blocks, 4, block_elems): block b holds, one after the other, elements
+[b*block_elems, (b+1)*block_elems) of theta, of m, of v and of gsum.  The four views
+``theta, m, v, gsum`` (shape (blocks, block_elems), strides (4*block_elems, 1)) are what the
+step entry points take; the binding derives the layout from their strides.  Allocation and
+copies only - no arithmetic.
+"""
+from __future__ import annotations
+
+DEFAULT_BLOCK_ELEMS = 8192      # 32 KiB per component: the fastest of 1 Ki .. 128 Ki elements on MI355X
+
+
+class BlockedState:
+    def __init__(self, n: int, block_elems: int = DEFAULT_BLOCK_ELEMS, device="cuda"):
+        import torch
+        if block_elems < 4 or block_elems & (block_elems - 1):
+            raise ValueError("block_elems must be a power of two >= 4")
+        self.n, self.block = int(n), int(block_elems)
+        self.blocks = (self.n + self.block - 1) // self.block
+        self.buf = torch.zeros(self.blocks, 4, self.block, dtype=torch.float32, device=device)
+        self.theta, self.m, self.v, self.gsum = (self.buf[:, c, :] for c in range(4))
+
+    def load(self, name: str, planar) -> None:
+        """Copy a planar fp32 tensor of n elements into component ``name``."""
+        view = getattr(self, name)
+        if planar.numel() != self.n:
+            raise ValueError(f"expected {self.n} elements")
+        full = self.n // self.block
+        if full:
+            view[:full].copy_(planar[:full * self.block].view(full, self.block))
+        rem = self.n - full * self.block
+        if rem:
+            view[full, :rem].copy_(planar[full * self.block:])
+
+    def planar(self, name: str):
+        """A planar copy (n elements) of component ``name``."""
+        return getattr(self, name).reshape(-1)[:self.n].clone()

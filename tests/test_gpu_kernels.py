@@ -392,3 +392,73 @@ def test_fused_reduce_steps_equal_the_separate_calls_and_the_oracle(acco, shape,
         assert_f32_close(vd.cpu().numpy(), v64, "v vs f64", abs_=1e-30)
     acco.set_launch_shape("reduce_estimate", *DEFAULT_SHAPE)
     acco.set_launch_shape("reduce_commit", *DEFAULT_SHAPE)
+
+
+# ------------------------------------------------------------------ blocked state layout
+
+
+@pytest.mark.parametrize("block", [4, 64, 4096])
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 2, 1), (512, 4, 0)])
+def test_blocked_state_gives_the_same_bits_as_planar(acco, block, shape):
+    for e in ("reduce", "estimate", "commit", "reduce_estimate", "reduce_commit"):
+        acco.set_launch_shape(e, *shape)
+    rng = np.random.default_rng(30 + block)
+    h = HYPERS[0]
+    ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    W = 3
+    for n in (1, 3, 5, block - 1, block, block + 1, 3 * block + 7, 100_003, (1 << 18) + 37):
+        if n < 1:
+            continue
+        log("blocked", block, shape, n)
+        theta, m, v, _ = _state(rng, n, "warm")
+        s1 = [_rand_bf16(rng, n, 2e-4) for _ in range(W)]
+        s2 = [_rand_bf16(rng, n, 2e-4) for _ in range(W)]
+        d1, d2 = [bf16_tensor(s) for s in s1], [bf16_tensor(s) for s in s2]
+        c1, c2 = [1, 2, 3], [2, 2, 2]
+        # oracle, planar by definition
+        g_h = np.empty(n, np.float32)
+        oracle.reduce(g_h, s1, accumulate_=False)
+        e32, e16 = oracle.estimate(theta, m, v, g_h, ohp, 4, sum(c1), precision="f32")
+        oracle.reduce(g_h, s2, accumulate_=True)
+        t_h, m_h, v_h = theta.copy(), m.copy(), v.copy()
+        b16 = oracle.commit(t_h, m_h, v_h, g_h, ohp, 4, sum(c1) + sum(c2), precision="f32")
+        for fused in (False, True):
+            st = acco.BlockedState(n, block)
+            st.buf.fill_(123.0)                    # padding and gaps must never be touched
+            for name, arr in (("theta", theta), ("m", m), ("v", v)):
+                st.load(name, dev(arr))
+            guard = st.buf.clone()
+            o32 = torch.empty(n, dtype=torch.float32, device="cuda")
+            o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            c16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            tot, step = acco.Counter(0), acco.Counter(3)
+            if fused:
+                acco.acco_reduce_estimate_step(st.theta, st.m, st.v, st.gsum, d1, c1, tot, ghp, 3,
+                                               theta_tilde_f32=o32, theta_tilde_bf16=o16, n=n)
+                acco.acco_reduce_commit_step(st.theta, st.m, st.v, st.gsum, d2, c2, tot, ghp, step,
+                                             theta_bf16=c16, n=n)
+            else:
+                acco.acco_reduce_shards(st.gsum, d1, False, c1, tot, n=n)
+                acco.acco_estimate_step(st.theta, st.m, st.v, st.gsum, ghp, 3, tot.value,
+                                        theta_tilde_f32=o32, theta_tilde_bf16=o16, n=n)
+                acco.acco_reduce_shards(st.gsum, d2, True, c2, tot, n=n)
+                acco.acco_commit_step(st.theta, st.m, st.v, st.gsum, ghp, step, tot.value,
+                                      theta_bf16=c16, n=n)
+            assert tot.value == 12 and step.value == 4
+            assert bit_mismatches(o32.cpu().numpy(), e32) == 0
+            assert np.array_equal(bits_of(o16), e16)
+            assert np.array_equal(bits_of(c16), b16)
+            assert bit_mismatches(st.planar("theta").cpu().numpy(), t_h) == 0
+            assert bit_mismatches(st.planar("m").cpu().numpy(), m_h) == 0
+            assert bit_mismatches(st.planar("v").cpu().numpy(), v_h) == 0
+            if not fused:
+                assert bit_mismatches(st.planar("gsum").cpu().numpy(), g_h) == 0
+            # nothing outside the n logical elements of each component was written
+            flat_new = st.buf.reshape(st.blocks, 4, block)
+            flat_old = guard.reshape(st.blocks, 4, block)
+            rem = n - (st.blocks - 1) * block
+            if rem < block:
+                assert torch.equal(flat_new[-1, :, rem:], flat_old[-1, :, rem:])
+    for e in ("reduce", "estimate", "commit", "reduce_estimate", "reduce_commit"):
+        acco.set_launch_shape(e, *DEFAULT_SHAPE)

@@ -31,7 +31,7 @@ def gpu_hyper(A, w):
 
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
-                 fused_publish=False, fused_reduce=False):
+                 fused_publish=False, fused_reduce=False, blocked=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -39,13 +39,15 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
         f"({sum(b - a for a, b in slices)} elements checked)")
     owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
                          fused_bf16_out=fused, fused_publish=fused_publish,
-                         fused_reduce=fused_reduce)
+                         fused_reduce=fused_reduce, blocked_state=blocked)
     if warm is None:
-        w.device_theta(owner.theta)
+        tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
+        w.device_theta(tmp)
+        owner.set_state("theta", tmp)
+        del tmp
     else:
-        owner.theta.copy_(torch.from_numpy(warm[0]))
-        owner.m.copy_(torch.from_numpy(warm[1]))
-        owner.v.copy_(torch.from_numpy(warm[2]))
+        for k, name in enumerate(("theta", "m", "v")):
+            owner.set_state(name, torch.from_numpy(warm[k]).cuda())
         owner.step.value = w.warm_steps
     grad_buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
     comm = "bf16" if comm_bf16 else "f32"
@@ -78,10 +80,10 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
             assert_bf16_close(got, w64, f"{w.name} r{r} s{stage} bf16 vs f64 form")
             exact &= np.array_equal(got, w32)
             if not (fused_reduce and stage == synth.STAGE_FULL):   # fused commit only reads gsum
-                gs = gather(owner.gsum, slices).numpy()
+                gs = gather(owner.get_state("gsum"), slices).numpy()
                 assert bit_mismatches(gs, np.concatenate([s.gsum for s in ref32.shards])) == 0
         for name in ("theta", "m", "v"):
-            got = gather(getattr(owner, name), slices).numpy()
+            got = gather(owner.get_state(name), slices).numpy()
             a32 = np.concatenate([getattr(s, name) for s in ref32.shards])
             a64 = np.concatenate([getattr(s, name) for s in ref64.shards])
             abs_ = 1e-30 if name == "v" else 1e-9
@@ -121,11 +123,18 @@ def test_tiny_with_fused_publish_and_fused_reduce():
     run_workload(w, comm_bf16=False, fused_reduce=True, rounds=2)
 
 
+def test_tiny_with_blocked_state():
+    w = synth.WORKLOADS["tiny"]
+    run_workload(w, blocked=True)
+    run_workload(w, blocked=True, fused_publish=True, fused_reduce=True)
+
+
 def test_ragged_small_shard_with_unequal_counts():
     w = synth.Workload(name="ragged", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
                        k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
     run_workload(w)
     run_workload(w, fused_publish=True, fused_reduce=True)
+    run_workload(w, fused_publish=True, fused_reduce=True, blocked=True)
 
 
 def test_gpt2_small_scale_shard_ten_rounds():
@@ -152,3 +161,8 @@ def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
 def test_seven_billion_scale_shard_fused_path_as_benched():
     # the configuration bench.py times by default: fused publish, fused reduce + step
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, rounds=3)
+
+
+def test_seven_billion_hetero_blocked_state_fused_path():
+    run_workload(synth.WORKLOADS["7b_hetero"], fused_publish=True, fused_reduce=True,
+                 blocked=True, rounds=2)
