@@ -52,6 +52,17 @@ def parse():
                     help="time one round of this update scheme sequenced on the base entry "
                          "points (paper_2406_02613_amd.schemes) instead of the default fused "
                          "ACCO round; the JSON line then carries that scheme's round time")
+    ap.add_argument("--two-stream", action="store_true",
+                    help="run the two-stream scheduler of Alg. 1 (computation stream accumulating "
+                         "while the communication stream runs the owner's stage) and report what "
+                         "the overlap costs each stream")
+    ap.add_argument("--link-ms", type=float, default=0.0,
+                    help="--two-stream: a timed wait of this many ms per stage on the "
+                         "communication stream where the reduce-scatter / all-gather transfers "
+                         "would be (no data moves; it only occupies the stream)")
+    ap.add_argument("--gemm", type=int, default=8192,
+                    help="--two-stream: size of the square bf16 GEMM standing in for a "
+                         "micro-batch's forward/backward (0 = none)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the shard (fp32, n elements read and "
                          "n written) so that a counter run has a kernel of known traffic")
@@ -200,6 +211,111 @@ def bench_scheme(args, torch, A, w, grads):
     return 0
 
 
+def bench_two_stream(args, torch, A, w):
+    """Alg. 1's two streams on one GPU at the workload's shard size: worker 0 accumulates on the
+    computation stream (GEMM stand-in + gradient write + acco_accumulate per micro-batch) while
+    the communication stream publishes, reduces over W shards and runs the estimate / commit."""
+    import synth
+    h = w.hyper
+    own = A.TwoStreamOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
+                                                        h.weight_decay))
+    tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
+    w.device_theta(tmp)
+    own.set_theta(tmp)
+    del tmp
+    peers = []
+    for wk in range(1, w.workers):
+        p = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+        synth.device_grad_bf16(p, w.grad_spec(0, 1, wk, 0), 0)
+        peers.append(p)
+    peer_counts = [2] * (w.workers - 1)
+    buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    a = b = None
+    if args.gemm > 0:
+        a = torch.randn(args.gemm, args.gemm, dtype=torch.bfloat16, device="cuda")
+        b = torch.randn(args.gemm, args.gemm, dtype=torch.bfloat16, device="cuda")
+    c = torch.empty(args.gemm, args.gemm, dtype=torch.bfloat16, device="cuda") if a is not None \
+        else None
+
+    def compute():
+        if a is not None:
+            torch.mm(a, b, out=c)
+
+    def grad_source(rnd, acc, k):
+        synth.device_grad_bf16(buf, w.grad_spec((rnd + 1) & 0xFFFF, acc, 0, k & 0xFFFF), 0)
+        return buf
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    # each stream on its own first
+    def one_microbatch():
+        compute()
+        B = A.binding
+        B.acco_accumulate(own.acc[2], grad_source(0, 2, 0), False)
+    mb_alone = timed(one_microbatch, 10)
+
+    def comm_pair():
+        own._communicate(1, peers, peer_counts)
+        own._communicate(2, peers, peer_counts)
+        own.comm_stream.synchronize()
+    own.count[1].value = own.count[2].value = 2
+    comm_alone = timed(comm_pair, 5) / 2
+    own.step.value = 0
+
+    transport = None
+    if args.link_ms > 0:
+        # calibrate torch's spin kernel (cycles per ms) once, then wait link_ms per stage
+        probe = 20_000_000
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda._sleep(1000)
+        e0.record()
+        torch.cuda._sleep(probe)
+        e1.record()
+        torch.cuda.synchronize()
+        cycles = int(args.link_ms * probe / e0.elapsed_time(e1))
+        transport = lambda: torch.cuda._sleep(cycles)
+
+    own.run(args.warmup, grad_source, peers, peer_counts, compute, transport=transport)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    log = own.run(args.steps, grad_source, peers, peer_counts, compute, transport=transport)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    st1 = [r for r in log.stages if r.stage == 1]
+    st2 = [r for r in log.stages if r.stage == 2]
+    mbs = sum(r.microbatches for r in log.stages)
+    mean = lambda xs: sum(xs) / max(len(xs), 1)
+    out = {
+        "metric": "shard optimizer-step elements/s (two-stream ACCO round: communication stream "
+                  "overlapped with gradient accumulation)",
+        "value": w.n * args.steps / (wall_ms * 1e-3), "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "mode": "two-stream", "n": w.n, "workers": w.workers,
+                   "gemm": args.gemm, "link_ms_per_stage": args.link_ms},
+        "two_stream": {
+            "microbatch_ms_alone": mb_alone,
+            "microbatch_ms_overlapped": mean([r.comp_ms / r.microbatches for r in log.stages]),
+            "comm_stage_ms_alone": comm_alone,
+            "comm_stage1_ms_overlapped": mean([r.comm_ms for r in st1]),
+            "comm_stage2_ms_overlapped": mean([r.comm_ms for r in st2]),
+            "microbatches_per_stage": mean([r.microbatches for r in log.stages]),
+            "supplementary_accumulation_steps": log.extra_accumulations(1),
+            "microbatches_total": mbs,
+        },
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def cpu_baseline(w, target_seconds):
     """The oracle (as it stands) on the first S elements of the same workload, one round."""
     import numpy as np
@@ -272,6 +388,8 @@ def main():
     A.binding.lib()
     w = synth.WORKLOADS[args.workload]
     h = w.hyper
+    if args.two_stream:
+        return bench_two_stream(args, torch, A, w)
     if args.scheme is not None:
         return bench_scheme(args, torch, A, w, make_grads(torch, synth, w)[0])
     blocked = not args.planar_state and not args.unfused_cast

@@ -7,11 +7,12 @@ from .binding import (ACCO_BF16, ACCO_F32, AccoError, AdamW, Counter, acco_accum
                       make_hyper, set_launch_shape, status_string, version)
 from .shard import ShardOwner
 from .state import BlockedState
+from .two_stream import TwoStreamOwner
 from .schemes import SchemeOwner, SCHEMES
 from . import layout
 
 __all__ = ["ACCO_BF16", "ACCO_F32", "AccoError", "AdamW", "Counter", "acco_accumulate",
            "acco_accumulate_publish", "acco_cast_params", "acco_commit_step", "acco_estimate_step",
            "acco_reduce_commit_step", "acco_reduce_estimate_step", "acco_reduce_shards",
-           "acco_sgd_commit_step", "acco_sgd_estimate_step", "make_sgd", "Sgd", "SchemeOwner", "SCHEMES", "BlockedState",
+           "acco_sgd_commit_step", "acco_sgd_estimate_step", "make_sgd", "Sgd", "SchemeOwner", "SCHEMES", "BlockedState", "TwoStreamOwner",
            "make_hyper", "set_launch_shape", "status_string", "version", "ShardOwner", "layout"]
