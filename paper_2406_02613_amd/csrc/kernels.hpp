@@ -1,12 +1,14 @@
-// Device code of the ACCO shard path for gfx950: five streaming kernels, all
-// elementwise and HBM-bound, built on one tile loop.
+// Device code of the ACCO shard path for gfx950: streaming kernels, all elementwise
+// and HBM-bound (no MFMA, no LDS), each built from an "Op" (what to load, what to
+// compute, what to store for one vector) and one of two drivers.
 //
-// Layout: every array is flat.  A "vector" is 4 consecutive elements: 16 bytes of
-// fp32 (one dwordx4 per lane) or 8 bytes of bf16 (one dwordx2 per lane), so each
-// wavefront instruction touches 1024 (512) contiguous bytes.  A workgroup of T
-// threads owns tiles of T*U vectors; each thread issues the loads of its U vectors
-// of every input array before the first use, so U*(arrays) 16-byte requests per
-// lane are in flight while HBM latency is paid.  Tiles are taken grid-stride.
+// A "vector" is 4 consecutive elements: 16 bytes of fp32 (one dwordx4 per lane) or
+// 8 bytes of bf16 (one dwordx2 per lane), so each wavefront instruction touches 1024
+// (512) contiguous bytes.
+//   flat_kernel    one vector per thread, one tile per workgroup, no loop: the default;
+//   stream_kernel  grid-stride over tiles of T*U vectors, the loads of a thread's U
+//                  vectors of every input issued before the first use (kept selectable
+//                  through acco_set_launch_shape; slower at every size measured).
 // The last n % 4 elements are done one by one by workgroup 0.
 //
 // Arithmetic: fp32, one IEEE operation per written operation (compiled with

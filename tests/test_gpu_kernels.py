@@ -11,8 +11,8 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 SIZES = [0, 1, 3, 4, 7, 8, 9, 63, 64, 65, 1000, 4096 + 5, (1 << 20), (1 << 20) + 37]
-DEFAULT_SHAPE = (256, 1, 0)      # the library's default: one 16-byte vector per thread, no loop
-SHAPES = [DEFAULT_SHAPE, (64, 1, 0), (256, 2, 0), (512, 4, 0), (256, 4, 2), (128, 2, 1)]
+DEFAULT_SHAPE = (64, 1, 0)       # the library's default: one wavefront per workgroup, no loop
+SHAPES = [DEFAULT_SHAPE, (256, 1, 0), (256, 2, 0), (512, 4, 0), (256, 4, 2), (128, 2, 1)]
 
 
 @pytest.fixture(scope="module")

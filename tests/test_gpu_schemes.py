@@ -30,7 +30,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("shape", [(256, 1, 0), (128, 2, 1), (512, 4, 0)])
+@pytest.mark.parametrize("shape", [(64, 1, 0), (128, 2, 1), (512, 4, 0)])
 def test_sgd_steps_match_the_oracle(acco, shape):
     acco.set_launch_shape("sgd", *shape)
     rng = np.random.default_rng(20)
@@ -58,7 +58,7 @@ def test_sgd_steps_match_the_oracle(acco, shape):
             assert st.value == 5
             assert bit_mismatches(td.cpu().numpy(), w32) == 0
             assert np.array_equal(bits_of(c16), w16)
-    acco.set_launch_shape("sgd", 256, 1, 0)
+    acco.set_launch_shape("sgd", 64, 1, 0)
 
 
 @pytest.mark.parametrize("scheme", ["acco", "ddp", "dpu", "wp"])
