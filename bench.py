@@ -9,10 +9,12 @@ and runs the committed AdamW step with the fused bf16 parameter output.  All inp
 (parameters, optimizer state, every micro-batch gradient of the round) are resident
 in HBM before the timed region starts.
 
-Prints ONE JSON line (see README/DESIGN for the fields).  `roofline` is the committed
-step kernel, timed with HIP events on the launching stream inside the timed region;
-`kernels` carries the same figures for every entry point; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload on this machine's host cores.
+Prints ONE JSON line.  `value` is shard elements per second through one whole round;
+`roofline` is the committed-step kernel of the timed round (the fused reduce + commit), timed
+with HIP events on the launching stream inside the timed region; `kernels` carries the same
+figures for every kernel of the round; `standalone_step_kernels` times acco_commit_step and
+acco_estimate_step on their own afterwards; `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload on this machine's host cores.
 """
 from __future__ import annotations
 

@@ -241,6 +241,21 @@ int acco_sgd_estimate_step(const float* theta, const float* gsum, float* theta_t
 int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* theta_bf16, int64_t n,
                          const acco_sgd_t* hp, int64_t* step, int64_t total_count, void* stream);
 
+/*
+ * Learning rate of update number `step` (0-based) under the cosine schedule of the paper's
+ * hyper-parameter tables (App. C: scheduler cosine, n_warmup_steps 0, nb_steps_tot 50000), with
+ * an optional linear warm-up; a host function - the result is what the caller puts into
+ * acco_adamw_t.lr for that step:
+ *   step <  warmup_steps:  base_lr * (step + 1) / warmup_steps
+ *   otherwise:             min_lr + (base_lr - min_lr) * (1 + cos(pi * p)) / 2,
+ *                          p = min(1, (step - warmup_steps) / max(1, total_steps - warmup_steps))
+ * The paper does not state a final learning rate; min_lr = 0 decays to zero.
+ * Returns NaN for invalid arguments (negative or non-finite rates, min_lr > base_lr, step < 0,
+ * warmup_steps < 0, total_steps < warmup_steps).
+ */
+double acco_lr_cosine(double base_lr, double min_lr, int64_t step, int64_t warmup_steps,
+                      int64_t total_steps);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* acco_status_string(int status);
 

@@ -156,6 +156,18 @@ def sgd_step(theta, gsum, lr: float, weight_decay: float, count: int, *, commit:
     return out, out_bf16
 
 
+def lr_cosine(base_lr: float, min_lr: float, step: int, warmup_steps: int,
+              total_steps: int) -> float:
+    """Cosine schedule of the paper's hyper-parameter tables with optional linear warm-up:
+    the learning rate of update number `step` (0-based)."""
+    import math
+    if step < warmup_steps:
+        return base_lr * (step + 1) / warmup_steps
+    span = max(1, total_steps - warmup_steps)
+    p = min(1.0, (step - warmup_steps) / span)
+    return min_lr + (base_lr - min_lr) * (1.0 + math.cos(math.pi * p)) / 2.0
+
+
 # --------------------------------------------------------------------------- one shard owner
 
 

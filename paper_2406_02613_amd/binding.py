@@ -22,7 +22,7 @@ ACCO_MAX_WORKERS = 64
 EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
-           "acco_status_string", "acco_version", "acco_set_launch_shape")
+           "acco_lr_cosine", "acco_status_string", "acco_version", "acco_set_launch_shape")
 
 
 class AdamW(ctypes.Structure):
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
+        L.acco_lr_cosine.restype = ctypes.c_double
+        L.acco_lr_cosine.argtypes = [ctypes.c_double, ctypes.c_double, i64, i64, i64]
         L.acco_status_string.restype = ctypes.c_char_p
         L.acco_status_string.argtypes = [ci]
         _lib = L
@@ -347,3 +349,9 @@ def acco_sgd_commit_step(theta, gsum, hp: Sgd, step: Counter, total_count: int, 
                                     _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
                                     ctypes.byref(hp), step.ref(), int(total_count), _stream())
     _check(rc, "acco_sgd_commit_step")
+
+
+def acco_lr_cosine(base_lr: float, min_lr: float, step: int, warmup_steps: int,
+                   total_steps: int) -> float:
+    return float(lib().acco_lr_cosine(float(base_lr), float(min_lr), int(step), int(warmup_steps),
+                                      int(total_steps)))

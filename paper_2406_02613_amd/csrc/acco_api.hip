@@ -674,6 +674,20 @@ ACCO_API int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* the
     return rc;
 }
 
+ACCO_API double acco_lr_cosine(double base_lr, double min_lr, int64_t step, int64_t warmup_steps,
+                               int64_t total_steps)
+{
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    if (!finite_nonneg(base_lr) || !finite_nonneg(min_lr) || min_lr > base_lr) return nan;
+    if (step < 0 || warmup_steps < 0 || total_steps < warmup_steps) return nan;
+    if (step < warmup_steps) return base_lr * (double)(step + 1) / (double)warmup_steps;
+    const int64_t span = total_steps - warmup_steps;
+    double        p    = (double)(step - warmup_steps) / (double)(span > 0 ? span : 1);
+    if (p > 1.0) p = 1.0;
+    const double pi = 3.14159265358979323846;
+    return min_lr + (base_lr - min_lr) * (1.0 + std::cos(pi * p)) * 0.5;
+}
+
 ACCO_API const char* acco_status_string(int status)
 {
     switch (status) {

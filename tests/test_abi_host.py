@@ -324,3 +324,30 @@ def test_state_layout_validation_and_interleaved_aliasing_rules():
     s2 = _shards(0x8000000, 0x9000000)
     assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 4 * blk), NONE) == 0
     assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 3), NONE) == B.ACCO_ERR_ARG
+
+
+def test_cosine_schedule_closed_forms_and_oracle():
+    import math
+    import oracle
+    base, lo, T = 6e-4, 6e-5, 50_000          # the paper's pre-training table: 6e-4, 50000 steps
+    f = B.acco_lr_cosine
+    assert f(base, lo, 0, 0, T) == base                                   # starts at the peak
+    assert abs(f(base, lo, T, 0, T) - lo) < 1e-18                         # ends at the floor
+    assert abs(f(base, lo, T // 2, 0, T) - (base + lo) / 2) < 1e-18       # half-way: the mean
+    assert abs(f(base, lo, T // 3 * 1, 0, T // 3 * 3) - (lo + 0.75 * (base - lo))) < 1e-15
+    assert f(base, lo, 10 * T, 0, T) == f(base, lo, T, 0, T)              # clamps after the end
+    assert f(base, 0.0, T, 0, T) < 1e-18
+    vals = [f(base, lo, s, 0, T) for s in range(0, T + 1, 500)]
+    assert all(a > b for a, b in zip(vals, vals[1:]))                     # monotone
+    for s in (0, 123, 4999, 25_000, 49_999):                              # symmetry of the cosine
+        assert abs(f(base, lo, s, 0, T) + f(base, lo, T - s, 0, T) - (base + lo)) < 1e-15
+    # linear warm-up, then the cosine measured from the end of the warm-up
+    assert f(base, lo, 0, 100, T) == base / 100 and f(base, lo, 99, 100, T) == base
+    assert f(base, lo, 100, 100, T) == base
+    for s in range(0, 2 * T, 777):
+        for wu in (0, 100):
+            assert math.isclose(f(base, lo, s, wu, T), oracle.lr_cosine(base, lo, s, wu, T),
+                                rel_tol=1e-13, abs_tol=1e-20)
+    for bad in ((-1.0, 0.0, 0, 0, 10), (1.0, 2.0, 0, 0, 10), (1.0, 0.0, -1, 0, 10),
+                (1.0, 0.0, 0, -1, 10), (1.0, 0.0, 0, 20, 10), (float("nan"), 0.0, 0, 0, 10)):
+        assert math.isnan(f(*bad))

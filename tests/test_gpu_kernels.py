@@ -462,3 +462,42 @@ def test_blocked_state_gives_the_same_bits_as_planar(acco, block, shape):
                 assert torch.equal(flat_new[-1, :, rem:], flat_old[-1, :, rem:])
     for e in ("reduce", "estimate", "commit", "reduce_estimate", "reduce_commit"):
         acco.set_launch_shape(e, *DEFAULT_SHAPE)
+
+
+def test_maximum_worker_count(acco):
+    # 64 shards: eight launches of eight for the plain reduction, seven plus the fused one for
+    # the fused steps; order stays ascending throughout
+    rng = np.random.default_rng(64)
+    n, W = 10_007, 64
+    sh = [_rand_bf16(rng, n, 1.0) for _ in range(W)]
+    sh[0][0] = oracle.cast(np.array([2.0 ** 24], np.float32))[0]
+    for k in range(1, W):
+        sh[k][0] = oracle.cast(np.array([1.0], np.float32))[0]
+    dsh = [bf16_tensor(s) for s in sh]
+    counts = [1] * W
+    g_h = np.empty(n, np.float32)
+    oracle.reduce(g_h, sh, accumulate_=False)
+    assert g_h[0] == np.float32(2.0 ** 24)
+    g_d = torch.empty(n, dtype=torch.float32, device="cuda")
+    tot = acco.Counter(0)
+    acco.acco_reduce_shards(g_d, dsh, False, counts, tot)
+    assert tot.value == 64 and bit_mismatches(g_d.cpu().numpy(), g_h) == 0
+    theta, m, v, _ = _state(rng, n, "warm")
+    h = HYPERS[0]
+    ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    td, md, vd = dev(theta), dev(m), dev(v)
+    o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    g2 = torch.empty(n, dtype=torch.float32, device="cuda")
+    acco.acco_reduce_estimate_step(td, md, vd, g2, dsh, counts, tot, ghp, 0, theta_tilde_bf16=o16)
+    assert bit_mismatches(g2.cpu().numpy(), g_h) == 0
+    _, w16 = oracle.estimate(theta, m, v, g_h, ohp, 1, 64, want_f32=False, precision="f32")
+    assert np.array_equal(bits_of(o16), w16)
+    step = acco.Counter(0)
+    acco.acco_reduce_commit_step(td, md, vd, g2, dsh, counts, tot, ghp, step, theta_bf16=o16)
+    oracle.reduce(g_h, sh, accumulate_=True)
+    b16 = oracle.commit(theta, m, v, g_h, ohp, 1, 128, precision="f32")
+    assert tot.value == 128 and step.value == 1
+    assert bit_mismatches(td.cpu().numpy(), theta) == 0 and np.array_equal(bits_of(o16), b16)
+    with pytest.raises(acco.AccoError):
+        acco.acco_reduce_shards(g_d, dsh + [dsh[0]], False)          # 65 workers

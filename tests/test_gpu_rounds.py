@@ -90,7 +90,8 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
             assert_f32_close(got, a32, f"{w.name} r{r} {name} vs f32 form", abs_=abs_)
             if name == "theta":
                 # independent roundings of two correct implementations add up round by round;
-                # scale the relative bound by the largest magnitude theta had
+                # scale the relative bound by the largest magnitude theta had, and let the
+                # absolute floor grow with the number of Adam steps summed
                 ref0 = np.concatenate([w.host_theta(a, b - a) for a, b in slices]) \
                     if warm is None else np.concatenate([warm[0][a:b] for a, b in slices])
                 err = np.abs(got.astype(np.float64) - a64)
