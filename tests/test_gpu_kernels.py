@@ -501,3 +501,41 @@ def test_maximum_worker_count(acco):
     assert bit_mismatches(td.cpu().numpy(), theta) == 0 and np.array_equal(bits_of(o16), b16)
     with pytest.raises(acco.AccoError):
         acco.acco_reduce_shards(g_d, dsh + [dsh[0]], False)          # 65 workers
+
+
+def test_indexing_beyond_two_to_the_31_elements(acco):
+    # element indices above 2^31 and byte offsets above 2^33: the cast and the committed step
+    # (blocked state) on a 2^31 + 37 element shard, checked on sampled ranges
+    n = (1 << 31) + 37
+    w = synth.Workload(name="huge", n=n, workers=1, rounds=1, grad_std=1e-3, seed=31)
+    slices = [(0, 4099), ((1 << 31) - 2051, (1 << 31) + 37), ((1 << 30) + 3, (1 << 30) + 4100)]
+    log("huge shard", n)
+    src = torch.empty(n, dtype=torch.float32, device="cuda")
+    w.device_theta(src)
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    acco.acco_cast_params(out, src)
+    for a, b in slices:
+        assert np.array_equal(bits_of(out[a:b]), oracle.cast(w.host_theta(a, b - a))), (a, b)
+    del out
+    # committed step from m = v = 0 with gsum = the same stream scaled (any values will do)
+    st = acco.BlockedState(n)
+    st.load("theta", src)
+    st.load("gsum", src)
+    del src
+    h = HYPERS[0]
+    ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    acco.acco_commit_step(st.theta, st.m, st.v, st.gsum, ghp, acco.Counter(0), 16, theta_bf16=o16,
+                          n=n)
+    theta_p, m_p, v_p = st.planar("theta"), st.planar("m"), st.planar("v")
+    for a, b in slices:
+        t = w.host_theta(a, b - a)
+        g = t.copy()
+        m = np.zeros(b - a, np.float32)
+        v = np.zeros(b - a, np.float32)
+        b16 = oracle.commit(t, m, v, g, ohp, 1, 16, precision="f32")
+        assert bit_mismatches(theta_p[a:b].cpu().numpy(), t) == 0, (a, b)
+        assert bit_mismatches(m_p[a:b].cpu().numpy(), m) == 0
+        assert bit_mismatches(v_p[a:b].cpu().numpy(), v) == 0
+        assert np.array_equal(bits_of(o16[a:b]), b16)
