@@ -480,7 +480,10 @@ def main():
                 "bytes_per_launch": k["bytes_per_elem"] * w.n, "avg_ms": k["avg_ms"]}
 
     out = {
-        "metric": "shard optimizer-step elements/s (one full ACCO round of one shard owner)",
+        "metric": "shard optimizer-step elements/s + achieved HBM GB/s vs MI355X peak",
+        "metric_detail": "value = shard elements / time of one full ACCO round of one shard owner "
+                         "(all micro-batch accumulations, publishes, both reductions, estimate, "
+                         "commit); achieved GB/s per kernel in roofline / kernels",
         "value": w.n / (ms_per_step * 1e-3),
         "unit": "elements/s",
         "n_gpus": 1,
