@@ -539,3 +539,75 @@ def test_indexing_beyond_two_to_the_31_elements(acco):
         assert bit_mismatches(m_p[a:b].cpu().numpy(), m) == 0
         assert bit_mismatches(v_p[a:b].cpu().numpy(), v) == 0
         assert np.array_equal(bits_of(o16[a:b]), b16)
+
+
+def test_random_hyper_parameters_steps_and_counts_stay_bit_exact(acco):
+    # a randomised sweep over the scalars the host folds (bias corrections at large step
+    # indices, odd counts, extreme betas): the kernel must keep reproducing the binary32 form
+    rng = np.random.default_rng(77)
+    n = 8192 + 5
+    for trial in range(60):
+        lr = float(10 ** rng.uniform(-6, -1))
+        b1 = float(rng.choice([0.0, 0.5, 0.9, 0.99, 0.999]))
+        b2 = float(rng.choice([0.0, 0.9, 0.95, 0.999, 0.9999]))
+        eps = float(10 ** rng.uniform(-12, -3))
+        wd = float(rng.choice([0.0, 0.01, 0.1, 1.0]))
+        step = int(rng.choice([0, 1, 2, 9, 99, 999, 12_345, 999_999, 10 ** 9]))
+        count = int(rng.choice([1, 2, 3, 5, 7, 32, 37, 1000, 2 ** 20 + 1, 2 ** 40]))
+        theta, m, v, gsum = _state(rng, n, "warm")
+        gsum = (gsum * np.float32(min(count, 1000))).astype(np.float32)
+        ohp = oracle.make_hyper(lr, b1, b2, eps, wd)
+        ghp = acco.make_hyper(lr, b1, b2, eps, wd)
+        td, md, vd, gd = dev(theta), dev(m), dev(v), dev(gsum)
+        o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        acco.acco_estimate_step(td, md, vd, gd, ghp, step, count, theta_tilde_bf16=o16)
+        _, w16 = oracle.estimate(theta, m, v, gsum, ohp, step + 1, count, want_f32=False,
+                                 precision="f32")
+        assert np.array_equal(bits_of(o16), w16), (trial, lr, b1, b2, eps, wd, step, count)
+        acco.acco_commit_step(td, md, vd, gd, ghp, acco.Counter(step), count)
+        oracle.commit(theta, m, v, gsum, ohp, step + 1, count, want_bf16=False, precision="f32")
+        bad = (bit_mismatches(td.cpu().numpy(), theta) + bit_mismatches(md.cpu().numpy(), m)
+               + bit_mismatches(vd.cpu().numpy(), v))
+        assert bad == 0, (trial, lr, b1, b2, eps, wd, step, count)
+
+
+def test_degenerate_cases_of_the_method(acco):
+    n = 1003
+    rng = np.random.default_rng(5)
+    # eps = 0 with a zero gradient and zero moments: 0/0, NaN on both sides (payloads may differ)
+    theta = rng.standard_normal(n).astype(np.float32)
+    z = np.zeros(n, np.float32)
+    td, md, vd, gd = dev(theta), dev(z), dev(z), dev(z)
+    acco.acco_commit_step(td, md, vd, gd, acco.make_hyper(1e-3, 0.9, 0.95, 0.0, 0.0),
+                          acco.Counter(0), 1)
+    t2, m2, v2 = theta.copy(), z.copy(), z.copy()
+    oracle.commit(t2, m2, v2, z, oracle.make_hyper(1e-3, 0.9, 0.95, 0.0, 0.0), 1, 1,
+                  want_bf16=False, precision="f32")
+    assert np.isnan(t2).all() and torch.isnan(td).all().item()
+    assert not torch.any(md != 0).item() and not torch.any(vd != 0).item()
+    # one worker, one micro-batch per stage: the round collapses to publish + step
+    w = synth.Workload(name="deg", n=n, workers=1, rounds=2, grad_std=1e-3, k_fixed=2, seed=3)
+    h = w.hyper
+    own = acco.ShardOwner(n, 1, acco.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay),
+                          fused_publish=True, fused_reduce=True, blocked_state=True)
+    th0 = w.host_theta(0, n)
+    own.set_state("theta", dev(th0))
+    ref = oracle.OracleShard(th0, 1, oracle.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
+                                                       h.weight_decay), precision="f32")
+    for r in range(w.rounds):
+        for stage in (1, 2):
+            g = synth.host_grad_bf16(w.grad_spec(r, stage, 0, 0), 0, n)
+            own.add_microbatch(0, bf16_tensor(g), last=True)
+            ref.add_microbatch(0, g)
+            (own.stage1 if stage == 1 else own.stage2)()
+            (ref.stage1 if stage == 1 else ref.stage2)()
+    assert bit_mismatches(own.get_state("theta").cpu().numpy(), ref.theta) == 0
+    assert np.array_equal(bits_of(own.theta_bf16), ref.theta_bf16)
+    # a worker that contributed nothing in a stage (count 0, all-zero buffer) changes no bits
+    sh = [_rand_bf16(rng, n), np.zeros(n, np.uint16)]
+    g1 = torch.empty(n, dtype=torch.float32, device="cuda")
+    g2 = torch.empty(n, dtype=torch.float32, device="cuda")
+    tot = acco.Counter(0)
+    acco.acco_reduce_shards(g1, [bf16_tensor(s) for s in sh], False, [3, 0], tot)
+    acco.acco_reduce_shards(g2, [bf16_tensor(sh[0])], False, [3], acco.Counter(0))
+    assert tot.value == 3 and torch.equal(g1.view(torch.int32), g2.view(torch.int32))
