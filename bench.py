@@ -36,7 +36,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 MEASURED_TRAFFIC_B_PER_ELEM = {
     "7b": {"accumulate_init": 6.0, "accumulate": 10.0, "cast": 6.0, "reduce_init": 20.0,
            "reduce_accumulate": 24.0, "estimate": 18.0, "commit_bf16": 30.0, "commit": 28.0,
-           "accumulate_publish": 8.0, "reduce_estimate": 34.0, "reduce_commit_bf16": 46.0},
+           "accumulate_publish": 8.0, "reduce_estimate": 34.0, "reduce_commit_bf16": 46.0,
+           "accumulate_first": 4.0, "accumulate_second_publish": 6.0},
 }
 
 
@@ -77,6 +78,9 @@ def parse():
                     help="commit without the fused bf16 output, then acco_cast_params")
     ap.add_argument("--unfused-publish", action="store_true",
                     help="publish with acco_cast_params instead of acco_accumulate_publish")
+    ap.add_argument("--no-bf16-stash", action="store_true",
+                    help="expand the first micro-batch to the fp32 accumulator (acco_accumulate "
+                         "init) instead of keeping it as a bf16 stash")
     ap.add_argument("--unfused-reduce", action="store_true",
                     help="acco_reduce_shards + acco_estimate/commit_step instead of the fused "
                          "reduce+step entry points")
@@ -121,7 +125,22 @@ def run_round(A, owner, w, grads, log, opt):
             row = grads[stage][wk]
             for mb, g in enumerate(row):
                 init = mb == 0
-                if opt.fused_publish and mb == len(row) - 1:
+                last = opt.fused_publish and mb == len(row) - 1
+                if opt.bf16_stash and init:
+                    log.timed("accumulate_first_publish" if last else "accumulate_first",
+                              B.acco_accumulate_first, owner.comm[wk] if last else owner.stash[wk],
+                              g, last, owner.count[wk])
+                    published[wk] = last
+                elif opt.bf16_stash and mb == 1:
+                    if last:
+                        log.timed("accumulate_second_publish", B.acco_accumulate_second,
+                                  owner.stash[wk], g, comm_bf16=owner.comm[wk],
+                                  count=owner.count[wk])
+                        published[wk] = True
+                    else:
+                        log.timed("accumulate_second", B.acco_accumulate_second, owner.stash[wk],
+                                  g, acc=owner.acc[wk], count=owner.count[wk])
+                elif last:
                     log.timed("accumulate_publish_init" if init else "accumulate_publish",
                               B.acco_accumulate_publish, owner.acc[wk], g, owner.comm[wk], init,
                               False, owner.count[wk])
@@ -166,6 +185,10 @@ def kernel_bytes_per_elem(name, workers):
         "reduce_init": red + 4, "reduce_accumulate": red + 8,
         "accumulate_publish": 4 + 2 + 2,           # acc read, grad read, bf16 comm written
         "accumulate_publish_init": 2 + 2,
+        "accumulate_first": 2 + 2,                 # grad read, bf16 stash written
+        "accumulate_first_publish": 2 + 2,
+        "accumulate_second": 2 + 2 + 4,            # stash, grad read; fp32 acc written
+        "accumulate_second_publish": 2 + 2 + 2,    # stash, grad read; bf16 comm written
         "reduce_estimate": 12 + red + 4 + 2,       # theta,m,v + shards read; gsum, bf16 written
         "reduce_commit": 12 + 4 + red + 12,        # theta,m,v,gsum + shards read; theta,m,v written
         "reduce_commit_bf16": 12 + 4 + red + 12 + 2,
@@ -397,7 +420,8 @@ def main():
     blocked = not args.planar_state and not args.unfused_cast
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
-                         blocked_state=blocked, block_elems=args.block_elems)
+                         blocked_state=blocked, block_elems=args.block_elems,
+                         bf16_stash=not (args.no_bf16_stash or args.base_path))
     w.device_theta(owner.acc[0])                      # a planar scratch the round overwrites
     owner.set_state("theta", owner.acc[0])
 
@@ -413,6 +437,7 @@ def main():
         fused_cast = not args.unfused_cast
         fused_publish = not (args.unfused_publish or args.base_path)
         fused_reduce = not (args.unfused_reduce or args.base_path)
+        bf16_stash = not (args.no_bf16_stash or args.base_path)
 
     opt = Opt()
     for r in range(args.warmup):
@@ -504,6 +529,7 @@ def main():
                                     "elements" if blocked else "planar"),
                    "fused_bf16_output": opt.fused_cast,
                    "fused_publish": opt.fused_publish,
+                   "bf16_stash_of_first_microbatch": opt.bf16_stash,
                    "fused_reduce": opt.fused_reduce,
                    "host_wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": roofline,

@@ -119,6 +119,28 @@ int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* com
                             int init, int keep_acc, int64_t* count, void* stream);
 
 /*
+ * The first two micro-batches of an accumulation without an fp32 round trip.  After the first
+ * micro-batch the accumulator equals that gradient, which bf16 holds exactly, so it is kept as
+ * a bf16 "stash"; the second micro-batch adds to it in fp32.  Values are identical to
+ * acco_accumulate(init = 1) followed by acco_accumulate / acco_accumulate_publish; 4 bytes per
+ * element less HBM traffic in each of the two calls.
+ *
+ * acco_accumulate_first:  stash[j] = grad[j];  *count = 1.
+ *   publish != 0: the accumulation consists of this one micro-batch and `stash_bf16` IS the
+ *   communication buffer: comm[j] = bf16_rne(float(grad[j])) (the same bits, NaNs quieted).
+ * acco_accumulate_second: s = float(stash[j]) + float(grad[j]);  *count = 2 (it must be 1).
+ *   Exactly one of acc / comm_bf16 is non-NULL:
+ *   acc:       acc[j] = s - the fp32 accumulator continues with acco_accumulate(init = 0);
+ *   comm_bf16: comm_bf16[j] = bf16_rne(s) - second and last micro-batch, published at once.
+ *   stash_bf16, grad_bf16, comm_bf16: device, bf16[n]; acc: device, fp32[n].
+ * Errors: NULLs, bad n, misalignment, an output overlapping an input, *count != 1 for second.
+ */
+int acco_accumulate_first(uint16_t* stash_bf16, const uint16_t* grad_bf16, int64_t n, int publish,
+                          int64_t* count, void* stream);
+int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stash_bf16,
+                           const uint16_t* grad_bf16, int64_t n, int64_t* count, void* stream);
+
+/*
  * fp32 -> bf16, round to nearest even (NaN stays NaN, overflow goes to infinity).
  * Used for Buffer_i <- g_i (bf16 communication buffer) and for the bf16 parameter
  * shard handed to the All_Gather when the step kernels' fused output is not used.
@@ -265,7 +287,7 @@ int acco_version(void);
 /*
  * Launch shape used for subsequent calls of one entry point ("accumulate", "cast",
  * "reduce", "estimate", "commit", "accumulate_publish", "reduce_estimate", "reduce_commit",
- * "sgd"):
+ * "sgd", "stash", "second"):
  * threads per workgroup (64..512, multiple of 64),
  * 16-byte vectors each thread keeps in flight per array (1, 2 or 4), and workgroups
  * per compute unit (0 = one workgroup per tile, > 0 = grid-stride over that many

@@ -19,7 +19,8 @@ ACCO_ERR_ARG, ACCO_ERR_ALIAS, ACCO_ERR_DEVICE = -4, -5, -6
 ACCO_BF16, ACCO_F32 = 0, 1
 ACCO_MAX_WORKERS = 64
 
-EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_cast_params", "acco_reduce_shards",
+EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first",
+           "acco_accumulate_second", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_status_string", "acco_version", "acco_set_launch_shape")
@@ -70,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, play,
                                        p]
         L.acco_accumulate_publish.argtypes = [p, p, p, i64, ci, ci, pi64, p]
+        L.acco_accumulate_first.argtypes = [p, p, i64, ci, pi64, p]
+        L.acco_accumulate_second.argtypes = [p, p, p, p, i64, pi64, p]
         L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
                                                 p, p, i64, ctypes.POINTER(AdamW), i64, play, p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
@@ -222,6 +225,29 @@ def acco_accumulate_publish(acc, grad_bf16, comm_bf16, init: bool, keep_acc: boo
                                        int(bool(init)), int(bool(keep_acc)),
                                        None if count is None else count.ref(), _stream())
     _check(rc, "acco_accumulate_publish")
+
+
+def acco_accumulate_first(stash_bf16, grad_bf16, publish: bool = False,
+                          count: Optional[Counter] = None) -> None:
+    import torch
+    n = grad_bf16.numel()
+    rc = lib().acco_accumulate_first(_dev(stash_bf16, torch.bfloat16, n, "stash_bf16"),
+                                     _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
+                                     int(bool(publish)), None if count is None else count.ref(),
+                                     _stream())
+    _check(rc, "acco_accumulate_first")
+
+
+def acco_accumulate_second(stash_bf16, grad_bf16, *, acc=None, comm_bf16=None,
+                           count: Optional[Counter] = None) -> None:
+    import torch
+    n = grad_bf16.numel()
+    rc = lib().acco_accumulate_second(_opt(acc, torch.float32, n, "acc"),
+                                      _opt(comm_bf16, torch.bfloat16, n, "comm_bf16"),
+                                      _dev(stash_bf16, torch.bfloat16, n, "stash_bf16"),
+                                      _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
+                                      None if count is None else count.ref(), _stream())
+    _check(rc, "acco_accumulate_second")
 
 
 def acco_cast_params(out_bf16, src) -> None:

@@ -36,6 +36,8 @@ enum Entry {
     kReduceEstimate,
     kReduceCommit,
     kSgd,
+    kStash,
+    kSecond,
     kEntries
 };
 
@@ -51,11 +53,14 @@ LaunchShape g_shape[kEntries] = {
     {{64}, {1}, {0}},  // reduce_estimate
     {{64}, {1}, {0}},  // reduce_commit
     {{64}, {1}, {0}},  // sgd
+    {{64}, {1}, {0}},  // stash
+    {{64}, {1}, {0}},  // second
 };
 
 const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
                                            "estimate",           "commit",          "accumulate_publish",
-                                           "reduce_estimate",    "reduce_commit",   "sgd"};
+                                           "reduce_estimate",    "reduce_commit",   "sgd",
+                                           "stash",              "second"};
 
 int cu_count()
 {
@@ -96,7 +101,7 @@ Geometry geometry(Entry e, int64_t nvec)
 template <class Op>
 int launch(Entry e, const Op& op, int64_t n, hipStream_t stream)
 {
-    const int64_t  nvec = n / 4;
+    const int64_t  nvec = n / Op::kElems;
     const Geometry g    = geometry(e, nvec);
     if (g.vectors == 1 && (int64_t)g.grid.x >= g.tiles) {
         hipLaunchKernelGGL((flat_kernel<Op>), g.grid, dim3(g.threads), 0, stream, op, nvec, n);
@@ -224,6 +229,49 @@ ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, v
     if (overlap(out_bf16, n * 2, src, n * 4)) return ACCO_ERR_ALIAS;
     if (n == 0) return ACCO_OK;
     return launch(kCast, CastOp{out_bf16, src}, n, static_cast<hipStream_t>(stream));
+}
+
+
+ACCO_API int acco_accumulate_first(uint16_t* stash_bf16, const uint16_t* grad_bf16, int64_t n,
+                                   int publish, int64_t* count, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (publish != 0 && publish != 1) return ACCO_ERR_ARG;
+    if (n > 0 && (stash_bf16 == nullptr || grad_bf16 == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(stash_bf16) || !aligned16(grad_bf16)) return ACCO_ERR_ALIGN;
+    if (overlap(stash_bf16, n * 2, grad_bf16, n * 2)) return ACCO_ERR_ALIAS;
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        rc = publish ? launch(kStash, StashOp<true>{stash_bf16, grad_bf16}, n, s)
+                     : launch(kStash, StashOp<false>{stash_bf16, grad_bf16}, n, s);
+    }
+    if (rc == ACCO_OK && count != nullptr) *count = 1;
+    return rc;
+}
+
+ACCO_API int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stash_bf16,
+                                    const uint16_t* grad_bf16, int64_t n, int64_t* count,
+                                    void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && (acc == nullptr) == (comm_bf16 == nullptr)) return ACCO_ERR_NULL;  // one output
+    if (n > 0 && (stash_bf16 == nullptr || grad_bf16 == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(acc) || !aligned16(comm_bf16) || !aligned16(stash_bf16) || !aligned16(grad_bf16))
+        return ACCO_ERR_ALIGN;
+    if (count != nullptr && *count != 1) return ACCO_ERR_ARG;
+    const void* ins[2] = {stash_bf16, grad_bf16};
+    for (const void* in : ins)
+        if (overlap(acc, n * 4, in, n * 2) || overlap(comm_bf16, n * 2, in, n * 2))
+            return ACCO_ERR_ALIAS;
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        rc = acc != nullptr ? launch(kSecond, SecondOp{acc, stash_bf16, grad_bf16}, n, s)
+                            : launch(kSecond, SecondPublishOp{comm_bf16, stash_bf16, grad_bf16}, n, s);
+    }
+    if (rc == ACCO_OK && count != nullptr) *count = 2;
+    return rc;
 }
 
 namespace {

@@ -23,6 +23,7 @@ namespace acco {
 
 typedef float    f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 constexpr int kReduceChunk = 8;   // worker shards summed per launch
 constexpr int kMaxThreads = 512;  // per workgroup: leaves 256 VGPRs per lane for loads in flight
@@ -144,7 +145,8 @@ __device__ __forceinline__ void st(T* p, T x)
     __builtin_nontemporal_store(x, p);
 }
 
-// Op supplies: struct In; In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
+// Op supplies: kElems (elements per vector: 4, or 8 for all-bf16 kernels); struct In;
+//              In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
 //              void scalar(int64_t elem) const.
 template <int U, class Op>
 __global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Op op, const int64_t nvec,
@@ -166,7 +168,7 @@ __global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Op op, const 
         }
     }
     if (blockIdx.x == 0) {
-        const int64_t j = nvec * 4 + threadIdx.x;
+        const int64_t j = nvec * Op::kElems + threadIdx.x;
         if (j < n) op.scalar(j);
     }
 }
@@ -180,7 +182,7 @@ __global__ void __launch_bounds__(kMaxThreads) flat_kernel(const Op op, const in
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nvec) op.apply(i, op.load(i));
     if (blockIdx.x == 0) {
-        const int64_t j = nvec * 4 + threadIdx.x;
+        const int64_t j = nvec * Op::kElems + threadIdx.x;
         if (j < n) op.scalar(j);
     }
 }
@@ -189,6 +191,7 @@ __global__ void __launch_bounds__(kMaxThreads) flat_kernel(const Op op, const in
 
 template <bool INIT>
 struct AccumulateOp {
+    static constexpr int kElems = 4;
     float*          acc;
     const uint16_t* grad;
     struct In {
@@ -218,6 +221,7 @@ struct AccumulateOp {
 // (INIT: comm = bf16(grad)).  KEEP also stores the fp32 sum back to acc.
 template <bool INIT, bool KEEP>
 struct AccumulatePublishOp {
+    static constexpr int kElems = 4;
     float*          acc;
     const uint16_t* grad;
     uint16_t*       comm;
@@ -248,9 +252,107 @@ struct AccumulatePublishOp {
     }
 };
 
+// ------------------------------------------------------------------ first / second micro-batch
+
+// After the first micro-batch of an accumulation the accumulator equals that gradient, which
+// is exactly representable in bf16: it is kept as a bf16 "stash" (2 bytes written instead of
+// 4, 2 read back instead of 4).  All-bf16 kernels move 8 elements (16 bytes) per lane.
+
+// a NaN in either half-word gets its quiet bit, as the fp32 -> bf16 rounding would give it
+__device__ __forceinline__ uint32_t quiet_bf16x2(uint32_t p)
+{
+    const uint32_t lo = ((p & 0x00007FFFu) > 0x00007F80u) ? 0x00000040u : 0u;
+    const uint32_t hi = ((p & 0x7FFF0000u) > 0x7F800000u) ? 0x00400000u : 0u;
+    return p | lo | hi;
+}
+
+// stash = grad, or (QUIET) comm = bf16(float(grad)) for a one-micro-batch accumulation
+template <bool QUIET>
+struct StashOp {
+    static constexpr int kElems = 8;
+    uint16_t*            dst;
+    const uint16_t*      src;
+    struct In {
+        u4 x;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.x = ld(reinterpret_cast<const u4*>(src) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        u4 x = in.x;
+        if (QUIET) x = (u4){quiet_bf16x2(x.x), quiet_bf16x2(x.y), quiet_bf16x2(x.z), quiet_bf16x2(x.w)};
+        st(reinterpret_cast<u4*>(dst) + i, x);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        const uint32_t h = src[j];
+        dst[j]           = (uint16_t)(QUIET ? (quiet_bf16x2(h) & 0xFFFFu) : h);
+    }
+};
+
+// second micro-batch: acc = float(stash) + float(grad), fp32 accumulator from here on
+struct SecondOp {
+    static constexpr int kElems = 4;
+    float*               acc;
+    const uint16_t*      stash;
+    const uint16_t*      grad;
+    struct In {
+        u2 s, g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.s = ld(reinterpret_cast<const u2*>(stash) + i);
+        in.g = ld(reinterpret_cast<const u2*>(grad) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        st(reinterpret_cast<f4*>(acc) + i, unpack_bf16x4(in.s) + unpack_bf16x4(in.g));
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        acc[j] = __uint_as_float((uint32_t)stash[j] << 16) + __uint_as_float((uint32_t)grad[j] << 16);
+    }
+};
+
+// second and last micro-batch fused with the publish: comm = bf16(float(stash) + float(grad))
+struct SecondPublishOp {
+    static constexpr int kElems = 8;
+    uint16_t*            comm;
+    const uint16_t*      stash;
+    const uint16_t*      grad;
+    struct In {
+        u4 s, g;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.s = ld(reinterpret_cast<const u4*>(stash) + i);
+        in.g = ld(reinterpret_cast<const u4*>(grad) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        const u2 lo = pack_bf16x4(unpack_bf16x4((u2){in.s.x, in.s.y}) + unpack_bf16x4((u2){in.g.x, in.g.y}));
+        const u2 hi = pack_bf16x4(unpack_bf16x4((u2){in.s.z, in.s.w}) + unpack_bf16x4((u2){in.g.z, in.g.w}));
+        st(reinterpret_cast<u4*>(comm) + i, (u4){lo.x, lo.y, hi.x, hi.y});
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        comm[j] = (uint16_t)to_bf16_bits(__uint_as_float((uint32_t)stash[j] << 16) +
+                                         __uint_as_float((uint32_t)grad[j] << 16));
+    }
+};
+
 // ------------------------------------------------------------------ cast
 
 struct CastOp {
+    static constexpr int kElems = 4;
     uint16_t*    out;
     const float* src;
     struct In {
@@ -282,6 +384,7 @@ struct ShardPtrs {
 // from the value already in gsum, else from shard 0 as it is.
 template <int WMAX, bool BF16, bool ACC, bool BLOCKED>
 struct ReduceOp {
+    static constexpr int kElems = 4;
     float*             gsum;
     ShardPtrs          shards;
     int                workers;  // 1 .. WMAX
@@ -349,6 +452,7 @@ __device__ __forceinline__ void adamw_vec(f4 t, f4 m, f4 v, f4 g, const AdamScal
 // new theta.  BLOCKED: theta, m, v, gsum share a blocked layout.
 template <bool COMMIT, bool OUT_F32, bool OUT_BF16, bool BLOCKED>
 struct AdamOp {
+    static constexpr int kElems = 4;
     const float*       theta;
     const float*       m;
     const float*       v;
@@ -409,6 +513,7 @@ struct AdamOp {
 template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16,
           bool BLOCKED>
 struct ReduceAdamOp {
+    static constexpr int kElems = 4;
     const float*       theta;
     const float*       m;
     const float*       v;
@@ -510,6 +615,7 @@ __device__ __forceinline__ float sgd_elem(float theta, float gsum, const SgdScal
 
 template <bool COMMIT, bool OUT_F32, bool OUT_BF16>
 struct SgdOp {
+    static constexpr int kElems = 4;
     const float* theta;
     const float* gsum;
     float*       theta_w;

@@ -13,7 +13,9 @@ GPU's memory:
            reduce        acco_reduce_shards(accumulate onto the stage-1 sum)
            commit        acco_commit_step           (theta, m, v, step; fused bf16 theta)
 
-Two fusions give the same values with fewer passes over HBM:
+Options that give the same values with fewer bytes over HBM:
+  bf16_stash     the first micro-batch of an accumulation is kept as bf16 (exact) and the
+                 second adds to it in fp32 (acco_accumulate_first / acco_accumulate_second);
   fused_publish  the last micro-batch of a stage goes through acco_accumulate_publish,
                  which writes the bf16 communication buffer directly (the caller says which
                  micro-batch is the last one: ``last=True``);
@@ -31,7 +33,7 @@ class ShardOwner:
     def __init__(self, n: int, workers: int, hp: B.AdamW, *, device="cuda", comm_bf16: bool = True,
                  fused_bf16_out: bool = True, fused_publish: bool = False,
                  fused_reduce: bool = False, blocked_state: bool = False,
-                 block_elems: int = 8192):
+                 block_elems: int = 8192, bf16_stash: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -39,6 +41,7 @@ class ShardOwner:
         self.fused_bf16_out = fused_bf16_out
         self.fused_publish = fused_publish and comm_bf16
         self.fused_reduce = fused_reduce
+        self.bf16_stash = bf16_stash and comm_bf16
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self.state = None
@@ -56,6 +59,8 @@ class ShardOwner:
         self.acc: List = [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)]
         self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                            if comm_bf16 else [])
+        self.stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
+                            if self.bf16_stash else [])
         self.theta_tilde_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.theta_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.count = [B.Counter(0) for _ in range(workers)]   # N_i of the running accumulation
@@ -63,6 +68,7 @@ class ShardOwner:
         self.step = B.Counter(0)                              # committed updates
         self._fresh = [True] * workers                        # next accumulate starts a new sum
         self._published = [False] * workers                   # comm[w] already written this stage
+        self._stashed = [False] * workers                     # the sum so far sits in stash[w]
 
     # planar access to the state, whatever its layout
     def set_state(self, name: str, planar) -> None:
@@ -78,7 +84,24 @@ class ShardOwner:
     def add_microbatch(self, worker: int, grad_bf16, last: bool = False) -> None:
         """Accumulate one micro-batch gradient.  ``last`` marks the final micro-batch of the
         stage for this worker (used only with fused_publish)."""
-        if last and self.fused_publish:
+        publish = last and self.fused_publish
+        if self.bf16_stash and self._fresh[worker]:
+            # first micro-batch: kept as bf16; if it is also the last, it IS the published sum
+            B.acco_accumulate_first(self.comm[worker] if publish else self.stash[worker],
+                                    grad_bf16, publish, self.count[worker])
+            self._published[worker] = publish
+            self._stashed[worker] = not publish
+        elif self.bf16_stash and self._stashed[worker]:
+            # second micro-batch: stash + grad in fp32, to the accumulator or straight out
+            if publish:
+                B.acco_accumulate_second(self.stash[worker], grad_bf16,
+                                         comm_bf16=self.comm[worker], count=self.count[worker])
+                self._published[worker] = True
+            else:
+                B.acco_accumulate_second(self.stash[worker], grad_bf16, acc=self.acc[worker],
+                                         count=self.count[worker])
+            self._stashed[worker] = False
+        elif publish:
             B.acco_accumulate_publish(self.acc[worker], grad_bf16, self.comm[worker],
                                       self._fresh[worker], False, self.count[worker])
             self._published[worker] = True
@@ -91,7 +114,11 @@ class ShardOwner:
         if not self.comm_bf16:
             return self.acc
         for w in range(self.W):
-            if not self._published[w]:
+            if self._published[w]:
+                continue
+            if self._stashed[w]:      # one micro-batch only, not marked last: publish the stash
+                B.acco_accumulate_first(self.comm[w], self.stash[w], True)
+            else:
                 B.acco_cast_params(self.comm[w], self.acc[w])
         return self.comm
 
@@ -101,6 +128,7 @@ class ShardOwner:
     def _end_stage(self) -> None:
         self._fresh = [True] * self.W
         self._published = [False] * self.W
+        self._stashed = [False] * self.W
 
     # communication stream
     def stage1(self) -> None:

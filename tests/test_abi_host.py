@@ -351,3 +351,31 @@ def test_cosine_schedule_closed_forms_and_oracle():
     for bad in ((-1.0, 0.0, 0, 0, 10), (1.0, 2.0, 0, 0, 10), (1.0, 0.0, -1, 0, 10),
                 (1.0, 0.0, 0, -1, 10), (1.0, 0.0, 0, 20, 10), (float("nan"), 0.0, 0, 0, 10)):
         assert math.isnan(f(*bad))
+
+
+def test_first_and_second_micro_batch_entry_points_validation_and_counter():
+    L = B.lib()
+    first, second = L.acco_accumulate_first, L.acco_accumulate_second
+    c = ctypes.c_int64(7)
+    cr = ctypes.byref(c)
+    assert first(NONE, vp(Bp), 4, 0, cr, NONE) == B.ACCO_ERR_NULL
+    assert first(vp(A), NONE, 4, 0, cr, NONE) == B.ACCO_ERR_NULL
+    assert first(vp(A), vp(Bp), -1, 0, cr, NONE) == B.ACCO_ERR_SIZE
+    assert first(vp(A), vp(Bp), 4, 2, cr, NONE) == B.ACCO_ERR_ARG
+    assert first(vp(A + 2), vp(Bp), 4, 0, cr, NONE) == B.ACCO_ERR_ALIGN
+    assert first(vp(A), vp(A + 16), 64, 0, cr, NONE) == B.ACCO_ERR_ALIAS
+    assert c.value == 7
+    assert first(vp(A), vp(Bp), 0, 0, cr, NONE) == 0 and c.value == 1      # a new accumulation
+    # second: exactly one output, and the counter must stand at one
+    assert second(NONE, NONE, vp(C), vp(D), 4, cr, NONE) == B.ACCO_ERR_NULL
+    assert second(NONE, NONE, NONE, NONE, 0, NONE, NONE) == 0          # an empty shard
+    assert second(vp(A), vp(Bp), vp(C), vp(D), 4, cr, NONE) == B.ACCO_ERR_NULL
+    assert second(vp(A), NONE, NONE, vp(D), 4, cr, NONE) == B.ACCO_ERR_NULL
+    assert second(vp(A), NONE, vp(C), vp(D + 8), 4, cr, NONE) == B.ACCO_ERR_ALIGN
+    assert second(vp(A), NONE, vp(A), vp(D), 4, cr, NONE) == B.ACCO_ERR_ALIAS
+    assert second(NONE, vp(Bp), vp(C), vp(Bp), 4, cr, NONE) == B.ACCO_ERR_ALIAS
+    assert c.value == 1
+    assert second(vp(A), NONE, vp(C), vp(D), 0, cr, NONE) == 0 and c.value == 2
+    assert second(vp(A), NONE, vp(C), vp(D), 0, cr, NONE) == B.ACCO_ERR_ARG   # not the second
+    c.value = 1
+    assert second(NONE, vp(Bp), vp(C), vp(D), 0, cr, NONE) == 0 and c.value == 2

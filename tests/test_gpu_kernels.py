@@ -611,3 +611,56 @@ def test_degenerate_cases_of_the_method(acco):
     acco.acco_reduce_shards(g1, [bf16_tensor(s) for s in sh], False, [3, 0], tot)
     acco.acco_reduce_shards(g2, [bf16_tensor(sh[0])], False, [3], acco.Counter(0))
     assert tot.value == 3 and torch.equal(g1.view(torch.int32), g2.view(torch.int32))
+
+
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (256, 1, 0), (128, 2, 1), (512, 4, 0)])
+def test_bf16_stash_of_the_first_micro_batch_changes_no_bits(acco, shape):
+    acco.set_launch_shape("stash", *shape)
+    acco.set_launch_shape("second", *shape)
+    rng = np.random.default_rng(40)
+    for n in SIZES + [15, 16, 17, 8 * 64 + 7]:
+        log("stash", shape, n)
+        g0, g1, g2 = (_rand_bf16(rng, n) for _ in range(3))
+        if n > 4:
+            g0[0], g1[0] = 0x8000, 0x8000          # -0 + -0 stays -0
+            g0[1] = 0x7FA0                          # a signalling NaN pattern
+            g0[2], g1[2] = 0x7F80, 0xFF80          # inf - inf
+        d0, d1, d2 = bf16_tensor(g0), bf16_tensor(g1), bf16_tensor(g2)
+        # oracle: plain fp32 accumulation, published after 1, 2 and 3 micro-batches
+        acc_h = np.empty(n, np.float32)
+        oracle.accumulate(acc_h, g0, init=True)
+        pub1 = oracle.cast(acc_h)
+        oracle.accumulate(acc_h, g1, init=False)
+        acc2_h, pub2 = acc_h.copy(), oracle.cast(acc_h)
+        oracle.accumulate(acc_h, g2, init=False)
+        pub3 = oracle.cast(acc_h)
+        cnt = acco.Counter(9)
+        stash = torch.full((n,), 2.0, dtype=torch.bfloat16, device="cuda")
+        comm = torch.full((n,), 2.0, dtype=torch.bfloat16, device="cuda")
+        acc = torch.full((n,), 2.0, dtype=torch.float32, device="cuda")
+        # one micro-batch only: published directly
+        acco.acco_accumulate_first(comm, d0, True, cnt)
+        assert cnt.value == 1
+        got, nan = bits_of(comm), np.isnan(oracle.bf16_to_f32(pub1))
+        assert np.array_equal(got[~nan], pub1[~nan]) and np.array_equal(got[nan], pub1[nan])
+        # two micro-batches: stash, then second + publish
+        acco.acco_accumulate_first(stash, d0, False, cnt)
+        assert np.array_equal(bits_of(stash), g0)                 # a stash keeps the raw bits
+        acco.acco_accumulate_second(stash, d1, comm_bf16=comm, count=cnt)
+        assert cnt.value == 2
+        nan2 = np.isnan(acc2_h)
+        got = bits_of(comm)
+        assert np.array_equal(got[~nan2], pub2[~nan2])
+        assert np.all((got[nan2] & 0x7F80) == 0x7F80) and np.all((got[nan2] & 0x7F) != 0)
+        # three: stash, second into the fp32 accumulator, then the ordinary fused last one
+        cnt.value = 1
+        acco.acco_accumulate_second(stash, d1, acc=acc, count=cnt)
+        a = acc.cpu().numpy()
+        assert np.array_equal(a.view(np.uint32)[~nan2], acc2_h.view(np.uint32)[~nan2])
+        assert np.isnan(a[nan2]).all()
+        acco.acco_accumulate_publish(acc, d2, comm, False, False, cnt)
+        assert cnt.value == 3
+        got = bits_of(comm)
+        assert np.array_equal(got[~nan2], pub3[~nan2])
+    acco.set_launch_shape("stash", *DEFAULT_SHAPE)
+    acco.set_launch_shape("second", *DEFAULT_SHAPE)

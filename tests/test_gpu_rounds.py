@@ -31,7 +31,7 @@ def gpu_hyper(A, w):
 
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
-                 fused_publish=False, fused_reduce=False, blocked=False):
+                 fused_publish=False, fused_reduce=False, blocked=False, stash=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -39,7 +39,7 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
         f"({sum(b - a for a, b in slices)} elements checked)")
     owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
                          fused_bf16_out=fused, fused_publish=fused_publish,
-                         fused_reduce=fused_reduce, blocked_state=blocked)
+                         fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -124,6 +124,12 @@ def test_tiny_with_fused_publish_and_fused_reduce():
     run_workload(w, comm_bf16=False, fused_reduce=True, rounds=2)
 
 
+def test_tiny_with_bf16_stash():
+    w = synth.WORKLOADS["tiny"]
+    run_workload(w, stash=True)                                  # one micro-batch per stage
+    run_workload(w, stash=True, fused_publish=True, fused_reduce=True, blocked=True)
+
+
 def test_tiny_with_blocked_state():
     w = synth.WORKLOADS["tiny"]
     run_workload(w, blocked=True)
@@ -136,6 +142,8 @@ def test_ragged_small_shard_with_unequal_counts():
     run_workload(w)
     run_workload(w, fused_publish=True, fused_reduce=True)
     run_workload(w, fused_publish=True, fused_reduce=True, blocked=True)
+    run_workload(w, stash=True)                                  # 1 to 4 micro-batches per stage
+    run_workload(w, stash=True, fused_publish=True, fused_reduce=True, blocked=True)
 
 
 def test_gpt2_small_scale_shard_ten_rounds():
@@ -161,9 +169,10 @@ def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
 
 def test_seven_billion_scale_shard_fused_path_as_benched():
     # the configuration bench.py times by default: fused publish, fused reduce + step
-    run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, rounds=3)
+    run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
+                 stash=True, rounds=3)
 
 
 def test_seven_billion_hetero_blocked_state_fused_path():
     run_workload(synth.WORKLOADS["7b_hetero"], fused_publish=True, fused_reduce=True,
-                 blocked=True, rounds=2)
+                 blocked=True, stash=True, rounds=2)
