@@ -13,6 +13,18 @@ def pytest_configure(config):
 
 
 @pytest.fixture(scope="session", autouse=True)
+def _native_libraries():
+    """Load what is built; build only what is missing (hipcc cross-compiles without a GPU)."""
+    from paper_2406_02613_amd import build as acco_build
+    from synth import build as synth_build
+    if not os.path.exists(acco_build.ACCO_SO):
+        acco_build.build_acco()
+    if not os.path.exists(synth_build.DEVICE_SO):
+        synth_build.build_device()
+    yield
+
+
+@pytest.fixture(scope="session", autouse=True)
 def _oracle_threads():
     """Let the oracle use the cores this process may run on (results do not depend on it)."""
     import oracle
