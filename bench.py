@@ -44,8 +44,8 @@ MEASURED_TRAFFIC_B_PER_ELEM = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="7b",
                     help="tiny | gpt2s | 1b | 7b | 7b_hetero (default: the 875M-element shard)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -369,14 +369,39 @@ def cpu_baseline(w, target_seconds):
                     sh.stage2()
         return time.perf_counter() - t0
 
+    def commit_alone(S, R):
+        rng = np.random.default_rng(0)
+        th = w.host_theta(0, S)
+        m = np.zeros(S, np.float32)
+        v = np.zeros(S, np.float32)
+        g = (rng.standard_normal(S) * w.grad_std).astype(np.float32)
+        oracle.commit(th, m, v, g, hp, 1, 1, want_bf16=True)
+        t0 = time.perf_counter()
+        for r in range(R):
+            oracle.commit(th, m, v, g, hp, r + 2, 32, want_bf16=True)
+        return time.perf_counter() - t0
+
     S = int(min(w.n, 1 << 24))            # ~100 host bytes per sampled element
     rounds(min(S, 1 << 18), 1)            # page in, start the thread pool
     t1 = rounds(S, 1)
-    R = int(max(1, min(200, round(target_seconds / max(t1, 1e-6)))))
+    R = int(max(1, min(200, round(0.6 * target_seconds / max(t1, 1e-6)))))
     t = rounds(S, R)
+    tc = commit_alone(S, 20)
+    # the same oracle on one thread, on a smaller sample (about a fifth of the time budget)
+    oracle.set_threads(1)
+    S1 = int(min(S, 1 << 21))
+    t11 = rounds(S1, 1)
+    R1 = int(max(1, min(50, round(0.2 * target_seconds / max(t11, 1e-6)))))
+    ts = rounds(S1, R1)
+    tc1 = commit_alone(S1, 10)
+    oracle.set_threads(cores)
     return {"value": S * R / t, "unit": "elements/s", "cores": cores, "kind": "oracle",
             "sample": f"{R} full rounds of workload '{w.name}' on its first {S} shard elements "
-                      f"(binary64 form, {cores} OpenMP threads, {t:.1f} s)"}
+                      f"(binary64 form, {cores} OpenMP threads, {t:.1f} s)",
+            "commit_step_alone_elements_per_s": S * 20 / tc,
+            "single_thread": {"value": S1 * R1 / ts, "cores": 1,
+                              "commit_step_alone_elements_per_s": S1 * 10 / tc1,
+                              "sample": f"{R1} rounds on the first {S1} elements, {ts:.1f} s"}}
 
 
 def make_grads(torch, synth, w):
@@ -478,11 +503,32 @@ def main():
         avg_ms = sum(times) / len(times)
         bpe = kernel_bytes_per_elem(name, w.workers)
         gbs = bpe * w.n / (avg_ms * 1e-3) / 1e9
-        return {"avg_ms": round(avg_ms, 4), "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
+        return {"avg_ms": round(avg_ms, 4), "median_ms": round(sorted(times)[len(times) // 2], 4),
+                "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
                 "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                 "elements/s": w.n / (avg_ms * 1e-3)}
 
     standalone = {name: figures(times[1:], name) for name, times in solo.summary().items()}
+
+    # What the memory system gives for the same access patterns without the arithmetic
+    # (planar fp32 arrays borrowed from the accumulators): context for the figures above.
+    probe = EventLog(torch)
+    probe.enabled = True
+    if w.workers >= 4:
+        a4 = owner.acc[:4]
+        for _ in range(6):
+            probe.timed("copy", B.acco_probe_copy, a4[0], a4[1])
+            probe.timed("triad", B.acco_probe_triad, a4[0], a4[1], a4[2], a4[3])
+            probe.timed("memcpy", a4[2].copy_, a4[3])
+        torch.cuda.synchronize()
+    ceilings = {}
+    for name, bpe, label in (("copy", 8, "device_copy_kernel"), ("memcpy", 8, "hipMemcpy_d2d"),
+                             ("triad", 28, "triad_4_reads_3_writes_in_place")):
+        ts = probe.summary().get(name, [])[1:]
+        if ts:
+            ms = sum(ts) / len(ts)
+            ceilings[label] = {"avg_ms": round(ms, 4), "bytes_per_elem": bpe,
+                               "GB/s": round(bpe * w.n / (ms * 1e-3) / 1e9, 1)}
 
     kernels = {}
     for name, times in log.summary().items():
@@ -490,6 +536,7 @@ def main():
         bpe = kernel_bytes_per_elem(name, w.workers)
         gbs = bpe * w.n / (avg_ms * 1e-3) / 1e9
         kernels[name] = {"calls_per_step": len(times) / args.steps, "avg_ms": round(avg_ms, 4),
+                         "median_ms": round(sorted(times)[len(times) // 2], 4),
                          "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
                          "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                          "elements/s": w.n / (avg_ms * 1e-3)}
@@ -537,6 +584,8 @@ def main():
         # acco_commit_step / acco_estimate_step launched on their own after the timed region
         # (gsum already reduced): the kernels the bandwidth target of the benchmark spec is stated on
         "standalone_step_kernels": standalone,
+        # plain streaming kernels with the same access patterns and no arithmetic, same buffers
+        "memory_system_reference": ceilings,
     }
     if not args.no_cpu_baseline:
         del grads

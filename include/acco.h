@@ -279,6 +279,16 @@ int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* theta_bf16, 
 double acco_lr_cosine(double base_lr, double min_lr, int64_t step, int64_t warmup_steps,
                       int64_t total_steps);
 
+/*
+ * Bandwidth probes - NOT part of the method.  The access patterns of the kernels above without
+ * their arithmetic, so that a benchmark can report what the device's memory system gives for
+ * them next to the kernels' own figures.  Planar fp32 arrays, same conventions and errors.
+ *   acco_probe_copy:   dst[j] = src[j]                         (4 B read, 4 B written)
+ *   acco_probe_triad:  a[j] += d[j]; b[j] += d[j]; c[j] += d[j] (16 B read, 12 B written)
+ */
+int acco_probe_copy(float* dst, const float* src, int64_t n, void* stream);
+int acco_probe_triad(float* a, float* b, float* c, const float* d, int64_t n, void* stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* acco_status_string(int status);
 
@@ -288,7 +298,7 @@ int acco_version(void);
 /*
  * Launch shape used for subsequent calls of one entry point ("accumulate", "cast",
  * "reduce", "estimate", "commit", "accumulate_publish", "reduce_estimate", "reduce_commit",
- * "sgd", "stash", "second"):
+ * "sgd", "stash", "second", "probe"):
  * threads per workgroup (64..512, multiple of 64),
  * 16-byte vectors each thread keeps in flight per array (1, 2 or 4), and workgroups
  * per compute unit (0 = one workgroup per tile, > 0 = grid-stride over that many

@@ -23,7 +23,7 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_accumulate_second", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
-           "acco_lr_cosine", "acco_status_string", "acco_version", "acco_set_launch_shape")
+           "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape")
 
 
 class AdamW(ctypes.Structure):
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
+        L.acco_probe_copy.argtypes = [p, p, i64, p]
+        L.acco_probe_triad.argtypes = [p, p, p, p, i64, p]
         L.acco_lr_cosine.restype = ctypes.c_double
         L.acco_lr_cosine.argtypes = [ctypes.c_double, ctypes.c_double, i64, i64, i64]
         L.acco_status_string.restype = ctypes.c_char_p
@@ -381,3 +383,19 @@ def acco_lr_cosine(base_lr: float, min_lr: float, step: int, warmup_steps: int,
                    total_steps: int) -> float:
     return float(lib().acco_lr_cosine(float(base_lr), float(min_lr), int(step), int(warmup_steps),
                                       int(total_steps)))
+
+
+def acco_probe_copy(dst, src) -> None:
+    import torch
+    n = src.numel()
+    _check(lib().acco_probe_copy(_dev(dst, torch.float32, n, "dst"),
+                                 _dev(src, torch.float32, n, "src"), n, _stream()),
+           "acco_probe_copy")
+
+
+def acco_probe_triad(a, b, c, d) -> None:
+    import torch
+    n = a.numel()
+    f32 = torch.float32
+    _check(lib().acco_probe_triad(_dev(a, f32, n, "a"), _dev(b, f32, n, "b"), _dev(c, f32, n, "c"),
+                                  _dev(d, f32, n, "d"), n, _stream()), "acco_probe_triad")

@@ -38,6 +38,7 @@ enum Entry {
     kSgd,
     kStash,
     kSecond,
+    kProbe,
     kEntries
 };
 
@@ -55,12 +56,13 @@ LaunchShape g_shape[kEntries] = {
     {{64}, {1}, {0}},  // sgd
     {{64}, {1}, {0}},  // stash
     {{64}, {1}, {0}},  // second
+    {{64}, {1}, {0}},  // probe
 };
 
 const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
                                            "estimate",           "commit",          "accumulate_publish",
                                            "reduce_estimate",    "reduce_commit",   "sgd",
-                                           "stash",              "second"};
+                                           "stash",              "second",          "probe"};
 
 int cu_count()
 {
@@ -720,6 +722,31 @@ ACCO_API int acco_sgd_commit_step(float* theta, const float* gsum, uint16_t* the
     }
     if (rc == ACCO_OK) *step += 1;
     return rc;
+}
+
+ACCO_API int acco_probe_copy(float* dst, const float* src, int64_t n, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && (dst == nullptr || src == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(dst) || !aligned16(src)) return ACCO_ERR_ALIGN;
+    if (overlap(dst, n * 4, src, n * 4)) return ACCO_ERR_ALIAS;
+    if (n == 0) return ACCO_OK;
+    return launch(kProbe, ProbeCopyOp{dst, src}, n, static_cast<hipStream_t>(stream));
+}
+
+ACCO_API int acco_probe_triad(float* a, float* b, float* c, const float* d, int64_t n,
+                              void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && (a == nullptr || b == nullptr || c == nullptr || d == nullptr))
+        return ACCO_ERR_NULL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(d)) return ACCO_ERR_ALIGN;
+    const void* arr[4] = {a, b, c, d};
+    for (int i = 0; i < 4; ++i)
+        for (int j = i + 1; j < 4; ++j)
+            if (overlap(arr[i], n * 4, arr[j], n * 4)) return ACCO_ERR_ALIAS;
+    if (n == 0) return ACCO_OK;
+    return launch(kProbe, ProbeTriadOp{a, b, c, d}, n, static_cast<hipStream_t>(stream));
 }
 
 ACCO_API double acco_lr_cosine(double base_lr, double min_lr, int64_t step, int64_t warmup_steps,

@@ -649,4 +649,61 @@ struct SgdOp {
     }
 };
 
+// ------------------------------------------------------------------ bandwidth probes
+
+// Not part of the method: the access patterns of the step kernels without their arithmetic,
+// to measure on the same device what the memory system gives (reported beside the kernels).
+struct ProbeCopyOp {
+    static constexpr int kElems = 4;
+    float*               dst;
+    const float*         src;
+    struct In {
+        f4 x;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.x = ld(reinterpret_cast<const f4*>(src) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        st(reinterpret_cast<f4*>(dst) + i, in.x);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const { dst[j] = src[j]; }
+};
+
+// four fp32 arrays read, three of them written back in place (a += d, b += d, c += d)
+struct ProbeTriadOp {
+    static constexpr int kElems = 4;
+    float*               a;
+    float*               b;
+    float*               c;
+    const float*         d;
+    struct In {
+        f4 a, b, c, d;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.a = ld(reinterpret_cast<const f4*>(a) + i);
+        in.b = ld(reinterpret_cast<const f4*>(b) + i);
+        in.c = ld(reinterpret_cast<const f4*>(c) + i);
+        in.d = ld(reinterpret_cast<const f4*>(d) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        st(reinterpret_cast<f4*>(a) + i, in.a + in.d);
+        st(reinterpret_cast<f4*>(b) + i, in.b + in.d);
+        st(reinterpret_cast<f4*>(c) + i, in.c + in.d);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const
+    {
+        a[j] += d[j];
+        b[j] += d[j];
+        c[j] += d[j];
+    }
+};
+
 }  // namespace acco

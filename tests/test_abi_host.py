@@ -379,3 +379,15 @@ def test_first_and_second_micro_batch_entry_points_validation_and_counter():
     assert second(vp(A), NONE, vp(C), vp(D), 0, cr, NONE) == B.ACCO_ERR_ARG   # not the second
     c.value = 1
     assert second(NONE, vp(Bp), vp(C), vp(D), 0, cr, NONE) == 0 and c.value == 2
+
+
+def test_probe_entry_points_validate_like_the_rest():
+    L = B.lib()
+    assert L.acco_probe_copy(NONE, vp(A), 4, NONE) == B.ACCO_ERR_NULL
+    assert L.acco_probe_copy(vp(A), vp(A + 16), 64, NONE) == B.ACCO_ERR_ALIAS
+    assert L.acco_probe_copy(vp(A + 4), vp(Bp), 4, NONE) == B.ACCO_ERR_ALIGN
+    assert L.acco_probe_copy(vp(A), vp(Bp), 0, NONE) == 0
+    assert L.acco_probe_triad(vp(A), vp(Bp), vp(C), NONE, 4, NONE) == B.ACCO_ERR_NULL
+    assert L.acco_probe_triad(vp(A), vp(Bp), vp(A), vp(D), 4, NONE) == B.ACCO_ERR_ALIAS
+    assert L.acco_probe_triad(vp(A), vp(Bp), vp(C), vp(D), -1, NONE) == B.ACCO_ERR_SIZE
+    assert L.acco_probe_triad(vp(A), vp(Bp), vp(C), vp(D), 0, NONE) == 0

@@ -664,3 +664,17 @@ def test_bf16_stash_of_the_first_micro_batch_changes_no_bits(acco, shape):
         assert np.array_equal(got[~nan2], pub3[~nan2])
     acco.set_launch_shape("stash", *DEFAULT_SHAPE)
     acco.set_launch_shape("second", *DEFAULT_SHAPE)
+
+
+def test_bandwidth_probes_do_what_they_say(acco):
+    rng = np.random.default_rng(9)
+    for n in (0, 1, 5, 4096 + 3, 100_001):
+        a, b, c, d = (rng.standard_normal(n).astype(np.float32) for _ in range(4))
+        da, db, dc, dd = dev(a), dev(b), dev(c), dev(d)
+        out = torch.zeros(n, dtype=torch.float32, device="cuda")
+        acco.binding.acco_probe_copy(out, dd)
+        assert bit_mismatches(out.cpu().numpy(), d) == 0
+        acco.binding.acco_probe_triad(da, db, dc, dd)
+        for got, want in ((da, a + d), (db, b + d), (dc, c + d)):
+            assert bit_mismatches(got.cpu().numpy(), want.astype(np.float32)) == 0
+        assert bit_mismatches(dd.cpu().numpy(), d) == 0
