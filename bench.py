@@ -284,6 +284,7 @@ def bench_two_stream(args, torch, A, w):
         compute()
         B = A.binding
         B.acco_accumulate(own.acc[2], grad_source(0, 2, 0), False)
+    own.acc[2].zero_()
     mb_alone = timed(one_microbatch, 10)
 
     def comm_pair():

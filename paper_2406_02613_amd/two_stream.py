@@ -69,6 +69,9 @@ class TwoStreamOwner:
         self.acc = {1: torch.empty(n, dtype=f32, device=dev),      # g~ (consumed by stage 1)
                     2: torch.empty(n, dtype=f32, device=dev)}      # g  (consumed by stage 2)
         self.count = {1: B.Counter(0), 2: B.Counter(0)}
+        # the first micro-batch of each accumulation is kept as bf16 (exact), see binding
+        self.stash = {1: torch.empty(n, dtype=bf16, device=dev),
+                      2: torch.empty(n, dtype=bf16, device=dev)}
         self.comm0 = torch.empty(n, dtype=bf16, device=dev)
         self.params_bf16 = torch.empty(n, dtype=bf16, device=dev)   # Buffer_i as the compute side sees it
         self.total = B.Counter(0)
@@ -96,7 +99,10 @@ class TwoStreamOwner:
             start = torch.cuda.Event(enable_timing=True)
             done = torch.cuda.Event(enable_timing=True)
             start.record()
-            B.acco_cast_params(self.comm0, self.acc[stage])          # Buffer_i <- (N, g)
+            if self.count[stage].value == 1:                          # Buffer_i <- (N, g)
+                B.acco_accumulate_first(self.comm0, self.stash[stage], True)
+            else:
+                B.acco_cast_params(self.comm0, self.acc[stage])
             if transport is not None:
                 transport()
             shards = [self.comm0, *peers]
@@ -126,7 +132,13 @@ class TwoStreamOwner:
                 if compute is not None:
                     compute()                                         # forward/backward stand-in
                 g = next_grad(k)                                      # bf16 gradient of micro-batch k
-                B.acco_accumulate(self.acc[stage], g, k == 0, self.count[stage])
+                if k == 0:
+                    B.acco_accumulate_first(self.stash[stage], g, False, self.count[stage])
+                elif k == 1:
+                    B.acco_accumulate_second(self.stash[stage], g, acc=self.acc[stage],
+                                             count=self.count[stage])
+                else:
+                    B.acco_accumulate(self.acc[stage], g, False, self.count[stage])
                 k += 1
                 mark = torch.cuda.Event()
                 mark.record()
