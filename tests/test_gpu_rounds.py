@@ -11,7 +11,6 @@ import time
 import numpy as np
 import pytest
 
-import oracle
 import synth
 from parity import (OracleSlices, assert_bf16_close, assert_f32_close, bit_mismatches, bits_of,
                     gather, gpu_run_stage, oracle_warm_state)

@@ -6,7 +6,7 @@ import pytest
 import oracle
 import synth
 from oracle.schemes import OracleScheme
-from parity import assert_f32_close, bf16_tensor, bit_mismatches, bits_of
+from parity import assert_f32_close, bit_mismatches, bits_of
 from test_oracle_schemes import closed_form, quad_setup, run_quadratic
 
 pytestmark = pytest.mark.gpu
