@@ -95,7 +95,11 @@ Geometry geometry(Entry e, int64_t nvec)
     const int64_t tile   = (int64_t)g.threads * g.vectors;
     g.tiles              = (nvec + tile - 1) / tile;
     const int64_t want   = g.tiles < 1 ? 1 : g.tiles;  // the scalar tail still needs workgroup 0
-    const int64_t cap    = per_cu > 0 ? (int64_t)per_cu * cu_count() : (int64_t)1 << 30;
+    // a dispatch holds fewer than 2^32 work-items per dimension; shards too long for one
+    // workgroup per tile fall back to the looping kernel
+    const int64_t most   = (((int64_t)1 << 32) - 1) / g.threads;
+    const int64_t asked  = per_cu > 0 ? (int64_t)per_cu * cu_count() : most;
+    const int64_t cap    = asked < most ? asked : most;
     g.grid               = dim3((unsigned)(want < cap ? want : cap));
     return g;
 }

@@ -678,3 +678,24 @@ def test_bandwidth_probes_do_what_they_say(acco):
         for got, want in ((da, a + d), (db, b + d), (dc, c + d)):
             assert bit_mismatches(got.cpu().numpy(), want.astype(np.float32)) == 0
         assert bit_mismatches(dd.cpu().numpy(), d) == 0
+
+
+def test_shard_longer_than_one_dispatch_of_one_wave_workgroups(acco):
+    # 2^34 + 5 elements: more 64-thread tiles than one dispatch can hold work-items for, so the
+    # launch falls back to the looping kernel; byte offsets go beyond 2^36
+    n = (1 << 34) + 5
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 6 + (8 << 30):
+        pytest.skip("needs about 104 GB of free device memory")
+    w = synth.Workload(name="giant", n=n, workers=1, rounds=1, seed=33)
+    log("giant shard", n)
+    src = torch.empty(n, dtype=torch.float32, device="cuda")
+    w.device_theta(src)
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    acco.acco_cast_params(out, src)
+    torch.cuda.synchronize()
+    for a, b in ((0, 4099), ((1 << 33) + 1, (1 << 33) + 4100), (n - 4101, n)):
+        assert np.array_equal(bits_of(out[a:b]), oracle.cast(w.host_theta(a, b - a))), (a, b)
+    del src, out
+    torch.cuda.empty_cache()
