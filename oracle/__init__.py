@@ -43,6 +43,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_f32_to_bf16.restype = ctypes.c_uint16
         L.oracle_accumulate.argtypes = [p, p, i64, ci]
         L.oracle_accumulate.restype = None
+        L.oracle_accumulate_bf16.argtypes = [p, p, i64, ci]
+        L.oracle_accumulate_bf16.restype = None
         L.oracle_cast.argtypes = [p, p, i64]
         L.oracle_cast.restype = None
         L.oracle_reduce.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci]
@@ -102,6 +104,13 @@ def accumulate(acc: np.ndarray, grad_bf16: np.ndarray, init: bool) -> None:
     assert acc.shape == grad_bf16.shape
     lib().oracle_accumulate(_f32(acc).ctypes.data, _u16(grad_bf16).ctypes.data, acc.size,
                             int(bool(init)))
+
+
+def accumulate_bf16(acc_bf16: np.ndarray, grad_bf16: np.ndarray, init: bool) -> None:
+    """Running sum held in bf16 (the paper's own buffer precision, Sec. 4)."""
+    assert acc_bf16.shape == grad_bf16.shape
+    lib().oracle_accumulate_bf16(_u16(acc_bf16).ctypes.data, _u16(grad_bf16).ctypes.data,
+                                 acc_bf16.size, int(bool(init)))
 
 
 def cast(src: np.ndarray) -> np.ndarray:
@@ -174,21 +183,25 @@ def lr_cosine(base_lr: float, min_lr: float, step: int, warmup_steps: int,
 class OracleShard:
     """State and round sequencing of one shard owner (Alg. 1, communication stream).
 
-    Holds the fp32 shard (theta, m, v), the update index, and per-worker fp32
-    gradient accumulators with their micro-batch counts.  ``precision`` selects
+    Holds the fp32 shard (theta, m, v), the update index, and per-worker gradient
+    accumulators (fp32, or bf16 as in the paper's setup) with their micro-batch counts.  ``precision`` selects
     the binary64 textbook form or the binary32 form of the AdamW update.
     """
 
     def __init__(self, theta: np.ndarray, workers: int, hp: Hyper, *, m=None, v=None,
-                 step: int = 0, precision: str = "f64", comm_dtype: str = "bf16"):
+                 step: int = 0, precision: str = "f64", comm_dtype: str = "bf16",
+                 acc_dtype: str = "f32"):
         n = theta.size
         self.n, self.W, self.hp, self.precision = n, workers, hp, precision
         self.comm_dtype = comm_dtype
+        self.acc_dtype = acc_dtype     # "f32" accumulators, or "bf16" as in the paper's setup
+        assert acc_dtype in ("f32", "bf16") and (acc_dtype == "f32" or comm_dtype == "bf16")
         self.theta = theta.astype(np.float32, copy=True)
         self.m = np.zeros(n, np.float32) if m is None else m.astype(np.float32, copy=True)
         self.v = np.zeros(n, np.float32) if v is None else v.astype(np.float32, copy=True)
         self.step = int(step)          # number of committed updates so far
-        self.acc = [np.zeros(n, np.float32) for _ in range(workers)]
+        self.acc = [np.zeros(n, np.float32 if acc_dtype == "f32" else np.uint16)
+                    for _ in range(workers)]
         self.count = [0] * workers     # micro-batches in each worker's accumulator
         self.gsum = np.zeros(n, np.float32)
         self.total = 0                 # micro-batches summed into gsum
@@ -197,10 +210,13 @@ class OracleShard:
 
     # computation stream: g_i += grad ; N_i += 1
     def add_microbatch(self, worker: int, grad_bf16: np.ndarray) -> None:
-        accumulate(self.acc[worker], grad_bf16, init=(self.count[worker] == 0))
+        add = accumulate if self.acc_dtype == "f32" else accumulate_bf16
+        add(self.acc[worker], grad_bf16, init=(self.count[worker] == 0))
         self.count[worker] += 1
 
     def _publish(self) -> List[np.ndarray]:
+        if self.acc_dtype == "bf16":
+            return self.acc            # the accumulator is the communication buffer
         if self.comm_dtype == "bf16":
             return [cast(a) for a in self.acc]
         return self.acc

@@ -108,6 +108,23 @@ ORACLE_EXPORT void oracle_accumulate(float* acc, const uint16_t* grad_bf16, int6
     }
 }
 
+/* The same accumulation with the running sum itself held in bf16, which is the
+ * precision the paper's experimental setup (Sec. 4, "gradient accumulation and
+ * communication buffers" in bf16) gives the buffer: the two bf16 values are added
+ * exactly-rounded in binary32 and the sum is rounded to bf16, nearest-even.
+ * (A binary32 sum of two bf16 values followed by the bf16 rounding equals the
+ * directly rounded bf16 sum: 24 bits are more than 2*8+2.) */
+ORACLE_EXPORT void oracle_accumulate_bf16(uint16_t* acc_bf16, const uint16_t* grad_bf16, int64_t n,
+                                          int init)
+{
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < n; ++j) {
+        if (init) { acc_bf16[j] = grad_bf16[j]; continue; }
+        float s = oracle_bf16_to_f32(acc_bf16[j]) + oracle_bf16_to_f32(grad_bf16[j]);
+        acc_bf16[j] = oracle_f32_to_bf16(s);
+    }
+}
+
 /* Buffer_i <- g_i (bf16 communication buffer) and the bf16 parameter copy that
  * the All_Gather distributes. */
 ORACLE_EXPORT void oracle_cast(uint16_t* out_bf16, const float* in, int64_t n)

@@ -212,3 +212,29 @@ def test_slices_of_a_run_equal_the_run_on_the_whole_shard():
         assert np.array_equal(x[a:b].view(np.uint32), y.view(np.uint32))
     assert np.array_equal(full.theta_bf16[a:b], part.theta_bf16)
     assert np.array_equal(full.theta_tilde_bf16[a:b], part.theta_tilde_bf16)
+
+
+def test_bf16_accumulators_equal_fp32_accumulators_for_single_microbatch_stages():
+    """With one micro-batch per worker and stage, the published buffer is that gradient itself in
+    either precision (bf16 -> fp32 -> bf16 is the identity), so the trajectories coincide bit for
+    bit; with more micro-batches the bf16 running sum rounds after every add and only stays close."""
+    one = synth.Workload(name="k2", n=3000, workers=3, rounds=2, theta_dist="uniform",
+                         theta_param=0.05, grad_std=1e-3, k_range=(2, 2), seed=5)
+    many = synth.Workload(name="k6", n=3000, workers=3, rounds=2, theta_dist="uniform",
+                          theta_param=0.05, grad_std=1e-3, k_range=(6, 6), seed=5)
+    out = {}
+    for w in (one, many):
+        for acc_dtype in ("f32", "bf16"):
+            sh = oracle.OracleShard(w.host_theta(0, w.n), w.workers, _hp(w),
+                                    precision="f32", acc_dtype=acc_dtype)
+            for rnd in range(w.rounds):
+                _run_round(sh, w, rnd, 0, w.n)
+            out[w.name, acc_dtype] = sh
+    a, b = out["k2", "f32"], out["k2", "bf16"]
+    for name in ("theta", "m", "v"):
+        assert np.array_equal(getattr(a, name).view(np.uint32), getattr(b, name).view(np.uint32))
+    assert np.array_equal(a.theta_bf16, b.theta_bf16)
+    a, b = out["k6", "f32"], out["k6", "bf16"]
+    assert not np.array_equal(a.m.view(np.uint32), b.m.view(np.uint32))
+    # each rounding of the running sum is at most 2^-9 relative; three adds per stage
+    assert np.max(np.abs(a.m - b.m)) <= 3 * 2.0 ** -9 * np.max(np.abs(a.m))
