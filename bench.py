@@ -81,6 +81,10 @@ def parse():
     ap.add_argument("--no-bf16-stash", action="store_true",
                     help="expand the first micro-batch to the fp32 accumulator (acco_accumulate "
                          "init) instead of keeping it as a bf16 stash")
+    ap.add_argument("--bf16-accumulate", action="store_true",
+                    help="running sums held in bf16 as in the paper's own setup "
+                         "(acco_accumulate_bf16; the accumulator is the communication buffer). "
+                         "Changes the values: the sum is rounded after every micro-batch")
     ap.add_argument("--unfused-reduce", action="store_true",
                     help="acco_reduce_shards + acco_estimate/commit_step instead of the fused "
                          "reduce+step entry points")
@@ -126,7 +130,11 @@ def run_round(A, owner, w, grads, log, opt):
             for mb, g in enumerate(row):
                 init = mb == 0
                 last = opt.fused_publish and mb == len(row) - 1
-                if opt.bf16_stash and init:
+                if opt.bf16_accumulate:
+                    log.timed("accumulate_bf16_init" if init else "accumulate_bf16",
+                              B.acco_accumulate_bf16, owner.comm[wk], g, init, owner.count[wk])
+                    published[wk] = True
+                elif opt.bf16_stash and init:
                     log.timed("accumulate_first_publish" if last else "accumulate_first",
                               B.acco_accumulate_first, owner.comm[wk] if last else owner.stash[wk],
                               g, last, owner.count[wk])
@@ -185,6 +193,8 @@ def kernel_bytes_per_elem(name, workers):
         "reduce_init": red + 4, "reduce_accumulate": red + 8,
         "accumulate_publish": 4 + 2 + 2,           # acc read, grad read, bf16 comm written
         "accumulate_publish_init": 2 + 2,
+        "accumulate_bf16_init": 2 + 2,             # grad read, bf16 running sum written
+        "accumulate_bf16": 2 + 2 + 2,              # running sum and grad read, sum written
         "accumulate_first": 2 + 2,                 # grad read, bf16 stash written
         "accumulate_first_publish": 2 + 2,
         "accumulate_second": 2 + 2 + 4,            # stash, grad read; fp32 acc written
@@ -342,7 +352,7 @@ def bench_two_stream(args, torch, A, w):
     return 0
 
 
-def cpu_baseline(w, target_seconds):
+def cpu_baseline(w, target_seconds, acc_dtype="f32"):
     """The oracle (as it stands) on the first S elements of the same workload, one round."""
     import numpy as np
     import oracle
@@ -357,7 +367,8 @@ def cpu_baseline(w, target_seconds):
         grads = {st: [[synth.host_grad_bf16(w.grad_spec(0, st, wk, mb), 0, S)
                        for mb in range(w.stage_counts(0, st)[wk])] for wk in range(w.workers)]
                  for st in (synth.STAGE_TILDE, synth.STAGE_FULL)}
-        sh = oracle.OracleShard(w.host_theta(0, S), w.workers, hp, precision="f64")
+        sh = oracle.OracleShard(w.host_theta(0, S), w.workers, hp, precision="f64",
+                                acc_dtype=acc_dtype)
         t0 = time.perf_counter()
         for _ in range(R):
             for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
@@ -447,14 +458,17 @@ def main():
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          blocked_state=blocked, block_elems=args.block_elems,
-                         bf16_stash=not (args.no_bf16_stash or args.base_path))
-    w.device_theta(owner.acc[0])                      # a planar scratch the round overwrites
-    owner.set_state("theta", owner.acc[0])
+                         bf16_stash=not (args.no_bf16_stash or args.base_path),
+                         bf16_accumulate=args.bf16_accumulate)
+    scratch = (owner.acc if owner.acc else
+               [torch.empty(w.n, dtype=torch.float32, device="cuda") for _ in range(2)])
+    w.device_theta(scratch[0])                        # a planar scratch the round overwrites
+    owner.set_state("theta", scratch[0])
 
     grads, n_bufs = make_grads(torch, synth, w)
 
     if args.calibrate_copy:
-        owner.acc[1].copy_(owner.acc[0])       # planar fp32: 4n bytes read, 4n bytes written
+        scratch[1].copy_(scratch[0])           # planar fp32: 4n bytes read, 4n bytes written
         torch.cuda.synchronize()
 
     log = EventLog(torch)
@@ -464,6 +478,7 @@ def main():
         fused_publish = not (args.unfused_publish or args.base_path)
         fused_reduce = not (args.unfused_reduce or args.base_path)
         bf16_stash = not (args.no_bf16_stash or args.base_path)
+        bf16_accumulate = args.bf16_accumulate
 
     opt = Opt()
     for r in range(args.warmup):
@@ -515,7 +530,7 @@ def main():
     # (planar fp32 arrays borrowed from the accumulators): context for the figures above.
     probe = EventLog(torch)
     probe.enabled = True
-    if w.workers >= 4:
+    if len(owner.acc) >= 4:
         a4 = owner.acc[:4]
         for _ in range(6):
             probe.timed("copy", B.acco_probe_copy, a4[0], a4[1])
@@ -577,7 +592,8 @@ def main():
                                     "elements" if blocked else "planar"),
                    "fused_bf16_output": opt.fused_cast,
                    "fused_publish": opt.fused_publish,
-                   "bf16_stash_of_first_microbatch": opt.bf16_stash,
+                   "bf16_stash_of_first_microbatch": opt.bf16_stash and not opt.bf16_accumulate,
+                   "accumulator_dtype": "bf16" if opt.bf16_accumulate else "f32",
                    "fused_reduce": opt.fused_reduce,
                    "host_wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": roofline,
@@ -590,7 +606,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         del grads
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds,
+                                           "bf16" if args.bf16_accumulate else "f32")
     print(json.dumps(out))
     return 0
 

@@ -142,6 +142,20 @@ int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stas
                            const uint16_t* grad_bf16, int64_t n, int64_t* count, void* stream);
 
 /*
+ * The accumulation of Alg. 1 with the running sum itself held in bf16, the precision the
+ * paper's experimental setup (Sec. 4) gives its gradient-accumulation and communication
+ * buffers.  The accumulator then IS the communication buffer (no publish step):
+ *   acc_bf16[j] = init ? grad[j] : bf16_rne(float(acc_bf16[j]) + float(grad[j]));  *count += 1.
+ * The sum is rounded after every micro-batch (a running sum of equal terms stops growing after
+ * 256 of them); acco_accumulate keeps fp32 instead and is what the round uses by default.
+ *   acc_bf16   device, bf16[n], in/out (out only when init != 0)
+ *   grad_bf16  device, bf16[n], in
+ * Other arguments and errors as acco_accumulate.
+ */
+int acco_accumulate_bf16(uint16_t* acc_bf16, const uint16_t* grad_bf16, int64_t n, int init,
+                         int64_t* count, void* stream);
+
+/*
  * fp32 -> bf16, round to nearest even (NaN stays NaN, overflow goes to infinity).
  * Used for Buffer_i <- g_i (bf16 communication buffer) and for the bf16 parameter
  * shard handed to the All_Gather when the step kernels' fused output is not used.

@@ -20,7 +20,7 @@ ACCO_BF16, ACCO_F32 = 0, 1
 ACCO_MAX_WORKERS = 64
 
 EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first",
-           "acco_accumulate_second", "acco_cast_params", "acco_reduce_shards",
+           "acco_accumulate_second", "acco_accumulate_bf16", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape")
@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
                                        p]
         L.acco_accumulate_publish.argtypes = [p, p, p, i64, ci, ci, pi64, p]
         L.acco_accumulate_first.argtypes = [p, p, i64, ci, pi64, p]
+        L.acco_accumulate_bf16.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_accumulate_second.argtypes = [p, p, p, p, i64, pi64, p]
         L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
                                                 p, p, i64, ctypes.POINTER(AdamW), i64, play, p]
@@ -215,6 +216,16 @@ def acco_accumulate(acc, grad_bf16, init: bool, count: Optional[Counter] = None)
                                _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
                                int(bool(init)), None if count is None else count.ref(), _stream())
     _check(rc, "acco_accumulate")
+
+
+def acco_accumulate_bf16(acc_bf16, grad_bf16, init: bool, count: Optional[Counter] = None) -> None:
+    import torch
+    n = grad_bf16.numel()
+    rc = lib().acco_accumulate_bf16(_dev(acc_bf16, torch.bfloat16, n, "acc_bf16"),
+                                    _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
+                                    int(bool(init)), None if count is None else count.ref(),
+                                    _stream())
+    _check(rc, "acco_accumulate_bf16")
 
 
 def acco_accumulate_publish(acc, grad_bf16, comm_bf16, init: bool, keep_acc: bool = False,

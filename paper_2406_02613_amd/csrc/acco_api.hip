@@ -227,6 +227,29 @@ ACCO_API int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, i
     return rc;
 }
 
+ACCO_API int acco_accumulate_bf16(uint16_t* acc_bf16, const uint16_t* grad_bf16, int64_t n, int init,
+                                  int64_t* count, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && (acc_bf16 == nullptr || grad_bf16 == nullptr)) return ACCO_ERR_NULL;
+    if (!aligned16(acc_bf16) || !aligned16(grad_bf16)) return ACCO_ERR_ALIGN;
+    if (init != 0 && init != 1) return ACCO_ERR_ARG;
+    if (count != nullptr && !init &&
+        (*count < 0 || *count == std::numeric_limits<int64_t>::max()))
+        return ACCO_ERR_ARG;
+    if (overlap(acc_bf16, n * 2, grad_bf16, n * 2)) return ACCO_ERR_ALIAS;
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        // in place: every lane reads its own elements of the running sum before it writes them
+        rc = init ? launch(kStash, StashOp<false>{acc_bf16, grad_bf16}, n, s)
+                  : launch(kSecond, SecondPublishOp{acc_bf16, acc_bf16, grad_bf16}, n, s);
+    }
+    if (rc == ACCO_OK && count != nullptr) *count = init ? 1 : *count + 1;
+    return rc;
+}
+
 ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stream)
 {
     if (int rc = check_n(n)) return rc;

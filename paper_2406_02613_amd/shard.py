@@ -16,6 +16,9 @@ GPU's memory:
 Options that give the same values with fewer bytes over HBM:
   bf16_stash     the first micro-batch of an accumulation is kept as bf16 (exact) and the
                  second adds to it in fp32 (acco_accumulate_first / acco_accumulate_second);
+  bf16_accumulate  the running sum itself is bf16 and doubles as the communication buffer,
+                 the precision of the paper's own setup (acco_accumulate_bf16); this one does
+                 change the values: the sum is rounded after every micro-batch;
   fused_publish  the last micro-batch of a stage goes through acco_accumulate_publish,
                  which writes the bf16 communication buffer directly (the caller says which
                  micro-batch is the last one: ``last=True``);
@@ -33,7 +36,8 @@ class ShardOwner:
     def __init__(self, n: int, workers: int, hp: B.AdamW, *, device="cuda", comm_bf16: bool = True,
                  fused_bf16_out: bool = True, fused_publish: bool = False,
                  fused_reduce: bool = False, blocked_state: bool = False,
-                 block_elems: int = 8192, bf16_stash: bool = False):
+                 block_elems: int = 8192, bf16_stash: bool = False,
+                 bf16_accumulate: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -41,7 +45,10 @@ class ShardOwner:
         self.fused_bf16_out = fused_bf16_out
         self.fused_publish = fused_publish and comm_bf16
         self.fused_reduce = fused_reduce
-        self.bf16_stash = bf16_stash and comm_bf16
+        self.bf16_accumulate = bf16_accumulate
+        if bf16_accumulate and not comm_bf16:
+            raise ValueError("bf16 accumulation publishes bf16 buffers")
+        self.bf16_stash = bf16_stash and comm_bf16 and not bf16_accumulate
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self.state = None
@@ -56,7 +63,8 @@ class ShardOwner:
             self.m = torch.zeros(n, dtype=f32, device=dev)
             self.v = torch.zeros(n, dtype=f32, device=dev)
             self.gsum = torch.empty(n, dtype=f32, device=dev)
-        self.acc: List = [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)]
+        self.acc: List = ([] if bf16_accumulate else
+                          [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)])
         self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                            if comm_bf16 else [])
         self.stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
@@ -85,7 +93,11 @@ class ShardOwner:
         """Accumulate one micro-batch gradient.  ``last`` marks the final micro-batch of the
         stage for this worker (used only with fused_publish)."""
         publish = last and self.fused_publish
-        if self.bf16_stash and self._fresh[worker]:
+        if self.bf16_accumulate:
+            B.acco_accumulate_bf16(self.comm[worker], grad_bf16, self._fresh[worker],
+                                   self.count[worker])
+            self._published[worker] = True
+        elif self.bf16_stash and self._fresh[worker]:
             # first micro-batch: kept as bf16; if it is also the last, it IS the published sum
             B.acco_accumulate_first(self.comm[worker] if publish else self.stash[worker],
                                     grad_bf16, publish, self.count[worker])

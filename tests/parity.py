@@ -101,7 +101,7 @@ class OracleSlices:
     """The oracle run on a list of index ranges of a workload, one OracleShard per range."""
 
     def __init__(self, w: synth.Workload, slices: Sequence[Tuple[int, int]], precision: str,
-                 comm_dtype: str = "bf16", warm=None):
+                 comm_dtype: str = "bf16", warm=None, acc_dtype: str = "f32"):
         self.w, self.slices = w, list(slices)
         self.shards: List[oracle.OracleShard] = []
         for k, (a, b) in enumerate(self.slices):
@@ -109,10 +109,11 @@ class OracleSlices:
                 th, m, v = (x[a:b] for x in warm)
                 sh = oracle.OracleShard(th, w.workers, oracle_hyper(w), m=m, v=v,
                                         step=w.warm_steps, precision=precision,
-                                        comm_dtype=comm_dtype)
+                                        comm_dtype=comm_dtype, acc_dtype=acc_dtype)
             else:
                 sh = oracle.OracleShard(w.host_theta(a, b - a), w.workers, oracle_hyper(w),
-                                        precision=precision, comm_dtype=comm_dtype)
+                                        precision=precision, comm_dtype=comm_dtype,
+                                        acc_dtype=acc_dtype)
             self.shards.append(sh)
 
     def run_stage(self, rnd: int, stage: int) -> None:

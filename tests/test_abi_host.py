@@ -23,7 +23,7 @@ def vp(x):
 def test_every_symbol_declared_in_the_header_is_exported():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(acco_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(acco_[a-z0-9_]+)\s*\(", text))
     assert declared == set(B.EXPORTS)
     L = B.lib()
     for name in declared:
@@ -379,6 +379,23 @@ def test_first_and_second_micro_batch_entry_points_validation_and_counter():
     assert second(vp(A), NONE, vp(C), vp(D), 0, cr, NONE) == B.ACCO_ERR_ARG   # not the second
     c.value = 1
     assert second(NONE, vp(Bp), vp(C), vp(D), 0, cr, NONE) == 0 and c.value == 2
+
+
+def test_bf16_running_sum_entry_point_validation_and_counter():
+    f = B.lib().acco_accumulate_bf16
+    c = ctypes.c_int64(3)
+    cr = ctypes.byref(c)
+    assert f(NONE, vp(Bp), 4, 0, cr, NONE) == B.ACCO_ERR_NULL
+    assert f(vp(A), NONE, 4, 1, cr, NONE) == B.ACCO_ERR_NULL
+    assert f(vp(A), vp(Bp), -2, 0, cr, NONE) == B.ACCO_ERR_SIZE
+    assert f(vp(A), vp(Bp), 4, 2, cr, NONE) == B.ACCO_ERR_ARG
+    assert f(vp(A + 2), vp(Bp), 4, 0, cr, NONE) == B.ACCO_ERR_ALIGN
+    assert f(vp(A), vp(A + 16), 64, 0, cr, NONE) == B.ACCO_ERR_ALIAS
+    bad = ctypes.c_int64(-1)
+    assert f(vp(A), vp(Bp), 0, 0, ctypes.byref(bad), NONE) == B.ACCO_ERR_ARG and bad.value == -1
+    assert c.value == 3
+    assert f(NONE, NONE, 0, 0, cr, NONE) == 0 and c.value == 4            # an empty shard still counts
+    assert f(vp(A), vp(Bp), 0, 1, cr, NONE) == 0 and c.value == 1         # init starts a new sum
 
 
 def test_probe_entry_points_validate_like_the_rest():

@@ -666,6 +666,40 @@ def test_bf16_stash_of_the_first_micro_batch_changes_no_bits(acco, shape):
     acco.set_launch_shape("second", *DEFAULT_SHAPE)
 
 
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (256, 1, 0), (128, 2, 1), (512, 4, 0)])
+def test_bf16_running_sum_is_bit_exact(acco, shape):
+    """The paper's buffer precision (Sec. 4): the sum is rounded to bf16 after every micro-batch."""
+    acco.set_launch_shape("stash", *shape)
+    acco.set_launch_shape("second", *shape)
+    rng = np.random.default_rng(41)
+    for n in SIZES + [15, 16, 17, 8 * 64 + 7]:
+        log("bf16 running sum", shape, n)
+        acc_h = np.full(n, 0x4123, np.uint16)
+        acc_d = bf16_tensor(acc_h)
+        cnt = acco.Counter(5)
+        for k in range(4):
+            g = _rand_bf16(rng, n, scale=1e-3 * (1 + 30 * (k == 2)))   # one much larger term
+            if n > 4:
+                g[0] = 0x8000                       # -0 survives the init and -0 + -0
+                g[1] = 0x0001 if k % 2 else 0x8001  # subnormals cancel exactly
+                g[2] = 0x7F00 if k < 2 else 0x0000  # overflows to +inf at the second add
+            oracle.accumulate_bf16(acc_h, g, init=(k == 0))
+            acco.acco_accumulate_bf16(acc_d, bf16_tensor(g), k == 0, cnt)
+            assert cnt.value == k + 1
+            assert np.array_equal(bits_of(acc_d), acc_h), (n, k)
+        if n > 4:
+            assert acc_h[0] == 0x8000 and acc_h[2] == 0x7F80
+    # stagnation at 256: the closed form of a bf16 running sum of ones
+    ones = torch.ones(1000, dtype=torch.bfloat16, device="cuda")
+    acc = torch.empty_like(ones)
+    cnt = acco.Counter(0)
+    for k in range(300):
+        acco.acco_accumulate_bf16(acc, ones, k == 0, cnt)
+    assert cnt.value == 300 and torch.all(acc.float() == 256.0)
+    acco.set_launch_shape("stash", *DEFAULT_SHAPE)
+    acco.set_launch_shape("second", *DEFAULT_SHAPE)
+
+
 def test_bandwidth_probes_do_what_they_say(acco):
     rng = np.random.default_rng(9)
     for n in (0, 1, 5, 4096 + 3, 100_001):

@@ -30,7 +30,8 @@ def gpu_hyper(A, w):
 
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
-                 fused_publish=False, fused_reduce=False, blocked=False, stash=False):
+                 fused_publish=False, fused_reduce=False, blocked=False, stash=False,
+                 bf16_acc=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -38,7 +39,8 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
         f"({sum(b - a for a, b in slices)} elements checked)")
     owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
                          fused_bf16_out=fused, fused_publish=fused_publish,
-                         fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash)
+                         fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash,
+                         bf16_accumulate=bf16_acc)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -50,8 +52,9 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
         owner.step.value = w.warm_steps
     grad_buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
     comm = "bf16" if comm_bf16 else "f32"
-    ref32 = OracleSlices(w, slices, "f32", comm, warm)
-    ref64 = OracleSlices(w, slices, "f64", comm, warm)
+    acc_dtype = "bf16" if bf16_acc else "f32"
+    ref32 = OracleSlices(w, slices, "f32", comm, warm, acc_dtype)
+    ref64 = OracleSlices(w, slices, "f64", comm, warm, acc_dtype)
     exact = True
     for r in range(rounds):
         for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
@@ -127,6 +130,16 @@ def test_tiny_with_bf16_stash():
     w = synth.WORKLOADS["tiny"]
     run_workload(w, stash=True)                                  # one micro-batch per stage
     run_workload(w, stash=True, fused_publish=True, fused_reduce=True, blocked=True)
+
+
+def test_bf16_running_sums_as_in_the_papers_setup():
+    """Accumulators held in bf16 (paper, Sec. 4): different values from the fp32 accumulators,
+    and the oracle in the same mode must be met bit for bit."""
+    run_workload(synth.WORKLOADS["tiny"], bf16_acc=True)
+    w = synth.Workload(name="ragged16", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
+                       k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
+    run_workload(w, bf16_acc=True)
+    run_workload(w, bf16_acc=True, fused_reduce=True, blocked=True)
 
 
 def test_tiny_with_blocked_state():
