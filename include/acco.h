@@ -27,7 +27,10 @@
  *     are then not dereferenced and may be NULL (an empty tensor has no address).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on it and the call returns without waiting; host
- *     counters are updated before return.
+ *     counters are updated before return.  A call enqueues kernel launches only (no
+ *     memset, copy, allocation or synchronisation) with its scalars passed by value, so
+ *     it may be recorded by a stream capture; a replay repeats the device work with the
+ *     scalars of the recorded call and touches no host counter.
  *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
  *     is enqueued and no host counter is modified.
  *   - Thread-safe; no global mutable state besides cached device properties.

@@ -4,12 +4,13 @@
 //
 // A "vector" is 4 consecutive elements: 16 bytes of fp32 (one dwordx4 per lane) or
 // 8 bytes of bf16 (one dwordx2 per lane), so each wavefront instruction touches 1024
-// (512) contiguous bytes.
+// (512) contiguous bytes.  Kernels whose arrays are all bf16 take 8 elements (one
+// dwordx4) per lane instead.
 //   flat_kernel    one vector per thread, one tile per workgroup, no loop: the default;
 //   stream_kernel  grid-stride over tiles of T*U vectors, the loads of a thread's U
 //                  vectors of every input issued before the first use (kept selectable
 //                  through acco_set_launch_shape; slower at every size measured).
-// The last n % 4 elements are done one by one by workgroup 0.
+// The elements after the last whole vector are done one by one by workgroup 0.
 //
 // Arithmetic: fp32, one IEEE operation per written operation (compiled with
 // -ffp-contract=off; the fused multiply-adds below are explicit), correctly
@@ -112,8 +113,9 @@ struct AdamScalars {
 
 // AdamW with decoupled decay on theta(t), bias-corrected moments, eps added to the
 // bias-corrected root.  `/` and __builtin_sqrtf compile to the correctly rounded
-// sequences (the __fsqrt_rn intrinsic does not: it was measured 1 ulp off on gfx950).  The decay is theta - (lr wd) theta in one fused operation
-// (a pre-rounded factor 1 - lr wd would bias theta on every step).
+// sequences (the __fsqrt_rn intrinsic does not: it was measured 1 ulp off on gfx950).
+// The decay is theta - (lr wd) theta in one fused operation (a pre-rounded factor
+// 1 - lr wd would bias theta on every step).
 __device__ __forceinline__ void adamw_elem(float theta, float m, float v, float gsum,
                                            const AdamScalars& s, float& theta_o, float& m_o,
                                            float& v_o)
