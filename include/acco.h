@@ -325,6 +325,20 @@ int acco_version(void);
 int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,
                           int workgroups_per_cu);
 
+/*
+ * Upper bound on the wavefronts of one entry point's kernels that are resident on a compute
+ * unit at a time (0 = the hardware's limit, 32).  The streaming kernels use no LDS; the bound
+ * is enforced by reserving an unused slice of the CU's 160 KiB of LDS per workgroup, so that
+ * only so many workgroups fit.  Fewer resident wavefronts mean fewer distinct DRAM pages open
+ * at a time, which pays for the kernels that stream many arrays at once.  At least 3
+ * workgroups must fit (one workgroup can reserve at most 64 KiB).  Process-wide.  The
+ * library's defaults are per entry point (from 9 for the committed step to none for the
+ * cast); the variants that start a new sum (init != 0), which write more than they read,
+ * always run unbounded.
+ * Returns ACCO_ERR_ARG for an unknown name or a bound outside 0, 3..32.
+ */
+int acco_set_resident_waves(const char* entry, int waves_per_cu);
+
 #ifdef __cplusplus
 }
 #endif

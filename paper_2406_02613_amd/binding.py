@@ -23,7 +23,8 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_accumulate_second", "acco_accumulate_bf16", "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
-           "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape")
+           "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
+           "acco_set_resident_waves")
 
 
 class AdamW(ctypes.Structure):
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
         L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
+        L.acco_set_resident_waves.argtypes = [ctypes.c_char_p, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
         L.acco_probe_copy.argtypes = [p, p, i64, p]
@@ -106,6 +108,12 @@ def set_launch_shape(entry: str, threads: int, vectors_in_flight: int,
     rc = lib().acco_set_launch_shape(entry.encode(), threads, vectors_in_flight, workgroups_per_cu)
     if rc != ACCO_OK:
         raise AccoError(rc, "acco_set_launch_shape")
+
+
+def set_resident_waves(entry: str, waves_per_cu: int) -> None:
+    rc = lib().acco_set_resident_waves(entry.encode(), waves_per_cu)
+    if rc != ACCO_OK:
+        raise AccoError(rc, "acco_set_resident_waves")
 
 
 # ----------------------------------------------------------------------------- marshalling

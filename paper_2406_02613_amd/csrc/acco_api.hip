@@ -24,6 +24,7 @@ struct LaunchShape {
     std::atomic<int> threads;
     std::atomic<int> vectors;  // U: 16-byte vectors per thread per array in flight
     std::atomic<int> wg_per_cu;
+    std::atomic<int> resident;  // wavefronts resident per CU at most (0 = hardware limit)
 };
 
 enum Entry {
@@ -44,19 +45,24 @@ enum Entry {
 
 // One wavefront per workgroup, one vector per thread: the fastest shape measured for every
 // entry point at 875M elements (64 > 256 > 512 > 128 threads; looping variants slower still).
+// Last column: wavefronts resident per CU at most.  The kernels that stream many arrays run
+// faster with fewer wavefronts in flight than the hardware would admit (32): enough bytes are
+// outstanding to cover the memory latency with 8-12 of them, and fewer concurrent wavefronts
+// keep fewer DRAM pages open at a time.  Values from sweeps at 31M, 125M and 875M elements
+// (same optimum at all three; no effect on cache-resident sizes).
 LaunchShape g_shape[kEntries] = {
-    {{64}, {1}, {0}},  // accumulate
-    {{64}, {1}, {0}},  // cast
-    {{64}, {1}, {0}},  // reduce
-    {{64}, {1}, {0}},  // estimate
-    {{64}, {1}, {0}},  // commit
-    {{64}, {1}, {0}},  // accumulate_publish
-    {{64}, {1}, {0}},  // reduce_estimate
-    {{64}, {1}, {0}},  // reduce_commit
-    {{64}, {1}, {0}},  // sgd
-    {{64}, {1}, {0}},  // stash
-    {{64}, {1}, {0}},  // second
-    {{64}, {1}, {0}},  // probe
+    {{64}, {1}, {0}, {24}},  // accumulate          (+1-2 %)
+    {{64}, {1}, {0}, {0}},   // cast                (any bound is slower)
+    {{64}, {1}, {0}, {16}},  // reduce              (+3 %)
+    {{64}, {1}, {0}, {12}},  // estimate            (+8 %)
+    {{64}, {1}, {0}, {9}},   // commit              (+4 %)
+    {{64}, {1}, {0}, {24}},  // accumulate_publish  (+1 %)
+    {{64}, {1}, {0}, {10}},  // reduce_estimate     (+6 %)
+    {{64}, {1}, {0}, {9}},   // reduce_commit       (+3 %)
+    {{64}, {1}, {0}, {0}},   // sgd
+    {{64}, {1}, {0}, {0}},   // stash               (no gain inside a round)
+    {{64}, {1}, {0}, {18}},  // second              (+4 %)
+    {{64}, {1}, {0}, {0}},   // probe
 };
 
 const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
@@ -80,13 +86,23 @@ int cu_count()
 }
 
 struct Geometry {
-    int     threads;
-    int     vectors;
-    int64_t tiles;
-    dim3    grid;
+    int      threads;
+    int      vectors;
+    int64_t  tiles;
+    dim3     grid;
+    unsigned lds_bytes;  // reserved (unused) LDS per workgroup: bounds the resident workgroups
 };
 
-Geometry geometry(Entry e, int64_t nvec)
+constexpr int kLdsPerCu   = 160 * 1024;  // gfx950
+constexpr int kLdsGranule = 1280;
+
+// LDS reservation that lets exactly `groups` workgroups share a compute unit.
+unsigned lds_for_groups(int groups)
+{
+    return (unsigned)(kLdsPerCu / groups / kLdsGranule * kLdsGranule);
+}
+
+Geometry geometry(Entry e, int64_t nvec, bool bounded)
 {
     Geometry g;
     g.threads = g_shape[e].threads.load(std::memory_order_relaxed);
@@ -101,29 +117,35 @@ Geometry geometry(Entry e, int64_t nvec)
     const int64_t asked  = per_cu > 0 ? (int64_t)per_cu * cu_count() : most;
     const int64_t cap    = asked < most ? asked : most;
     g.grid               = dim3((unsigned)(want < cap ? want : cap));
+    const int resident   = g_shape[e].resident.load(std::memory_order_relaxed);
+    const int groups     = resident / (g.threads / 64);       // workgroups per CU
+    g.lds_bytes = (bounded && resident > 0) ? lds_for_groups(groups < 3 ? 3 : groups) : 0u;
     return g;
 }
 
+// bounded = false: ignore the entry's bound on resident wavefronts (kernels that write more
+// than they read want the full occupancy)
 template <class Op>
-int launch(Entry e, const Op& op, int64_t n, hipStream_t stream)
+int launch(Entry e, const Op& op, int64_t n, hipStream_t stream, bool bounded = true)
 {
     const int64_t  nvec = n / Op::kElems;
-    const Geometry g    = geometry(e, nvec);
+    const Geometry g    = geometry(e, nvec, bounded);
     if (g.vectors == 1 && (int64_t)g.grid.x >= g.tiles) {
-        hipLaunchKernelGGL((flat_kernel<Op>), g.grid, dim3(g.threads), 0, stream, op, nvec, n);
+        hipLaunchKernelGGL((flat_kernel<Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
+                           n);
         return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
     }
     switch (g.vectors) {
         case 1:
-            hipLaunchKernelGGL((stream_kernel<1, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<1, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
                                g.tiles, n);
             break;
         case 2:
-            hipLaunchKernelGGL((stream_kernel<2, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<2, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
                                g.tiles, n);
             break;
         default:
-            hipLaunchKernelGGL((stream_kernel<4, Op>), g.grid, dim3(g.threads), 0, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<4, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
                                g.tiles, n);
             break;
     }
@@ -219,7 +241,7 @@ ACCO_API int acco_accumulate(float* acc, const uint16_t* grad_bf16, int64_t n, i
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
         if (init)
-            rc = launch(kAccumulate, AccumulateOp<true>{acc, grad_bf16}, n, s);
+            rc = launch(kAccumulate, AccumulateOp<true>{acc, grad_bf16}, n, s, false);
         else
             rc = launch(kAccumulate, AccumulateOp<false>{acc, grad_bf16}, n, s);
     }
@@ -543,9 +565,9 @@ ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
         if (init && keep_acc)
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, true>{acc, grad_bf16, comm_bf16}, n, s);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, true>{acc, grad_bf16, comm_bf16}, n, s, false);
         else if (init)
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, false>{acc, grad_bf16, comm_bf16}, n, s);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, false>{acc, grad_bf16, comm_bf16}, n, s, false);
         else if (keep_acc)
             rc = launch(kAccumulatePublish, AccumulatePublishOp<false, true>{acc, grad_bf16, comm_bf16}, n, s);
         else
@@ -807,6 +829,22 @@ ACCO_API const char* acco_status_string(int status)
 ACCO_API int acco_version(void)
 {
     return 100;  // 0.1.0
+}
+
+ACCO_API int acco_set_resident_waves(const char* entry, int waves_per_cu)
+{
+    if (entry == nullptr) return ACCO_ERR_NULL;
+    // at least 3 workgroups must fit: one workgroup may reserve at most 64 KiB of LDS
+    if (waves_per_cu != 0 && (waves_per_cu < 3 || waves_per_cu > 32)) return ACCO_ERR_ARG;
+    for (int e = 0; e < kEntries; ++e) {
+        if (std::strcmp(entry, kEntryNames[e]) == 0) {
+            const int per_group = g_shape[e].threads.load(std::memory_order_relaxed) / 64;
+            if (waves_per_cu != 0 && waves_per_cu / per_group < 3) return ACCO_ERR_ARG;
+            g_shape[e].resident.store(waves_per_cu, std::memory_order_relaxed);
+            return ACCO_OK;
+        }
+    }
+    return ACCO_ERR_ARG;
 }
 
 ACCO_API int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,

@@ -175,6 +175,22 @@ def test_launch_shape_validation():
                 ("commit", 256, 2, -1), ("nope", 256, 2, 0)):
         with pytest.raises(B.AccoError):
             B.set_launch_shape(*bad)
+    B.set_launch_shape("commit", 64, 1, 0)
+
+
+def test_resident_wave_bound_validation():
+    for ok in (0, 3, 9, 32):
+        B.set_resident_waves("cast", ok)
+    for bad in (("cast", 1), ("cast", 2), ("cast", 33), ("cast", -4), ("nope", 8)):
+        with pytest.raises(B.AccoError):
+            B.set_resident_waves(*bad)
+    # the bound counts wavefronts: workgroups of four need room for at least three of them
+    B.set_launch_shape("cast", 256, 1, 0)
+    with pytest.raises(B.AccoError):
+        B.set_resident_waves("cast", 8)
+    B.set_resident_waves("cast", 12)
+    B.set_launch_shape("cast", 64, 1, 0)
+    B.set_resident_waves("cast", 0)
 
 
 def test_binding_rejects_host_tensors_before_touching_the_library():

@@ -700,6 +700,40 @@ def test_bf16_running_sum_is_bit_exact(acco, shape):
     acco.set_launch_shape("second", *DEFAULT_SHAPE)
 
 
+def test_resident_wave_bounds_change_no_bits(acco):
+    """The bound on resident wavefronts (an LDS reservation) is a scheduling knob only."""
+    rng = np.random.default_rng(43)
+    n = (1 << 20) + 37
+    hp, ohp = acco.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1), oracle.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+    th = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    m = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    v = (rng.standard_normal(n) ** 2 * 1e-8).astype(np.float32)
+    g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    want = [x.copy() for x in (th, m, v)]
+    want_bf16 = oracle.commit(*want, g, ohp, 7, 4, precision="f32")
+    try:
+        for shape, bound in (((64, 1, 0), 0), ((64, 1, 0), 3), ((64, 1, 0), 9), ((64, 1, 0), 32),
+                             ((256, 1, 0), 12), ((512, 4, 2), 24), ((512, 1, 0), 9)):
+            log("resident waves", shape, bound)
+            acco.set_launch_shape("commit", *shape)
+            acco.set_resident_waves("commit", 0)
+            if bound:
+                try:
+                    acco.set_resident_waves("commit", bound)
+                except acco.AccoError:
+                    assert bound // (shape[0] // 64) < 3          # refused, not mis-launched
+                    continue
+            d = [dev(x) for x in (th, m, v)]
+            out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            acco.acco_commit_step(*d, dev(g), hp, acco.Counter(6), 4, theta_bf16=out)
+            for got, w in zip(d, want):
+                assert bit_mismatches(got.cpu().numpy(), w) == 0
+            assert np.array_equal(bits_of(out), want_bf16)
+    finally:
+        acco.set_launch_shape("commit", *DEFAULT_SHAPE)
+        acco.set_resident_waves("commit", 9)
+
+
 def test_bandwidth_probes_do_what_they_say(acco):
     rng = np.random.default_rng(9)
     for n in (0, 1, 5, 4096 + 3, 100_001):
