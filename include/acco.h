@@ -33,7 +33,8 @@
  *     scalars of the recorded call and touches no host counter.
  *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
  *     is enqueued and no host counter is modified.
- *   - Thread-safe; no global mutable state besides cached device properties.
+ *   - Thread-safe; no global mutable state besides cached device properties and the
+ *     process-wide launch settings at the end of this header.
  */
 #ifndef ACCO_H
 #define ACCO_H

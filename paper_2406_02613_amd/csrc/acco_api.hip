@@ -828,7 +828,7 @@ ACCO_API const char* acco_status_string(int status)
 
 ACCO_API int acco_version(void)
 {
-    return 100;  // 0.1.0
+    return 200;  // 0.2.0
 }
 
 ACCO_API int acco_set_resident_waves(const char* entry, int waves_per_cu)
