@@ -394,6 +394,67 @@ def test_fused_reduce_steps_equal_the_separate_calls_and_the_oracle(acco, shape,
     acco.set_launch_shape("reduce_commit", *DEFAULT_SHAPE)
 
 
+def test_buffers_that_start_inside_an_allocation_and_guard_bands(acco):
+    """Every array is a view that starts 16 bytes (or a few multiples) into a larger allocation;
+    the elements just before and just after each view must come out untouched."""
+    rng = np.random.default_rng(88)
+    W, n, pad = 3, 70_001, 64                       # ragged: 70,001 = 4 * 17,500 + 1
+    ohp = oracle.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+    ghp = acco.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
+
+    def view(host, lead):                            # lead elements of guard before the data
+        dt = torch.bfloat16 if host.dtype == np.uint16 else torch.float32
+        big = torch.full((lead + n + pad,), 3.0, dtype=dt, device="cuda")
+        v = big[lead:lead + n]
+        v.copy_(bf16_tensor(host) if host.dtype == np.uint16 else dev(host))
+        return big, v
+
+    def guards_intact(big, lead):
+        return bool(torch.all(big[:lead] == 3.0)) and bool(torch.all(big[lead + n:] == 3.0))
+
+    theta, m, v, _ = _state(rng, n, "warm")
+    grads = [[_rand_bf16(rng, n) for _ in range(2)] for _ in range(W)]
+    # oracle
+    acc_h = [np.empty(n, np.float32) for _ in range(W)]
+    for w in range(W):
+        oracle.accumulate(acc_h[w], grads[w][0], init=True)
+        oracle.accumulate(acc_h[w], grads[w][1], init=False)
+    comm_h = [oracle.cast(a) for a in acc_h]
+    gz = np.zeros(n, np.float32)                     # stage-2 form: shards added onto gsum = 0
+    oracle.reduce(gz, comm_h, accumulate_=True)
+    t_h, m_h, v_h = theta.copy(), m.copy(), v.copy()
+    # GPU: fp32 views lead by 4, 8, 12, ... elements, bf16 views by 8, 16, ...
+    bt, td = view(theta, 4)
+    bm, md = view(m, 8)
+    bv, vd = view(v, 12)
+    bg, gd = view(np.zeros(n, np.float32), 16)
+    bo, od = view(np.zeros(n, np.uint16), 24)
+    comm, bigs = [], [(bt, 4), (bm, 8), (bv, 12), (bg, 16), (bo, 24)]
+    for w in range(W):
+        ba, ad = view(np.zeros(n, np.float32), 4 * (w + 1))
+        bc, cd = view(np.zeros(n, np.uint16), 8 * (w + 1))
+        b0, g0 = view(grads[w][0], 8 * (w + 2))
+        b1, g1 = view(grads[w][1], 8 * (w + 3))
+        bigs += [(ba, 4 * (w + 1)), (bc, 8 * (w + 1)), (b0, 8 * (w + 2)), (b1, 8 * (w + 3))]
+        cnt = acco.Counter(0)
+        acco.acco_accumulate(ad, g0, True, cnt)
+        acco.acco_accumulate_publish(ad, g1, cd, False, True, cnt)
+        assert bit_mismatches(ad.cpu().numpy(), acc_h[w]) == 0
+        comm.append(cd)
+    b16 = oracle.commit(t_h, m_h, v_h, gz, ohp, 3, 2 * W, precision="f32")
+    step, tot = acco.Counter(2), acco.Counter(0)
+    acco.acco_reduce_commit_step(td, md, vd, gd, comm, [2] * W, tot, ghp, step, theta_bf16=od)
+    assert step.value == 3 and tot.value == 2 * W
+    for d, h_ in ((td, t_h), (md, m_h), (vd, v_h)):
+        assert bit_mismatches(d.cpu().numpy(), h_) == 0
+    assert np.array_equal(bits_of(od), b16)
+    for big, lead in bigs:
+        assert guards_intact(big, lead)
+    # a view that starts 4 bytes in is refused, not mis-launched
+    with pytest.raises(acco.AccoError):
+        acco.acco_cast_params(od, bt[1:1 + n])
+
+
 # ------------------------------------------------------------------ blocked state layout
 
 
