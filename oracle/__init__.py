@@ -190,9 +190,10 @@ class OracleShard:
 
     def __init__(self, theta: np.ndarray, workers: int, hp: Hyper, *, m=None, v=None,
                  step: int = 0, precision: str = "f64", comm_dtype: str = "bf16",
-                 acc_dtype: str = "f32"):
+                 acc_dtype: str = "f32", lr_schedule=None):
         n = theta.size
         self.n, self.W, self.hp, self.precision = n, workers, hp, precision
+        self.lr_schedule = lr_schedule  # step (0-based) -> learning rate of that update
         self.comm_dtype = comm_dtype
         self.acc_dtype = acc_dtype     # "f32" accumulators, or "bf16" as in the paper's setup
         assert acc_dtype in ("f32", "bf16") and (acc_dtype == "f32" or comm_dtype == "bf16")
@@ -207,6 +208,12 @@ class OracleShard:
         self.total = 0                 # micro-batches summed into gsum
         self.theta_tilde_bf16: Optional[np.ndarray] = None
         self.theta_bf16: Optional[np.ndarray] = None
+
+    def _hp(self) -> Hyper:
+        if self.lr_schedule is None:
+            return self.hp
+        h = self.hp
+        return Hyper(float(self.lr_schedule(self.step)), h.beta1, h.beta2, h.eps, h.weight_decay)
 
     # computation stream: g_i += grad ; N_i += 1
     def add_microbatch(self, worker: int, grad_bf16: np.ndarray) -> None:
@@ -226,7 +233,7 @@ class OracleShard:
         assert all(c >= 1 for c in self.count)
         reduce(self.gsum, self._publish(), accumulate_=False)
         self.total = sum(self.count)                # All_Reduce of the counts
-        _, self.theta_tilde_bf16 = estimate(self.theta, self.m, self.v, self.gsum, self.hp,
+        _, self.theta_tilde_bf16 = estimate(self.theta, self.m, self.v, self.gsum, self._hp(),
                                             self.step + 1, self.total, want_f32=False,
                                             precision=self.precision)
         self.count = [0] * self.W
@@ -236,7 +243,7 @@ class OracleShard:
         assert all(c >= 1 for c in self.count)
         reduce(self.gsum, self._publish(), accumulate_=True)
         self.total += sum(self.count)
-        self.theta_bf16 = commit(self.theta, self.m, self.v, self.gsum, self.hp, self.step + 1,
+        self.theta_bf16 = commit(self.theta, self.m, self.v, self.gsum, self._hp(), self.step + 1,
                                  self.total, precision=self.precision)
         self.step += 1
         self.count = [0] * self.W

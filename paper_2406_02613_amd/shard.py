@@ -37,10 +37,14 @@ class ShardOwner:
                  fused_bf16_out: bool = True, fused_publish: bool = False,
                  fused_reduce: bool = False, blocked_state: bool = False,
                  block_elems: int = 8192, bf16_stash: bool = False,
-                 bf16_accumulate: bool = False):
+                 bf16_accumulate: bool = False, lr_schedule=None):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
+        # optional: lr_schedule(step) -> learning rate of update number `step` (0-based), e.g.
+        # lambda t: acco_lr_cosine(6e-4, 0.0, t, 0, 50000); both stages of a round use the
+        # rate of the update they estimate / commit
+        self.lr_schedule = lr_schedule
         self.comm_bf16 = comm_bf16
         self.fused_bf16_out = fused_bf16_out
         self.fused_publish = fused_publish and comm_bf16
@@ -134,6 +138,13 @@ class ShardOwner:
                 B.acco_cast_params(self.comm[w], self.acc[w])
         return self.comm
 
+    def _hp(self) -> B.AdamW:
+        if self.lr_schedule is None:
+            return self.hp
+        h = self.hp
+        return B.AdamW(float(self.lr_schedule(self.step.value)), h.beta1, h.beta2, h.eps,
+                       h.weight_decay)
+
     def _counts(self) -> List[int]:
         return [c.value for c in self.count]
 
@@ -147,11 +158,11 @@ class ShardOwner:
         shards = self._publish()
         if self.fused_reduce:
             B.acco_reduce_estimate_step(self.theta, self.m, self.v, self.gsum, shards,
-                                        self._counts(), self.total, self.hp, self.step.value,
+                                        self._counts(), self.total, self._hp(), self.step.value,
                                         theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
         else:
             B.acco_reduce_shards(self.gsum, shards, False, self._counts(), self.total, n=self.n)
-            B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step.value,
+            B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self._hp(), self.step.value,
                                  self.total.value, theta_tilde_bf16=self.theta_tilde_bf16,
                                  n=self.n)
         self._end_stage()
@@ -161,11 +172,11 @@ class ShardOwner:
         out = self.theta_bf16 if self.fused_bf16_out else None
         if self.fused_reduce:
             B.acco_reduce_commit_step(self.theta, self.m, self.v, self.gsum, shards,
-                                      self._counts(), self.total, self.hp, self.step,
+                                      self._counts(), self.total, self._hp(), self.step,
                                       theta_bf16=out, n=self.n)
         else:
             B.acco_reduce_shards(self.gsum, shards, True, self._counts(), self.total, n=self.n)
-            B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self.hp, self.step,
+            B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self._hp(), self.step,
                                self.total.value, theta_bf16=out, n=self.n)
         if not self.fused_bf16_out:
             if self.state is not None:

@@ -11,6 +11,7 @@ import time
 import numpy as np
 import pytest
 
+import oracle
 import synth
 from parity import (OracleSlices, assert_bf16_close, assert_f32_close, bit_mismatches, bits_of,
                     gather, gpu_run_stage, oracle_warm_state)
@@ -31,7 +32,7 @@ def gpu_hyper(A, w):
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
-                 bf16_acc=False):
+                 bf16_acc=False, schedules=None):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -40,7 +41,8 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
     owner = A.ShardOwner(w.n, w.workers, gpu_hyper(A, w), comm_bf16=comm_bf16,
                          fused_bf16_out=fused, fused_publish=fused_publish,
                          fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash,
-                         bf16_accumulate=bf16_acc)
+                         bf16_accumulate=bf16_acc,
+                         lr_schedule=None if schedules is None else schedules[0])
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -55,6 +57,9 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
     acc_dtype = "bf16" if bf16_acc else "f32"
     ref32 = OracleSlices(w, slices, "f32", comm, warm, acc_dtype)
     ref64 = OracleSlices(w, slices, "f64", comm, warm, acc_dtype)
+    if schedules is not None:
+        for sh in ref32.shards + ref64.shards:
+            sh.lr_schedule = schedules[1]
     exact = True
     for r in range(rounds):
         for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
@@ -140,6 +145,20 @@ def test_bf16_running_sums_as_in_the_papers_setup():
                        k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
     run_workload(w, bf16_acc=True)
     run_workload(w, bf16_acc=True, fused_reduce=True, blocked=True)
+
+
+def test_cosine_learning_rate_schedule_through_the_rounds():
+    """The paper's cosine schedule (App. C): the library's host helper on the GPU side, the
+    oracle's own on the other; the rate of an update is shared by its two stages."""
+    import paper_2406_02613_amd as A
+    w = synth.Workload(name="sched", n=200_000 + 5, workers=3, rounds=8, grad_std=1e-3,
+                       k_range=(2, 4), seed=6)
+    lr = w.hyper.lr
+    gpu = lambda t: A.acco_lr_cosine(lr, lr / 10, t, 2, 8)        # noqa: E731
+    cpu = lambda t: oracle.lr_cosine(lr, lr / 10, t, 2, 8)        # noqa: E731
+    run_workload(w, schedules=(gpu, cpu))
+    run_workload(w, schedules=(gpu, cpu), fused_publish=True, fused_reduce=True, blocked=True,
+                 stash=True)
 
 
 def test_tiny_with_blocked_state():

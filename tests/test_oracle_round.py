@@ -170,6 +170,39 @@ def test_rounds_follow_plain_adamw_on_the_full_batch_gradient(precision):
     assert sh.step == w.rounds
 
 
+def test_scheduled_rounds_follow_torch_adamw_under_cosine_annealing():
+    """Cosine schedule of the paper's hyper-parameter tables (App. C): the rate of update t is a
+    host scalar; the oracle's rounds with it track torch's AdamW + CosineAnnealingLR."""
+    T = 12                                            # short horizon: the rate really moves
+    w = synth.Workload(name="s", n=4000, workers=2, rounds=T, grad_std=1e-3, k_range=(2, 4),
+                       seed=23)
+    h = w.hyper
+    sched = lambda t: oracle.lr_cosine(h.lr, h.lr / 10, t, 0, T)      # noqa: E731
+    assert abs(sched(0) - h.lr) < 1e-18 and abs(sched(T) - h.lr / 10) < 1e-18 and sched(5) > sched(6)
+    sh = oracle.OracleShard(w.host_theta(0, w.n), w.workers, _hp(w), precision="f32",
+                            comm_dtype="f32", lr_schedule=sched)
+    p = torch.nn.Parameter(torch.from_numpy(w.host_theta(0, w.n).copy()))
+    opt = torch.optim.AdamW([p], lr=h.lr, betas=(h.beta1, h.beta2), eps=h.eps,
+                            weight_decay=h.weight_decay, foreach=False, fused=False)
+    lrs = torch.optim.lr_scheduler.CosineAnnealingLR(opt, T_max=T, eta_min=h.lr / 10)
+    for r in range(T):
+        assert abs(opt.param_groups[0]["lr"] - sched(r)) <= 1e-12 * h.lr
+        grads = []
+        _run_round(sh, w, r, 0, w.n, grads=grads)
+        gbar, _ = _brute_force_mean(grads, (1, 2))
+        p.grad = torch.from_numpy(gbar.astype(np.float32))
+        opt.step()
+        lrs.step()
+    drift = T * 2.0 ** -25
+    assert close(sh.theta, p.detach().numpy(), rel=TOL_REL + drift, abs_=TOL_ABS + drift * 0.1)
+    # and the schedule matters: a constant rate ends somewhere else
+    const = oracle.OracleShard(w.host_theta(0, w.n), w.workers, _hp(w), precision="f32",
+                               comm_dtype="f32")
+    for r in range(T):
+        _run_round(const, w, r, 0, w.n)
+    assert not close(const.theta, sh.theta, rel=1e-4, abs_=1e-6)
+
+
 def test_counters_match_a_recount_of_the_micro_batch_table():
     w = synth.WORKLOADS["7b_hetero"]
     small = synth.Workload(name="c", n=64, workers=w.workers, rounds=w.rounds, k_range=w.k_range,
