@@ -340,6 +340,10 @@ int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,
  */
 int acco_set_resident_waves(const char* entry, int waves_per_cu);
 
+/* Puts the launch shape and the resident-wavefront bound of every entry point back to the
+ * library's defaults. */
+void acco_reset_launch_settings(void);
+
 #ifdef __cplusplus
 }
 #endif

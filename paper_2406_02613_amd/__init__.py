@@ -6,7 +6,8 @@ from .binding import (ACCO_BF16, ACCO_F32, AccoError, AdamW, Counter, acco_accum
                       acco_estimate_step, acco_lr_cosine, acco_reduce_commit_step, acco_reduce_estimate_step,
                       acco_reduce_shards, acco_sgd_commit_step, acco_sgd_estimate_step, make_sgd,
                       Sgd,
-                      make_hyper, set_launch_shape, set_resident_waves, status_string,
+                      make_hyper, set_launch_shape, set_resident_waves, reset_launch_settings,
+                      status_string,
                       version)
 from .shard import ShardOwner
 from .state import BlockedState
@@ -20,4 +21,4 @@ __all__ = ["ACCO_BF16", "ACCO_F32", "AccoError", "AdamW", "Counter", "acco_accum
            "acco_cast_params", "acco_commit_step", "acco_estimate_step",
            "acco_lr_cosine", "acco_reduce_commit_step", "acco_reduce_estimate_step", "acco_reduce_shards",
            "acco_sgd_commit_step", "acco_sgd_estimate_step", "make_sgd", "Sgd", "SchemeOwner", "SCHEMES", "BlockedState", "TwoStreamOwner",
-           "make_hyper", "set_launch_shape", "set_resident_waves", "status_string", "version", "ShardOwner", "layout"]
+           "make_hyper", "set_launch_shape", "set_resident_waves", "reset_launch_settings", "status_string", "version", "ShardOwner", "layout"]

@@ -24,7 +24,7 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
-           "acco_set_resident_waves")
+           "acco_set_resident_waves", "acco_reset_launch_settings")
 
 
 class AdamW(ctypes.Structure):
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.acco_set_resident_waves.argtypes = [ctypes.c_char_p, ci]
         for name in EXPORTS:
             getattr(L, name).restype = ci
+        L.acco_reset_launch_settings.argtypes = []
+        L.acco_reset_launch_settings.restype = None
         L.acco_probe_copy.argtypes = [p, p, i64, p]
         L.acco_probe_triad.argtypes = [p, p, p, p, i64, p]
         L.acco_lr_cosine.restype = ctypes.c_double
@@ -108,6 +110,10 @@ def set_launch_shape(entry: str, threads: int, vectors_in_flight: int,
     rc = lib().acco_set_launch_shape(entry.encode(), threads, vectors_in_flight, workgroups_per_cu)
     if rc != ACCO_OK:
         raise AccoError(rc, "acco_set_launch_shape")
+
+
+def reset_launch_settings() -> None:
+    lib().acco_reset_launch_settings()
 
 
 def set_resident_waves(entry: str, waves_per_cu: int) -> None:

@@ -50,20 +50,39 @@ enum Entry {
 // outstanding to cover the memory latency with 8-12 of them, and fewer concurrent wavefronts
 // keep fewer DRAM pages open at a time.  Values from sweeps at 31M, 125M and 875M elements
 // (same optimum at all three; no effect on cache-resident sizes).
-LaunchShape g_shape[kEntries] = {
-    {{64}, {1}, {0}, {24}},  // accumulate          (+1-2 %)
-    {{64}, {1}, {0}, {0}},   // cast                (any bound is slower)
-    {{64}, {1}, {0}, {16}},  // reduce              (+3 %)
-    {{64}, {1}, {0}, {12}},  // estimate            (+8 %)
-    {{64}, {1}, {0}, {9}},   // commit              (+4 %)
-    {{64}, {1}, {0}, {24}},  // accumulate_publish  (+1 %)
-    {{64}, {1}, {0}, {10}},  // reduce_estimate     (+6 %)
-    {{64}, {1}, {0}, {9}},   // reduce_commit       (+3 %)
-    {{64}, {1}, {0}, {16}},  // sgd                 (+2-3 %)
-    {{64}, {1}, {0}, {0}},   // stash               (no gain inside a round)
-    {{64}, {1}, {0}, {18}},  // second              (+4 % with bf16 output; fp32 output: unbounded)
-    {{64}, {1}, {0}, {0}},   // probe
+struct ShapeDefault {
+    int threads, vectors, wg_per_cu, resident;
 };
+
+constexpr ShapeDefault kDefaults[kEntries] = {
+    {64, 1, 0, 24},  // accumulate          (+1-2 %)
+    {64, 1, 0, 0},   // cast                (any bound is slower)
+    {64, 1, 0, 16},  // reduce              (+3 %)
+    {64, 1, 0, 12},  // estimate            (+8 %)
+    {64, 1, 0, 9},   // commit              (+4 %)
+    {64, 1, 0, 24},  // accumulate_publish  (+1 %)
+    {64, 1, 0, 10},  // reduce_estimate     (+6 %)
+    {64, 1, 0, 9},   // reduce_commit       (+3 %)
+    {64, 1, 0, 16},  // sgd                 (+2-3 %)
+    {64, 1, 0, 0},   // stash               (no gain inside a round)
+    {64, 1, 0, 18},  // second              (+4 % with bf16 output; fp32 output: unbounded)
+    {64, 1, 0, 0},   // probe
+};
+
+LaunchShape g_shape[kEntries];
+
+void reset_shapes()
+{
+    for (int e = 0; e < kEntries; ++e) {
+        g_shape[e].threads.store(kDefaults[e].threads, std::memory_order_relaxed);
+        g_shape[e].vectors.store(kDefaults[e].vectors, std::memory_order_relaxed);
+        g_shape[e].wg_per_cu.store(kDefaults[e].wg_per_cu, std::memory_order_relaxed);
+        g_shape[e].resident.store(kDefaults[e].resident, std::memory_order_relaxed);
+    }
+}
+
+// the settings hold their defaults before any entry point can run
+[[maybe_unused]] const bool g_shapes_ready = (reset_shapes(), true);
 
 const char* const kEntryNames[kEntries] = {"accumulate",         "cast",            "reduce",
                                            "estimate",           "commit",          "accumulate_publish",
@@ -829,6 +848,11 @@ ACCO_API const char* acco_status_string(int status)
 ACCO_API int acco_version(void)
 {
     return 200;  // 0.2.0
+}
+
+ACCO_API void acco_reset_launch_settings(void)
+{
+    reset_shapes();
 }
 
 ACCO_API int acco_set_resident_waves(const char* entry, int waves_per_cu)

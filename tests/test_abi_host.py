@@ -175,7 +175,7 @@ def test_launch_shape_validation():
                 ("commit", 256, 2, -1), ("nope", 256, 2, 0)):
         with pytest.raises(B.AccoError):
             B.set_launch_shape(*bad)
-    B.set_launch_shape("commit", 64, 1, 0)
+    B.reset_launch_settings()
 
 
 def test_resident_wave_bound_validation():
@@ -189,8 +189,7 @@ def test_resident_wave_bound_validation():
     with pytest.raises(B.AccoError):
         B.set_resident_waves("cast", 8)
     B.set_resident_waves("cast", 12)
-    B.set_launch_shape("cast", 64, 1, 0)
-    B.set_resident_waves("cast", 0)
+    B.reset_launch_settings()
 
 
 def test_binding_rejects_host_tensors_before_touching_the_library():

@@ -791,8 +791,7 @@ def test_resident_wave_bounds_change_no_bits(acco):
                 assert bit_mismatches(got.cpu().numpy(), w) == 0
             assert np.array_equal(bits_of(out), want_bf16)
     finally:
-        acco.set_launch_shape("commit", *DEFAULT_SHAPE)
-        acco.set_resident_waves("commit", 9)
+        acco.reset_launch_settings()
 
 
 def test_bandwidth_probes_do_what_they_say(acco):
