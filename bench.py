@@ -510,6 +510,40 @@ def main():
     ms_total = t_start.elapsed_time(t_end)
     ms_per_step = ms_total / args.steps
 
+    # The same round on the five base entry points only (acco_accumulate, acco_cast_params as the
+    # publish, acco_reduce_shards, acco_estimate_step, acco_commit_step with its bf16 output),
+    # after the timed region and on the same buffers: what the fusions and the stash are worth.
+    base_round = None
+    if owner.acc and not args.base_path and not args.bf16_accumulate:
+        class BaseOpt:
+            fused_cast = opt.fused_cast
+            fused_publish = False
+            fused_reduce = False
+            bf16_stash = False
+            bf16_accumulate = False
+
+        blog = EventLog(torch)
+        run_round(A, owner, w, grads, blog, BaseOpt())
+        blog.enabled = True
+        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(2, min(5, args.steps))
+        b0.record()
+        for r in range(reps):
+            run_round(A, owner, w, grads, blog, BaseOpt())
+        b1.record()
+        torch.cuda.synchronize()
+        bms = b0.elapsed_time(b1) / reps
+        bbytes = sum(kernel_bytes_per_elem(k, w.workers) * len(v) / reps
+                     for k, v in blog.summary().items())
+        base_round = {"ms_per_step": round(bms, 4), "steps": reps,
+                      "elements/s": w.n / (bms * 1e-3), "bytes_per_elem": bbytes,
+                      "GB/s": round(bbytes * w.n / (bms * 1e-3) / 1e9, 1),
+                      "kernels": {k: {"calls_per_step": len(v) / reps,
+                                      "avg_ms": round(sum(v) / len(v), 4),
+                                      "GB/s": round(kernel_bytes_per_elem(k, w.workers) * w.n
+                                                    / (sum(v) / len(v) * 1e-3) / 1e9, 1)}
+                                  for k, v in blog.summary().items()}}
+
     # The committed and the speculative step on their own (gsum already reduced), after the
     # timed region: the kernels the benchmark spec's bandwidth target is stated on.  Same buffers.
     solo = EventLog(torch)
@@ -612,6 +646,8 @@ def main():
         # acco_commit_step / acco_estimate_step launched on their own after the timed region
         # (gsum already reduced): the kernels the bandwidth target of the benchmark spec is stated on
         "standalone_step_kernels": standalone,
+        # the round again on the five base entry points only (no fused entry point, no stash)
+        "base_entry_points_round": base_round,
         # plain streaming kernels with the same access patterns and no arithmetic, same buffers
         "memory_system_reference": ceilings,
         # The paper times whole training runs, not this path; its wall-clock table (ZeRO-1 vs
