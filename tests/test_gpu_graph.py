@@ -6,7 +6,6 @@ import numpy as np
 import pytest
 
 import oracle
-import synth
 from parity import bf16_tensor, bits_of
 
 pytestmark = pytest.mark.gpu
