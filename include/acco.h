@@ -138,6 +138,9 @@ int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* com
  *   acc:       acc[j] = s - the fp32 accumulator continues with acco_accumulate(init = 0);
  *   comm_bf16: comm_bf16[j] = bf16_rne(s) - second and last micro-batch, published at once.
  *   stash_bf16, grad_bf16, comm_bf16: device, bf16[n]; acc: device, fp32[n].
+ *   A caller whose first gradient stays untouched until the second arrives (backward wrote it
+ *   straight into the accumulation buffer) passes that buffer as stash_bf16 and needs no
+ *   acco_accumulate_first; it sets the counter to 1 itself.
  * Errors: NULLs, bad n, misalignment, an output overlapping an input, *count != 1 for second.
  */
 int acco_accumulate_first(uint16_t* stash_bf16, const uint16_t* grad_bf16, int64_t n, int publish,

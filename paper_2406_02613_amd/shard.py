@@ -16,6 +16,11 @@ GPU's memory:
 Options that give the same values with fewer bytes over HBM:
   bf16_stash     the first micro-batch of an accumulation is kept as bf16 (exact) and the
                  second adds to it in fp32 (acco_accumulate_first / acco_accumulate_second);
+  adopt_first    with bf16_stash: the first micro-batch's gradient buffer is used in place as
+                 the stash instead of being copied (saves that 4 B/elem pass).  The caller
+                 promises not to overwrite that buffer until the worker's next micro-batch has
+                 been added or the stage has run - what a framework gets when backward writes
+                 its first gradient of an accumulation straight into the accumulation buffer;
   bf16_accumulate  the running sum itself is bf16 and doubles as the communication buffer,
                  the precision of the paper's own setup (acco_accumulate_bf16); this one does
                  change the values: the sum is rounded after every micro-batch;
@@ -37,7 +42,7 @@ class ShardOwner:
                  fused_bf16_out: bool = True, fused_publish: bool = False,
                  fused_reduce: bool = False, blocked_state: bool = False,
                  block_elems: int = 8192, bf16_stash: bool = False,
-                 bf16_accumulate: bool = False, lr_schedule=None):
+                 bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -53,6 +58,7 @@ class ShardOwner:
         if bf16_accumulate and not comm_bf16:
             raise ValueError("bf16 accumulation publishes bf16 buffers")
         self.bf16_stash = bf16_stash and comm_bf16 and not bf16_accumulate
+        self.adopt_first = adopt_first and self.bf16_stash
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self.state = None
@@ -72,7 +78,7 @@ class ShardOwner:
         self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                            if comm_bf16 else [])
         self.stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
-                            if self.bf16_stash else [])
+                            if self.bf16_stash and not self.adopt_first else [None] * workers)
         self.theta_tilde_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.theta_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.count = [B.Counter(0) for _ in range(workers)]   # N_i of the running accumulation
@@ -101,6 +107,13 @@ class ShardOwner:
             B.acco_accumulate_bf16(self.comm[worker], grad_bf16, self._fresh[worker],
                                    self.count[worker])
             self._published[worker] = True
+        elif self.adopt_first and self._fresh[worker] and not publish:
+            # first micro-batch, used where it lies: no device work, only the bookkeeping
+            if grad_bf16.numel() != self.n or grad_bf16.dtype != self.torch.bfloat16:
+                raise ValueError("grad_bf16: wrong size or dtype")
+            self.stash[worker] = grad_bf16
+            self.count[worker].value = 1
+            self._stashed[worker] = True
         elif self.bf16_stash and self._fresh[worker]:
             # first micro-batch: kept as bf16; if it is also the last, it IS the published sum
             B.acco_accumulate_first(self.comm[worker] if publish else self.stash[worker],
@@ -109,6 +122,8 @@ class ShardOwner:
             self._stashed[worker] = not publish
         elif self.bf16_stash and self._stashed[worker]:
             # second micro-batch: stash + grad in fp32, to the accumulator or straight out
+            if self.adopt_first and grad_bf16.data_ptr() == self.stash[worker].data_ptr():
+                raise ValueError("the buffer adopted as the first micro-batch was reused")
             if publish:
                 B.acco_accumulate_second(self.stash[worker], grad_bf16,
                                          comm_bf16=self.comm[worker], count=self.count[worker])
@@ -152,6 +167,8 @@ class ShardOwner:
         self._fresh = [True] * self.W
         self._published = [False] * self.W
         self._stashed = [False] * self.W
+        if self.adopt_first:
+            self.stash = [None] * self.W          # the adopted buffers go back to the caller
 
     # communication stream
     def stage1(self) -> None:

@@ -133,11 +133,17 @@ class OracleSlices:
 # ------------------------------------------------------------------ GPU runs
 
 
-def gpu_run_stage(owner, w: synth.Workload, rnd: int, stage: int, grad_buf) -> None:
-    """Feed one stage of round rnd through the HIP library (full shard, device-generated)."""
+def gpu_run_stage(owner, w: synth.Workload, rnd: int, stage: int, grad_buf,
+                  fresh_buffers: bool = False) -> None:
+    """Feed one stage of round rnd through the HIP library (full shard, device-generated).
+    fresh_buffers: every micro-batch gradient gets a buffer of its own (instead of one buffer
+    that the next micro-batch overwrites), as an owner that adopts buffers needs."""
+    import torch
     counts = w.stage_counts(rnd, stage)
     for wk in range(w.workers):
         for mb in range(counts[wk]):
+            if fresh_buffers:
+                grad_buf = torch.empty_like(grad_buf)
             synth.device_grad_bf16(grad_buf, w.grad_spec(rnd, stage, wk, mb), 0)
             owner.add_microbatch(wk, grad_buf, last=(mb == counts[wk] - 1))
     if stage == synth.STAGE_TILDE:

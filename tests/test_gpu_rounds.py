@@ -32,7 +32,7 @@ def gpu_hyper(A, w):
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
-                 bf16_acc=False, schedules=None):
+                 bf16_acc=False, schedules=None, adopt=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -42,7 +42,8 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
                          fused_bf16_out=fused, fused_publish=fused_publish,
                          fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash,
                          bf16_accumulate=bf16_acc,
-                         lr_schedule=None if schedules is None else schedules[0])
+                         lr_schedule=None if schedules is None else schedules[0],
+                         adopt_first=adopt)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -64,7 +65,7 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
     for r in range(rounds):
         for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
             t0 = time.time()
-            gpu_run_stage(owner, w, r, stage, grad_buf)
+            gpu_run_stage(owner, w, r, stage, grad_buf, fresh_buffers=adopt)
             torch.cuda.synchronize()
             ref32.run_stage(r, stage)
             ref64.run_stage(r, stage)
@@ -159,6 +160,23 @@ def test_cosine_learning_rate_schedule_through_the_rounds():
     run_workload(w, schedules=(gpu, cpu))
     run_workload(w, schedules=(gpu, cpu), fused_publish=True, fused_reduce=True, blocked=True,
                  stash=True)
+
+
+def test_first_gradient_adopted_in_place_changes_no_bits():
+    """adopt_first: the first micro-batch's buffer serves as the stash where it lies."""
+    import paper_2406_02613_amd as A
+    w = synth.Workload(name="adopt", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
+                       k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
+    run_workload(w, stash=True, adopt=True)                       # 1 to 4 micro-batches per stage
+    run_workload(w, stash=True, adopt=True, fused_publish=True, fused_reduce=True, blocked=True)
+    run_workload(synth.WORKLOADS["tiny"], stash=True, adopt=True, fused_publish=True,
+                 fused_reduce=True)                               # one micro-batch per stage
+    # reusing the adopted buffer for the next micro-batch is caught
+    own = A.ShardOwner(64, 1, gpu_hyper(A, w), bf16_stash=True, adopt_first=True)
+    g = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    own.add_microbatch(0, g)
+    with pytest.raises(ValueError):
+        own.add_microbatch(0, g)
 
 
 def test_tiny_with_blocked_state():
