@@ -1,5 +1,5 @@
 // Device code of the ACCO shard path for gfx950: streaming kernels, all elementwise
-// and HBM-bound (no MFMA, no LDS), each built from an "Op" (what to load, what to
+// and HBM-bound (no MFMA, nothing staged in LDS), each built from an "Op" (what to load, what to
 // compute, what to store for one vector) and one of two drivers.
 //
 // A "vector" is 4 consecutive elements: 16 bytes of fp32 (one dwordx4 per lane) or
