@@ -122,7 +122,8 @@ class ShardOwner:
             self._stashed[worker] = not publish
         elif self.bf16_stash and self._stashed[worker]:
             # second micro-batch: stash + grad in fp32, to the accumulator or straight out
-            if self.adopt_first and grad_bf16.data_ptr() == self.stash[worker].data_ptr():
+            if (self.adopt_first and self.n > 0
+                    and grad_bf16.data_ptr() == self.stash[worker].data_ptr()):
                 raise ValueError("the buffer adopted as the first micro-batch was reused")
             if publish:
                 B.acco_accumulate_second(self.stash[worker], grad_bf16,
