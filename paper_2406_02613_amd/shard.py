@@ -143,6 +143,10 @@ class ShardOwner:
         self._fresh[worker] = False
 
     def _publish(self):
+        for w in range(self.W):
+            if self._fresh[w]:
+                raise ValueError(f"worker {w} has no micro-batch in this stage (Alg. 1 gives every "
+                                 "worker at least one gradient per accumulation)")
         if not self.comm_bf16:
             return self.acc
         for w in range(self.W):

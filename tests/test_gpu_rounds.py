@@ -179,6 +179,16 @@ def test_first_gradient_adopted_in_place_changes_no_bits():
         own.add_microbatch(0, g)
 
 
+def test_a_stage_without_a_gradient_from_every_worker_is_refused():
+    import paper_2406_02613_amd as A
+    w = synth.WORKLOADS["tiny"]
+    own = A.ShardOwner(256, 2, gpu_hyper(A, w))
+    own.add_microbatch(0, torch.zeros(256, dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(ValueError):
+        own.stage1()
+    assert own.step.value == 0 and own.total.value == 0
+
+
 def test_tiny_with_blocked_state():
     w = synth.WORKLOADS["tiny"]
     run_workload(w, blocked=True)
