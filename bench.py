@@ -1,20 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the ACCO per-shard optimizer path on one MI355X.
 
-A step is one ACCO round of one shard owner: every micro-batch gradient of every
-simulated worker is accumulated (fp32), each worker's sum is published to its bf16
-communication buffer, the owner reduces the W buffers, runs the speculative estimate
-step, then accumulates / publishes / reduces the second half onto the retained sum
-and runs the committed AdamW step with the fused bf16 parameter output.  All inputs
-(parameters, optimizer state, every micro-batch gradient of the round) are resident
-in HBM before the timed region starts.
+A step is one ACCO round of one shard owner, sequenced by paper_2406_02613_amd.ShardOwner (the
+same object the parity tests drive): every micro-batch gradient of every simulated worker is
+accumulated, each worker's sum is published to its bf16 communication buffer, the owner reduces
+the W buffers and runs the speculative estimate step, then the second half is accumulated,
+published and reduced onto the retained sum and the committed AdamW step runs with its fused
+bf16 parameter output.  All inputs (parameters, optimizer state, every micro-batch gradient of
+the round) are resident in HBM before the timed region starts.
 
-Prints ONE JSON line.  `value` is shard elements per second through one whole round;
-`roofline` is the committed-step kernel of the timed round (the fused reduce + commit), timed
-with HIP events on the launching stream inside the timed region; `kernels` carries the same
-figures for every kernel of the round; `standalone_step_kernels` times acco_commit_step and
-acco_estimate_step on their own afterwards; `cpu_baseline` is the CPU oracle timed on a
-bounded sample of the same workload on this machine's host cores.
+Prints ONE JSON line.
+  value        shard elements per second through one whole round
+  kernels      every kernel of the timed round, timed with HIP events on the launching stream
+  roofline     acco_commit_step (fused bf16 output) on its own, on the same buffers after the
+               timed region, at the workload's shard length and - for the two 875M-element
+               workloads - at both 875,000,000 and 875,000,037 elements; `in_timed_round`
+               inside it is the committed-step kernel of the timed round itself (the fused
+               reduce + commit)
+  checked      after the timed region the state (theta, m, v, both bf16 outputs) on sampled
+               index ranges is compared bit for bit with the CPU oracle's binary32 form replayed
+               for the same number of rounds on the same gradients
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload on this machine
+
+`bench.py --summarize-rocprof DIR` runs no GPU work: it formats rocprofv3 output found under DIR
+(kernel statistics, FETCH_SIZE / WRITE_SIZE counters) into the text summaries kept under
+profiles/.
 """
 from __future__ import annotations
 
@@ -29,16 +39,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
-
-# HBM bytes per element per launch measured with rocprofv3 counters (FETCH_SIZE x 2.0 +
-# WRITE_SIZE x 1.0, factors from a plain copy of known size in the same run) on workload '7b';
-# the commands and the raw figures are in profiles/bench_7b_hbm_traffic.txt.
-MEASURED_TRAFFIC_B_PER_ELEM = {
-    "7b": {"accumulate_init": 6.0, "accumulate": 10.0, "cast": 6.0, "reduce_init": 20.0,
-           "reduce_accumulate": 24.0, "estimate": 18.0, "commit_bf16": 30.0, "commit": 28.0,
-           "accumulate_publish": 8.0, "reduce_estimate": 34.0, "reduce_commit_bf16": 46.0,
-           "accumulate_first": 4.0, "accumulate_second_publish": 6.0},
-}
+HEADLINE_SIZES = (875_000_000, 875_000_037)   # the two shard lengths the bandwidth bar is set on
 
 
 def parse():
@@ -49,6 +50,11 @@ def parse():
     ap.add_argument("--workload", default="7b",
                     help="tiny | gpt2s | 1b | 7b | 7b_hetero (default: the 875M-element shard)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true",
+                    help="skip the comparison of the timed state with the oracle")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the base-entry-point round, the adopted-gradient round and the "
+                         "bandwidth probes (the headline step kernels are still timed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle sample")
     ap.add_argument("--scheme", default=None, choices=["acco", "ddp", "dpu", "wp"],
@@ -91,6 +97,13 @@ def parse():
     ap.add_argument("--base-path", action="store_true",
                     help="the five base entry points only (= all three --unfused-* flags "
                          "except the fused bf16 output of the commit)")
+    ap.add_argument("--per-worker-launches", action="store_true",
+                    help="one accumulate launch per worker and micro-batch instead of one launch "
+                         "for all workers that are at the same point of their accumulation")
+    ap.add_argument("--summarize-rocprof", metavar="DIR", default=None,
+                    help="no GPU work: format the rocprofv3 output under DIR (DIR/trace, "
+                         "DIR/fetch, DIR/write and the bench lines DIR/*.json written by the "
+                         "profiled runs) into profiles/bench_<workload>_*.txt")
     return ap.parse_args()
 
 
@@ -106,14 +119,15 @@ PAPER_CONTEXT = {
 
 
 class EventLog:
-    """HIP event pairs on torch's current stream (the stream every kernel is launched on)."""
+    """HIP event pairs on torch's current stream (the stream every kernel is launched on).
+    An instance is what ShardOwner.trace takes: log(label, fn, *args) runs fn between two events."""
 
     def __init__(self, torch):
         self.torch = torch
-        self.pairs = {}      # name -> list of (start, end)
+        self.pairs = {}      # label -> list of (start, end)
         self.enabled = False
 
-    def timed(self, name, fn, *a, **kw):
+    def __call__(self, name, fn, *a, **kw):
         if not self.enabled:
             return fn(*a, **kw)
         s = self.torch.cuda.Event(enable_timing=True)
@@ -124,85 +138,27 @@ class EventLog:
         self.pairs.setdefault(name, []).append((s, e))
         return out
 
+    timed = __call__
+
     def summary(self):
         return {k: [s.elapsed_time(e) for s, e in v] for k, v in self.pairs.items()}
 
 
-def run_round(A, owner, w, grads, log, opt):
-    """One ACCO round through the C ABI; grads[stage][worker][mb] are resident bf16 tensors.
-    opt.fused_publish / opt.fused_reduce / opt.fused_cast select the fused entry points."""
+def run_round(owner, w, grads):
+    """One ACCO round of the shard owner on resident gradients grads[stage][worker][mb]."""
     import synth
-    B = A.binding
     for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
-        first = stage == synth.STAGE_TILDE
-        published = [False] * w.workers
-        stash = [None] * w.workers
-        for wk in range(w.workers):
-            row = grads[stage][wk]
-            for mb, g in enumerate(row):
-                init = mb == 0
-                last = opt.fused_publish and mb == len(row) - 1
-                if opt.bf16_accumulate:
-                    log.timed("accumulate_bf16_init" if init else "accumulate_bf16",
-                              B.acco_accumulate_bf16, owner.comm[wk], g, init, owner.count[wk])
-                    published[wk] = True
-                elif opt.bf16_stash and init and getattr(opt, "adopt_first", False) and not last:
-                    stash[wk] = g                      # used where it lies: no device work
-                    owner.count[wk].value = 1
-                elif opt.bf16_stash and init:
-                    log.timed("accumulate_first_publish" if last else "accumulate_first",
-                              B.acco_accumulate_first, owner.comm[wk] if last else owner.stash[wk],
-                              g, last, owner.count[wk])
-                    published[wk] = last
-                    stash[wk] = owner.stash[wk]
-                elif opt.bf16_stash and mb == 1:
-                    if last:
-                        log.timed("accumulate_second_publish", B.acco_accumulate_second,
-                                  stash[wk], g, comm_bf16=owner.comm[wk],
-                                  count=owner.count[wk])
-                        published[wk] = True
-                    else:
-                        log.timed("accumulate_second", B.acco_accumulate_second, stash[wk],
-                                  g, acc=owner.acc[wk], count=owner.count[wk])
-                elif last:
-                    log.timed("accumulate_publish_init" if init else "accumulate_publish",
-                              B.acco_accumulate_publish, owner.acc[wk], g, owner.comm[wk], init,
-                              False, owner.count[wk])
-                    published[wk] = True
-                else:
-                    log.timed("accumulate_init" if init else "accumulate", B.acco_accumulate,
-                              owner.acc[wk], g, init, owner.count[wk])
-        for wk in range(w.workers):
-            if not published[wk]:
-                log.timed("cast", B.acco_cast_params, owner.comm[wk], owner.acc[wk])
-        counts = [c.value for c in owner.count]
-        out = owner.theta_bf16 if opt.fused_cast else None
-        if opt.fused_reduce and first:
-            log.timed("reduce_estimate", B.acco_reduce_estimate_step, owner.theta, owner.m,
-                      owner.v, owner.gsum, owner.comm, counts, owner.total, owner.hp,
-                      owner.step.value, theta_tilde_bf16=owner.theta_tilde_bf16, n=w.n)
-        elif opt.fused_reduce:
-            log.timed("reduce_commit_bf16" if opt.fused_cast else "reduce_commit",
-                      B.acco_reduce_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
-                      owner.comm, counts, owner.total, owner.hp, owner.step, theta_bf16=out,
-                      n=w.n)
+        rows = grads[stage]
+        owner.add_microbatch_rows(rows)
+        if stage == synth.STAGE_TILDE:
+            owner.stage1()
         else:
-            log.timed("reduce_init" if first else "reduce_accumulate", B.acco_reduce_shards,
-                      owner.gsum, owner.comm, not first, counts, owner.total, w.n)
-            if first:
-                log.timed("estimate", B.acco_estimate_step, owner.theta, owner.m, owner.v,
-                          owner.gsum, owner.hp, owner.step.value, owner.total.value,
-                          theta_tilde_bf16=owner.theta_tilde_bf16, n=w.n)
-            else:
-                log.timed("commit_bf16" if opt.fused_cast else "commit", B.acco_commit_step,
-                          owner.theta, owner.m, owner.v, owner.gsum, owner.hp, owner.step,
-                          owner.total.value, theta_bf16=out, n=w.n)
-        if not first and not opt.fused_cast:
-            log.timed("cast", B.acco_cast_params, owner.theta_bf16, owner.theta)
+            owner.stage2()
 
 
 def kernel_bytes_per_elem(name, workers):
-    """Algorithmic HBM bytes per shard element of one launch."""
+    """Algorithmic HBM bytes per shard element of one launch (per worker for the batched
+    accumulation launches, whose labels end in the number of workers they cover)."""
     from paper_2406_02613_amd import layout
     red = 2 * workers                              # W bf16 shards read
     table = {
@@ -219,6 +175,9 @@ def kernel_bytes_per_elem(name, workers):
         "reduce_commit": 12 + 4 + red + 12,        # theta,m,v,gsum + shards read; theta,m,v written
         "reduce_commit_bf16": 12 + 4 + red + 12 + 2,
     }
+    if "*" in name:                                # "label*k": one launch over k workers
+        base, k = name.split("*")
+        return int(k) * kernel_bytes_per_elem(base, workers)
     return table[name] if name in table else layout.BYTES_PER_ELEM[name]
 
 
@@ -432,6 +391,175 @@ def cpu_baseline(w, target_seconds, acc_dtype="f32"):
                               "sample": f"{R1} rounds on the first {S1} elements, {ts:.1f} s"}}
 
 
+# ------------------------------------------------------------------ rocprofv3 summaries
+
+# kernel-name fragment -> label of bench.py's kernel table ("*" = one launch over several workers)
+KERNEL_LABELS = (
+    ("Batch<acco::StashOp<false>", "accumulate_first*"),
+    ("Batch<acco::StashOp<true>", "accumulate_first_publish*"),
+    ("Batch<acco::SecondPublishOp", "accumulate_second_publish*"),
+    ("Batch<acco::SecondOp", "accumulate_second*"),
+    ("Batch<acco::AccumulateOp<true>", "accumulate_init*"),
+    ("Batch<acco::AccumulateOp<false>", "accumulate*"),
+    ("Batch<acco::AccumulatePublishOp<false, false>", "accumulate_publish*"),
+    ("Batch<acco::CastOp", "cast*"),
+    ("Single<acco::StashOp<false>", "accumulate_first"),
+    ("Single<acco::StashOp<true>", "accumulate_first_publish"),
+    ("Single<acco::SecondPublishOp", "accumulate_second_publish"),
+    ("Single<acco::SecondOp", "accumulate_second"),
+    ("Single<acco::AccumulateOp<true>", "accumulate_init"),
+    ("Single<acco::AccumulateOp<false>", "accumulate"),
+    ("Single<acco::AccumulatePublishOp<false, false>", "accumulate_publish"),
+    ("Single<acco::AccumulatePublishOp<true, false>", "accumulate_publish_init"),
+    ("Single<acco::CastOp", "cast"),
+    ("ReduceAdamOp<false, true, false, true, false, true", "reduce_estimate"),
+    ("ReduceAdamOp<true, true, true, false, false, true", "reduce_commit_bf16"),
+    ("ReduceAdamOp<true, true, true, false, false, false", "reduce_commit"),
+    ("Single<acco::AdamOp<true, false, true", "commit_bf16"),
+    ("Single<acco::AdamOp<true, false, false", "commit"),
+    ("Single<acco::AdamOp<false, false, true", "estimate"),
+    ("ReduceOp<8, true, false", "reduce_init"),
+    ("ReduceOp<8, true, true", "reduce_accumulate"),
+)
+
+
+def _short_kernel(name):
+    import re
+    name = name.replace("void acco::flat_kernel<acco::", "").replace("void acco::stream_kernel<", "")
+    name = name.replace("(anonymous namespace)::", "").replace("acco::", "")
+    return re.sub(r" ?>?\(.*$", "", name)
+
+
+def _label_of(kernel_name, grid_size, n):
+    """bench label of a dispatch; batched launches get their worker count from the grid."""
+    for frag, label in KERNEL_LABELS:
+        if frag in kernel_name:
+            if label.endswith("*"):
+                per_lane = 8 if ("StashOp" in frag or "SecondPublishOp" in frag) else 4
+                one = -(-(n // per_lane) // 64) * 64          # work-items of one worker's row
+                return label + str(max(1, round(grid_size / one)))
+            return label
+    return None
+
+
+def summarize_rocprof(raw):
+    """Text summaries under profiles/ from rocprofv3 output.  For every bench line raw/TAG.json:
+    raw/TAG/*_kernel_stats.csv (a --kernel-trace --stats run of the command in raw/TAG.cmd) ->
+    profiles/TAG_kernel_stats.txt; raw/TAG_fetch and raw/TAG_write (--pmc FETCH_SIZE /
+    WRITE_SIZE runs with --calibrate-copy) -> profiles/TAG_hbm_traffic.txt."""
+    import collections
+    import csv
+    import glob
+    wrote = []
+    for jpath in sorted(glob.glob(os.path.join(raw, "*.json"))):
+        tag = os.path.basename(jpath)[:-5]
+        try:
+            line = json.loads(open(jpath).read().strip().splitlines()[-1])
+        except (ValueError, IndexError):
+            continue
+        cfg = line.get("config", {})
+        n, workers = cfg.get("n"), cfg.get("workers")
+        cmd = lambda t: (open(os.path.join(raw, t + ".cmd")).read().strip()    # noqa: E731
+                         if os.path.exists(os.path.join(raw, t + ".cmd")) else "(not recorded)")
+        stats = glob.glob(os.path.join(raw, tag, "*_kernel_stats.csv"))
+        if stats:
+            out = [f"rocprofv3 kernel statistics - {line.get('metric', '')}",
+                   f"workload: {cfg.get('workload', '?')}", "",
+                   "Command (from /tmp with TMPDIR=/tmp on the MI355X box; $R = repository root):",
+                   "  " + cmd(tag), "",
+                   f"{'kernel':72s} {'calls':>6s} {'avg_ns':>10s} {'min_ns':>10s} {'max_ns':>10s} {'%':>6s}"]
+            rows = list(csv.DictReader(open(stats[0])))
+            for r in rows[:28]:
+                out.append(f"{_short_kernel(r['Name'])[:72]:72s} {r['Calls']:>6s} "
+                           f"{float(r['AverageNs']):10.0f} {r['MinNs']:>10s} {r['MaxNs']:>10s} "
+                           f"{float(r['Percentage']):6.2f}")
+            ks = line.get("kernels")
+            if isinstance(ks, dict) and n:
+                out += ["", "Same run, bench.py's own HIP-event timing (timed rounds only):"]
+                for k, v in ks.items():
+                    out.append(f"  {k:30s} {v['calls_per_step']:5.1f} calls/round  avg {v['avg_ms']:.4f} ms"
+                               f"  {v['bytes_per_elem']:3d} B/elem  {v['GB/s']:7.1f} GB/s  "
+                               f"{100 * v['frac_of_peak']:.1f} % of 8 TB/s")
+                out.append(f"  whole round: {line['ms_per_step']:.3f} ms -> {line['value']:.4g} shard "
+                           f"elements/s; checked against the oracle: {line.get('checked')}")
+                # rocprofv3's average against the events', kernel by kernel
+                by_label = collections.defaultdict(list)
+                for r in rows:
+                    lab = _label_of(r["Name"], 0, n)
+                    if lab:
+                        by_label[lab.rstrip("0123456789")].append(r)
+                out += ["", "Agreement of the two clocks (rocprofv3 average over ALL launches of the "
+                            "kernel in the process vs HIP events over the timed rounds):"]
+                for k, v in ks.items():
+                    cand = by_label.get(k.split("*")[0] + ("*" if "*" in k else ""))
+                    if cand and len(cand) == 1:
+                        out.append(f"  {k:30s} rocprofv3 {float(cand[0]['AverageNs']) / 1e6:.4f} ms   "
+                                   f"events {v['avg_ms']:.4f} ms")
+            sa = line.get("standalone_step_kernels")
+            if isinstance(sa, dict):
+                out += ["", "acco_commit_step / acco_estimate_step on their own after the timed region "
+                            "(HIP events), per shard length:"]
+                for n_k, tab in sa.items():
+                    for k, v in tab.items():
+                        out.append(f"  n={n_k:>11s} {k:12s} avg {v['avg_ms']:.4f} ms  {v['bytes_per_elem']:2d} B/elem"
+                                   f"  {v['GB/s']:7.1f} GB/s  {100 * v['frac_of_peak']:.1f} % of 8 TB/s")
+            for key in ("two_stream", "base_entry_points_round", "adopted_first_gradient_round"):
+                if isinstance(line.get(key), dict):
+                    out += ["", f"{key}: " + json.dumps({k: v for k, v in line[key].items()
+                                                         if k != "kernels"})]
+            path = os.path.join(ROOT, "profiles", f"{tag}_kernel_stats.txt")
+            open(path, "w").write("\n".join(out) + "\n")
+            wrote.append(path)
+        fetch = glob.glob(os.path.join(raw, tag + "_fetch", "*_counter_collection.csv"))
+        write = glob.glob(os.path.join(raw, tag + "_write", "*_counter_collection.csv"))
+        if fetch and write and n:
+            vals = collections.defaultdict(lambda: {"FETCH_SIZE": [], "WRITE_SIZE": []})
+            names = {}
+            copies = {"FETCH_SIZE": [], "WRITE_SIZE": []}
+            for ctr, f in (("FETCH_SIZE", fetch[0]), ("WRITE_SIZE", write[0])):
+                for r in csv.DictReader(open(f)):
+                    if "copyBuffer" in r["Kernel_Name"]:
+                        copies[ctr].append(float(r["Counter_Value"]))
+                        continue
+                    lab = _label_of(r["Kernel_Name"], int(r["Grid_Size"]), n)
+                    if lab:
+                        vals[lab][ctr].append(float(r["Counter_Value"]))
+                        names[lab] = _short_kernel(r["Kernel_Name"])
+            if not copies["FETCH_SIZE"] or not copies["WRITE_SIZE"]:
+                continue
+            # the calibration copy is the large one (torch also issues tiny copies)
+            fs = 4.0 * n / (max(copies["FETCH_SIZE"]) * 1024)
+            ws = 4.0 * n / (max(copies["WRITE_SIZE"]) * 1024)
+            out = [f"HBM traffic per launch from rocprofv3 counters - workload: {cfg.get('workload', '?')}",
+                   "", "Commands (from /tmp with TMPDIR=/tmp; one counter per run; $R = repository root):",
+                   "  " + cmd(tag + "_fetch"), "  " + cmd(tag + "_write"), "",
+                   "Calibration: --calibrate-copy issues one plain device copy of n fp32 (4 n bytes read, "
+                   "4 n written;", f"it runs as __amd_rocclr_copyBuffer).  FETCH_SIZE reads "
+                   f"{max(copies['FETCH_SIZE']):.1f} KiB for it, WRITE_SIZE {max(copies['WRITE_SIZE']):.1f} KiB,",
+                   f"so FETCH_SIZE is scaled by {fs:.3f} and WRITE_SIZE by {ws:.3f} to give bytes.", "",
+                   f"{'bench label':30s} {'kernel':44s} {'launches':>8s} {'FETCH KiB':>12s} {'WRITE KiB':>12s} "
+                   f"{'read B/el':>9s} {'write B/el':>10s} {'total':>7s} {'algorithmic':>11s}"]
+            table = {}
+            for lab, v in sorted(vals.items()):
+                if not v["FETCH_SIZE"] or not v["WRITE_SIZE"]:
+                    continue
+                f = sum(v["FETCH_SIZE"]) / len(v["FETCH_SIZE"])
+                wv = sum(v["WRITE_SIZE"]) / len(v["WRITE_SIZE"])
+                rb, wb = f * 1024 * fs / n, wv * 1024 * ws / n
+                table[lab] = round(rb + wb, 3)
+                out.append(f"{lab:30s} {names[lab][:44]:44s} {len(v['FETCH_SIZE']):8d} {f:12.1f} {wv:12.1f} "
+                           f"{rb:9.3f} {wb:10.3f} {rb + wb:7.2f} {kernel_bytes_per_elem(lab, workers):11d}")
+            out += ["", "B/el = bytes per shard element per launch (a launch over k workers moves k workers' "
+                        "bytes).", "Measured traffic equals the algorithmic bytes where the last two columns agree.",
+                    "", "TRAFFIC_B_PER_ELEM_JSON " + json.dumps(table)]
+            path = os.path.join(ROOT, "profiles", f"{tag}_hbm_traffic.txt")
+            open(path, "w").write("\n".join(out) + "\n")
+            wrote.append(path)
+    for pth in wrote:
+        print("wrote", os.path.relpath(pth, ROOT))
+    return 0 if wrote else 1
+
+
 def make_grads(torch, synth, w):
     """Every micro-batch gradient of one round, resident in HBM: grads[stage][worker][mb]."""
     grads = {}
@@ -450,8 +578,125 @@ def make_grads(torch, synth, w):
     return grads, n_bufs
 
 
+class OracleReplay:
+    """The checker leg: the CPU oracle (binary32 form) on sampled index ranges of the workload,
+    fed the same gradients round after round, to be compared with what the GPU holds."""
+
+    ARRAYS = ("theta", "m", "v", "theta_bf16", "theta_tilde_bf16")
+
+    def __init__(self, w, acc_dtype="f32"):
+        import oracle
+        import synth
+        self.w, self.slices = w, w.sample_slices()
+        h = w.hyper
+        hp = oracle.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay)
+        self.shards = [oracle.OracleShard(w.host_theta(a, b - a), w.workers, hp, precision="f32",
+                                          acc_dtype=acc_dtype) for a, b in self.slices]
+        self.grads = [{st: [[synth.host_grad_bf16(w.grad_spec(0, st, wk, mb), a, b - a)
+                             for mb in range(w.stage_counts(0, st)[wk])]
+                            for wk in range(w.workers)]
+                       for st in (synth.STAGE_TILDE, synth.STAGE_FULL)} for a, b in self.slices]
+        self.rounds = 0
+
+    def run(self, rounds):
+        import synth
+        for sh, gr in zip(self.shards, self.grads):
+            for _ in range(rounds):
+                for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
+                    for wk, row in enumerate(gr[st]):
+                        for g in row:
+                            sh.add_microbatch(wk, g)
+                    sh.stage1() if st == synth.STAGE_TILDE else sh.stage2()
+        self.rounds += rounds
+
+    def snapshot(self, torch, owner):
+        """Host copies of the GPU's arrays on the sampled ranges (taken outside any timed region)."""
+        snap = {}
+        for name in ("theta", "m", "v"):
+            full = owner.get_state(name)
+            snap[name] = torch.cat([full[a:b] for a, b in self.slices]).cpu().numpy()
+            del full
+        for name in ("theta_bf16", "theta_tilde_bf16"):
+            t = getattr(owner, name)
+            snap[name] = torch.cat([t[a:b] for a, b in self.slices]).view(torch.int16).cpu().numpy()
+        snap["step"] = owner.step.value
+        return snap
+
+    def compare(self, snap):
+        """Bit-for-bit comparison of a snapshot with the oracle's present state."""
+        import numpy as np
+        bad = {}
+        for name in self.ARRAYS:
+            want = np.concatenate([getattr(sh, name) for sh in self.shards])
+            got = snap[name]
+            if name.endswith("bf16"):
+                diff = got.view(np.uint16) != want.view(np.uint16)
+            else:
+                diff = got.view(np.uint32) != want.view(np.uint32)
+            if diff.any():
+                bad[name] = int(diff.sum())
+        if snap["step"] != self.shards[0].step:
+            bad["step"] = (snap["step"], self.shards[0].step)
+        elems = sum(b - a for a, b in self.slices)
+        return {"ok": not bad, "mismatches": bad, "elements": elems, "rounds": self.rounds,
+                "ranges": len(self.slices)}
+
+
+def time_rounds(torch, owner, w, grads, reps, warm=1):
+    """A few more rounds with the owner's present options, per-kernel events included."""
+    log = EventLog(torch)
+    owner.trace = log
+    for _ in range(warm):
+        run_round(owner, w, grads)
+    log.enabled = True
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run_round(owner, w, grads)
+    e1.record()
+    torch.cuda.synchronize()
+    owner.trace = None
+    ms = e0.elapsed_time(e1) / reps
+    summ = log.summary()
+    bpe = sum(kernel_bytes_per_elem(k, w.workers) * len(v) / reps for k, v in summ.items())
+    return {"ms_per_step": round(ms, 4), "steps": reps, "elements/s": w.n / (ms * 1e-3),
+            "bytes_per_elem": bpe, "GB/s": round(bpe * w.n / (ms * 1e-3) / 1e9, 1),
+            "launches_per_step": sum(len(v) for v in summ.values()) / reps,
+            "kernels": {k: {"calls_per_step": len(v) / reps, "avg_ms": round(sum(v) / len(v), 4),
+                            "GB/s": round(kernel_bytes_per_elem(k, w.workers) * w.n
+                                          / (sum(v) / len(v) * 1e-3) / 1e9, 1)}
+                        for k, v in summ.items()}}, warm + reps
+
+
+def figures(times, name, n, workers):
+    avg_ms = sum(times) / len(times)
+    bpe = kernel_bytes_per_elem(name, workers)
+    gbs = bpe * n / (avg_ms * 1e-3) / 1e9
+    return {"calls": len(times), "avg_ms": round(avg_ms, 4),
+            "median_ms": round(sorted(times)[len(times) // 2], 4), "min_ms": round(min(times), 4),
+            "bytes_per_elem": bpe, "GB/s": round(gbs, 1),
+            "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "elements/s": n / (avg_ms * 1e-3)}
+
+
+def profiled_traffic(workload, kernel):
+    """HBM bytes per element of `kernel` as rocprofv3's FETCH_SIZE / WRITE_SIZE counters gave
+    them for this workload: read from the committed summary of those two counter runs (written
+    by --summarize-rocprof), not measured by this run."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_B_PER_ELEM_JSON "):
+                table = json.loads(line.split(" ", 1)[1])
+                return table.get(kernel), os.path.relpath(path, ROOT)
+    except OSError:
+        pass
+    return None, None
+
+
 def main():
     args = parse()
+    if args.summarize_rocprof is not None:
+        return summarize_rocprof(args.summarize_rocprof)
     if args.gpus != 1:
         print("bench.py: this path is measured on ONE GPU; --gpus above 1 is not supported "
               "(no collectives are part of this build).", file=sys.stderr)
@@ -471,11 +716,18 @@ def main():
     if args.scheme is not None:
         return bench_scheme(args, torch, A, w, make_grads(torch, synth, w)[0])
     blocked = not args.planar_state and not args.unfused_cast
+    stash = not (args.no_bf16_stash or args.base_path)
+    main_opts = dict(fused_bf16_out=not args.unfused_cast,
+                     fused_publish=not (args.unfused_publish or args.base_path),
+                     fused_reduce=not (args.unfused_reduce or args.base_path),
+                     bf16_stash=stash and not args.bf16_accumulate, adopt_first=False)
+    batched = not args.per_worker_launches
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          blocked_state=blocked, block_elems=args.block_elems,
-                         bf16_stash=not (args.no_bf16_stash or args.base_path),
-                         bf16_accumulate=args.bf16_accumulate)
+                         bf16_stash=not args.bf16_accumulate,        # allocate the stash buffers
+                         bf16_accumulate=args.bf16_accumulate, batched=batched)
+    owner.set_options(**main_opts)
     scratch = (owner.acc if owner.acc else
                [torch.empty(w.n, dtype=torch.float32, device="cuda") for _ in range(2)])
     w.device_theta(scratch[0])                        # a planar scratch the round overwrites
@@ -488,17 +740,9 @@ def main():
         torch.cuda.synchronize()
 
     log = EventLog(torch)
-
-    class Opt:
-        fused_cast = not args.unfused_cast
-        fused_publish = not (args.unfused_publish or args.base_path)
-        fused_reduce = not (args.unfused_reduce or args.base_path)
-        bf16_stash = not (args.no_bf16_stash or args.base_path)
-        bf16_accumulate = args.bf16_accumulate
-
-    opt = Opt()
+    owner.trace = log
     for r in range(args.warmup):
-        run_round(A, owner, w, grads, log, opt)
+        run_round(owner, w, grads)
     torch.cuda.synchronize()
 
     log.enabled = True
@@ -508,145 +752,133 @@ def main():
     wall0 = time.perf_counter()
     t_start.record()
     for r in range(args.steps):
-        run_round(A, owner, w, grads, log, opt)
+        run_round(owner, w, grads)
     t_end.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
-    ms_total = t_start.elapsed_time(t_end)
-    ms_per_step = ms_total / args.steps
+    owner.trace = None
+    ms_per_step = t_start.elapsed_time(t_end) / args.steps
+
+    # ---- outside the timed region: is the state the timed rounds left the right one?
+    checks = []
+    replay = None
+    if not args.no_check:
+        replay = OracleReplay(w, "bf16" if args.bf16_accumulate else "f32")
+        snap = replay.snapshot(torch, owner)
+        replay.run(args.warmup + args.steps)
+        checks.append(dict(replay.compare(snap), after="timed rounds"))
 
     # The same round on the five base entry points only (acco_accumulate, acco_cast_params as the
-    # publish, acco_reduce_shards, acco_estimate_step, acco_commit_step with its bf16 output),
-    # after the timed region and on the same buffers: what the fusions and the stash are worth.
-    base_round = None
-    if owner.acc and not args.base_path and not args.bf16_accumulate:
-        class BaseOpt:
-            fused_cast = opt.fused_cast
-            fused_publish = False
-            fused_reduce = False
-            bf16_stash = False
-            bf16_accumulate = False
-
-        blog = EventLog(torch)
-        run_round(A, owner, w, grads, blog, BaseOpt())
-        blog.enabled = True
-        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(2, min(5, args.steps))
-        b0.record()
-        for r in range(reps):
-            run_round(A, owner, w, grads, blog, BaseOpt())
-        b1.record()
-        torch.cuda.synchronize()
-        bms = b0.elapsed_time(b1) / reps
-        bbytes = sum(kernel_bytes_per_elem(k, w.workers) * len(v) / reps
-                     for k, v in blog.summary().items())
-        base_round = {"ms_per_step": round(bms, 4), "steps": reps,
-                      "elements/s": w.n / (bms * 1e-3), "bytes_per_elem": bbytes,
-                      "GB/s": round(bbytes * w.n / (bms * 1e-3) / 1e9, 1),
-                      "kernels": {k: {"calls_per_step": len(v) / reps,
-                                      "avg_ms": round(sum(v) / len(v), 4),
-                                      "GB/s": round(kernel_bytes_per_elem(k, w.workers) * w.n
-                                                    / (sum(v) / len(v) * 1e-3) / 1e9, 1)}
-                                  for k, v in blog.summary().items()}}
-
+    # publish, acco_reduce_shards, acco_estimate_step, acco_commit_step with its bf16 output), on
+    # the same buffers and continuing from the same state: what the fusions and the stash are worth.
+    base_round = adopted_round = None
+    extras = not args.no_extras and not args.bf16_accumulate
+    if extras and not args.base_path:
+        owner.set_options(fused_publish=False, fused_reduce=False, bf16_stash=False)
+        owner.batched = False
+        base_round, done = time_rounds(torch, owner, w, grads, max(2, min(5, args.steps)))
+        if replay is not None:
+            snap = replay.snapshot(torch, owner)
+            replay.run(done)
+            checks.append(dict(replay.compare(snap), after="base-entry-point rounds"))
+        owner.batched = batched
     # The default path once more with the first micro-batch of every accumulation used in place
     # as the stash (no acco_accumulate_first copy): valid for a caller whose backward pass writes
     # that gradient into a buffer it then leaves alone, as the resident gradients here are.
-    adopted_round = None
-    if opt.bf16_stash and opt.fused_publish and not args.bf16_accumulate:
-        class AdoptOpt:
-            fused_cast = opt.fused_cast
-            fused_publish = True
-            fused_reduce = opt.fused_reduce
-            bf16_stash = True
-            bf16_accumulate = False
-            adopt_first = True
+    if extras and main_opts["bf16_stash"] and main_opts["fused_publish"]:
+        owner.set_options(**dict(main_opts, adopt_first=True))
+        adopted_round, done = time_rounds(torch, owner, w, grads, max(2, min(5, args.steps)))
+        if replay is not None:
+            snap = replay.snapshot(torch, owner)
+            replay.run(done)
+            checks.append(dict(replay.compare(snap), after="adopted-first-gradient rounds"))
+    owner.set_options(**main_opts)
+    replay = None
 
-        alog = EventLog(torch)
-        run_round(A, owner, w, grads, alog, AdoptOpt())
-        alog.enabled = True
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(2, min(5, args.steps))
-        a0.record()
-        for r in range(reps):
-            run_round(A, owner, w, grads, alog, AdoptOpt())
-        a1.record()
-        torch.cuda.synchronize()
-        ams = a0.elapsed_time(a1) / reps
-        abytes = sum(kernel_bytes_per_elem(k, w.workers) * len(v) / reps
-                     for k, v in alog.summary().items())
-        adopted_round = {"ms_per_step": round(ams, 4), "steps": reps,
-                         "elements/s": w.n / (ams * 1e-3), "bytes_per_elem": abytes,
-                         "GB/s": round(abytes * w.n / (ams * 1e-3) / 1e9, 1)}
-
-    # The committed and the speculative step on their own (gsum already reduced), after the
-    # timed region: the kernels the benchmark spec's bandwidth target is stated on.  Same buffers.
-    solo = EventLog(torch)
-    solo.enabled = True
+    # ---- acco_commit_step and acco_estimate_step on their own (gsum already reduced): the
+    # kernels the bandwidth target is stated on.  Same buffers; for the 875M-element workloads
+    # at both headline shard lengths (the interleaved state buffer has room for the 37 more).
     B = A.binding
-    for _ in range(max(3, args.steps)):
-        solo.timed("commit_bf16", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
-                   owner.hp, owner.step, max(owner.total.value, 1), theta_bf16=owner.theta_bf16,
-                   n=w.n)
-        solo.timed("commit", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
-                   owner.hp, owner.step, max(owner.total.value, 1), n=w.n)
-        solo.timed("estimate", B.acco_estimate_step, owner.theta, owner.m, owner.v, owner.gsum,
-                   owner.hp, owner.step.value, max(owner.total.value, 1),
-                   theta_tilde_bf16=owner.theta_tilde_bf16, n=w.n)
-    torch.cuda.synchronize()
-
-    def figures(times, name):
-        avg_ms = sum(times) / len(times)
-        bpe = kernel_bytes_per_elem(name, w.workers)
-        gbs = bpe * w.n / (avg_ms * 1e-3) / 1e9
-        return {"avg_ms": round(avg_ms, 4), "median_ms": round(sorted(times)[len(times) // 2], 4),
-                "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
-                "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
-                "elements/s": w.n / (avg_ms * 1e-3)}
-
-    standalone = {name: figures(times[1:], name) for name, times in solo.summary().items()}
+    sizes = [w.n]
+    if w.n in HEADLINE_SIZES and blocked:
+        sizes = list(HEADLINE_SIZES)
+    out_bf16 = torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda")
+    standalone = {}
+    for n_k in sizes:
+        solo = EventLog(torch)
+        solo.enabled = True
+        o16 = out_bf16[:n_k]
+        cnt = max(owner.total.value, 1)
+        for _ in range(max(3, args.steps) + 1):
+            solo("commit_bf16", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
+                 owner.hp, owner.step, cnt, theta_bf16=o16, n=n_k)
+            solo("commit", B.acco_commit_step, owner.theta, owner.m, owner.v, owner.gsum,
+                 owner.hp, owner.step, cnt, n=n_k)
+            solo("estimate", B.acco_estimate_step, owner.theta, owner.m, owner.v, owner.gsum,
+                 owner.hp, owner.step.value, cnt, theta_tilde_bf16=o16, n=n_k)
+        torch.cuda.synchronize()
+        standalone[str(n_k)] = {name: figures(ts[1:], name, n_k, w.workers)
+                                for name, ts in solo.summary().items()}
+    del out_bf16
 
     # What the memory system gives for the same access patterns without the arithmetic
     # (planar fp32 arrays borrowed from the accumulators): context for the figures above.
-    probe = EventLog(torch)
-    probe.enabled = True
-    if len(owner.acc) >= 4:
+    ceilings = {}
+    if extras and len(owner.acc) >= 4:
+        probe = EventLog(torch)
+        probe.enabled = True
         a4 = owner.acc[:4]
         for _ in range(6):
-            probe.timed("copy", B.acco_probe_copy, a4[0], a4[1])
-            probe.timed("triad", B.acco_probe_triad, a4[0], a4[1], a4[2], a4[3])
-            probe.timed("memcpy", a4[2].copy_, a4[3])
+            probe("copy", B.acco_probe_copy, a4[0], a4[1])
+            probe("triad", B.acco_probe_triad, a4[0], a4[1], a4[2], a4[3])
+            probe("memcpy", a4[2].copy_, a4[3])
         torch.cuda.synchronize()
-    ceilings = {}
-    for name, bpe, label in (("copy", 8, "device_copy_kernel"), ("memcpy", 8, "hipMemcpy_d2d"),
-                             ("triad", 28, "triad_4_reads_3_writes_in_place")):
-        ts = probe.summary().get(name, [])[1:]
-        if ts:
-            ms = sum(ts) / len(ts)
-            ceilings[label] = {"avg_ms": round(ms, 4), "bytes_per_elem": bpe,
-                               "GB/s": round(bpe * w.n / (ms * 1e-3) / 1e9, 1)}
+        for name, bpe, label in (("copy", 8, "device_copy_kernel"), ("memcpy", 8, "hipMemcpy_d2d"),
+                                 ("triad", 28, "triad_4_reads_3_writes_in_place")):
+            ts = probe.summary().get(name, [])[1:]
+            if ts:
+                ms = sum(ts) / len(ts)
+                ceilings[label] = {"avg_ms": round(ms, 4), "bytes_per_elem": bpe,
+                                   "GB/s": round(bpe * w.n / (ms * 1e-3) / 1e9, 1)}
 
     kernels = {}
     for name, times in log.summary().items():
-        avg_ms = sum(times) / len(times)
-        bpe = kernel_bytes_per_elem(name, w.workers)
-        gbs = bpe * w.n / (avg_ms * 1e-3) / 1e9
-        kernels[name] = {"calls_per_step": len(times) / args.steps, "avg_ms": round(avg_ms, 4),
-                         "median_ms": round(sorted(times)[len(times) // 2], 4),
-                         "min_ms": round(min(times), 4), "bytes_per_elem": bpe,
-                         "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
-                         "elements/s": w.n / (avg_ms * 1e-3)}
+        kernels[name] = dict(figures(times, name, w.n, w.workers),
+                             calls_per_step=len(times) / args.steps)
+        del kernels[name]["calls"]
+    bytes_per_round = sum(k["bytes_per_elem"] * k["calls_per_step"] for k in kernels.values())
 
-    head = ("reduce_commit" if opt.fused_reduce else "commit") + ("_bf16" if opt.fused_cast else "")
-    k = kernels[head]
-    roofline = {"kernel": ("acco_reduce_commit_step" if opt.fused_reduce else "acco_commit_step")
-                + (" (fused bf16 output)" if opt.fused_cast else ""),
-                "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": k["frac_of_peak"],
-                "traffic": (MEASURED_TRAFFIC_B_PER_ELEM.get(w.name, {}).get(head) or 0) * w.n
-                or None,
-                "bytes_per_launch": k["bytes_per_elem"] * w.n, "avg_ms": k["avg_ms"]}
+    # roofline: the committed step with its fused bf16 output on its own, at the workload's
+    # length; next to it the other headline length and the committed-step kernel of the round
+    head = standalone[str(w.n)]["commit_bf16"]
+    traffic, traffic_src = profiled_traffic(w.name, "commit_bf16")
+    round_head = next((k for k in ("reduce_commit_bf16", "reduce_commit", "commit_bf16", "commit")
+                       if k in kernels), None)
+    roofline = {"kernel": "acco_commit_step (fused bf16 output), on its own after the timed region",
+                "bound": "hbm", "achieved": head["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": head["frac_of_peak"], "n": w.n,
+                "bytes_per_launch": head["bytes_per_elem"] * w.n, "avg_ms": head["avg_ms"],
+                # counters of an earlier rocprofv3 run of this command, kept under profiles/
+                "traffic": None if traffic is None else traffic * w.n,
+                "traffic_source": traffic_src,
+                "headline_sizes": {n_k: {name: {"GB/s": f["GB/s"], "frac": f["frac_of_peak"],
+                                                "avg_ms": f["avg_ms"],
+                                                "bytes_per_elem": f["bytes_per_elem"]}
+                                         for name, f in tab.items()}
+                                   for n_k, tab in standalone.items()}}
+    if round_head is not None:
+        k = kernels[round_head]
+        rt, _ = profiled_traffic(w.name, round_head)
+        roofline["in_timed_round"] = {
+            "kernel": {"reduce_commit_bf16": "acco_reduce_commit_step (fused bf16 output)",
+                       "reduce_commit": "acco_reduce_commit_step",
+                       "commit_bf16": "acco_commit_step (fused bf16 output)",
+                       "commit": "acco_commit_step"}[round_head],
+            "achieved": k["GB/s"], "frac": k["frac_of_peak"], "avg_ms": k["avg_ms"],
+            "bytes_per_launch": k["bytes_per_elem"] * w.n,
+            "traffic": None if rt is None else rt * w.n}
 
+    ok = all(c["ok"] for c in checks)
     out = {
         "metric": "shard optimizer-step elements/s + achieved HBM GB/s vs MI355X peak",
         "metric_detail": "value = shard elements / time of one full ACCO round of one shard owner "
@@ -667,19 +899,29 @@ def main():
                                f"simulated workers, {sum(w.microbatches(0, k) for k in range(w.workers))} "
                                f"bf16 micro-batch gradients per round, AdamW lr={h.lr} "
                                f"betas=({h.beta1},{h.beta2}) eps={h.eps} wd={h.weight_decay}",
+                   "n": w.n, "workers": w.workers,
+                   "sequenced_by": "paper_2406_02613_amd.ShardOwner",
                    "resident_gradient_buffers": n_bufs,
                    "state_layout": (f"theta,m,v,gsum interleaved in blocks of {args.block_elems} "
                                     "elements" if blocked else "planar"),
-                   "fused_bf16_output": opt.fused_cast,
-                   "fused_publish": opt.fused_publish,
-                   "bf16_stash_of_first_microbatch": opt.bf16_stash and not opt.bf16_accumulate,
-                   "accumulator_dtype": "bf16" if opt.bf16_accumulate else "f32",
-                   "fused_reduce": opt.fused_reduce,
+                   "fused_bf16_output": main_opts["fused_bf16_out"],
+                   "fused_publish": main_opts["fused_publish"],
+                   "bf16_stash_of_first_microbatch": main_opts["bf16_stash"],
+                   "accumulator_dtype": "bf16" if args.bf16_accumulate else "f32",
+                   "fused_reduce": main_opts["fused_reduce"],
+                   "one_accumulate_launch_for_all_workers": batched,
+                   "launches_per_step": sum(k["calls_per_step"] for k in kernels.values()),
+                   "bytes_per_elem_per_step": bytes_per_round,
                    "host_wall_ms_per_step": wall * 1e3 / args.steps},
+        "round_GB/s": round(bytes_per_round * w.n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
         "kernels": kernels,
+        # were the timed rounds (and the extra rounds after them) the right computation?  The
+        # state on sampled index ranges against the CPU oracle's binary32 form, bit for bit.
+        "checked": bool(checks) and ok,
+        "check": checks or "skipped (--no-check)",
         # acco_commit_step / acco_estimate_step launched on their own after the timed region
-        # (gsum already reduced): the kernels the bandwidth target of the benchmark spec is stated on
+        # (gsum already reduced), per shard length
         "standalone_step_kernels": standalone,
         # the round again on the five base entry points only (no fused entry point, no stash)
         "base_entry_points_round": base_round,
@@ -697,7 +939,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds,
                                            "bf16" if args.bf16_accumulate else "f32")
     print(json.dumps(out))
-    return 0
+    return 0 if (ok or not checks) else 1
 
 
 if __name__ == "__main__":

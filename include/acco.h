@@ -2,8 +2,8 @@
  * acco.h - C ABI of the ACCO per-shard optimizer path for AMD MI355X (gfx950).
  *
  * One shard owner's work between the gradient Reduce_Scatter and the parameter
- * All_Gather of ACCO's communication stream (Alg. 1 of the paper, "Training with
- * ACCO in parallel for a worker i"; update rule: eq. (ACCO), stages (1) and (2)):
+ * All_Gather of ACCO's communication stream (Alg. 1 of the paper; update rule:
+ * eq. (ACCO), stages (1) and (2)):
  *
  *   acco_accumulate      g_i <- g_i + grad(micro-batch), N_i <- N_i + 1
  *   acco_cast_params     fp32 -> bf16 (publish g_i to the communication buffer;
@@ -34,7 +34,8 @@
  *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
  *     is enqueued and no host counter is modified.
  *   - Thread-safe; no global mutable state besides cached device properties and the
- *     process-wide launch settings at the end of this header.
+ *     process-wide launch settings at the end of this header (each entry point's settings are
+ *     one atomic word: a launch sees either the old set or the new one, never a mixture).
  */
 #ifndef ACCO_H
 #define ACCO_H
@@ -147,6 +148,50 @@ int acco_accumulate_first(uint16_t* stash_bf16, const uint16_t* grad_bf16, int64
                           int64_t* count, void* stream);
 int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stash_bf16,
                            const uint16_t* grad_bf16, int64_t n, int64_t* count, void* stream);
+
+/*
+ * The accumulation calls above for SEVERAL workers' accumulators in one launch (grid.y = worker).
+ * On a real node one process accumulates its whole gradient - all W shards of it - per
+ * micro-batch; with the W shards as W separate buffers that is W launches of the calls above,
+ * or one of this.  Same values; what it saves is launches (a round of the GPT-2-small-scale
+ * workload is 10 launches instead of 34) and the ramp-down / ramp-up between them.
+ *   op       which step, the same for every worker of the call:
+ *     ACCO_BATCH_ACCUMULATE_INIT     acc[w][j]  = grad[w][j]                       count = 1
+ *     ACCO_BATCH_ACCUMULATE          acc[w][j] += grad[w][j]                       count += 1
+ *     ACCO_BATCH_ACCUMULATE_PUBLISH  out[w][j]  = bf16_rne(acc[w][j] + grad[w][j]) count += 1
+ *                                    (acc is read only, as with keep_acc == 0)
+ *     ACCO_BATCH_FIRST               out[w][j]  = grad[w][j]      (out is the stash) count = 1
+ *     ACCO_BATCH_FIRST_PUBLISH       out[w][j]  = bf16_rne(float(grad[w][j]))        count = 1
+ *     ACCO_BATCH_SECOND              acc[w][j]  = float(stash[w][j]) + float(grad[w][j])
+ *                                                                         count 1 -> 2
+ *     ACCO_BATCH_SECOND_PUBLISH      out[w][j]  = bf16_rne(float(stash[w][j]) + float(grad[w][j]))
+ *                                                                         count 1 -> 2
+ *     ACCO_BATCH_PUBLISH             out[w][j]  = bf16_rne(acc[w][j])     counts untouched
+ *     ACCO_BATCH_RUNNING_BF16        out[w][j]  = bf16_rne(float(out[w][j]) + float(grad[w][j]))
+ *                                    (the bf16 running sum of acco_accumulate_bf16)  count += 1
+ *   workers  1 .. ACCO_MAX_WORKERS (more than 16 are served by several launches)
+ *   acc, out_bf16, stash_bf16, grad_bf16   HOST arrays of `workers` DEVICE pointers (fp32[n] for
+ *            acc, bf16[n] for the others), read before the call returns; an array the
+ *            operation does not use may be NULL
+ *   counts   host, int64[workers], nullable, in/out: the workers' micro-batch counters
+ * Errors: as the single calls; in addition no buffer the call writes may overlap any other
+ *         buffer of the call, of the same or of another worker (ACCO_ERR_ALIAS).
+ */
+typedef enum acco_batch_op {
+    ACCO_BATCH_ACCUMULATE_INIT    = 0,
+    ACCO_BATCH_ACCUMULATE         = 1,
+    ACCO_BATCH_ACCUMULATE_PUBLISH = 2,
+    ACCO_BATCH_FIRST              = 3,
+    ACCO_BATCH_FIRST_PUBLISH      = 4,
+    ACCO_BATCH_SECOND             = 5,
+    ACCO_BATCH_SECOND_PUBLISH     = 6,
+    ACCO_BATCH_PUBLISH            = 7,
+    ACCO_BATCH_RUNNING_BF16       = 8
+} acco_batch_op;
+
+int acco_accumulate_batch(int op, int workers, float* const* acc, uint16_t* const* out_bf16,
+                          const uint16_t* const* stash_bf16, const uint16_t* const* grad_bf16,
+                          int64_t n, int64_t* counts, void* stream);
 
 /*
  * The accumulation of Alg. 1 with the running sum itself held in bf16, the precision the

@@ -29,9 +29,8 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.ORACLE_SO):
-            _build.build_oracle()
-        L = ctypes.CDLL(_build.ORACLE_SO)
+        # rebuilt when the source changed; ACCO_SANITIZE=1 selects the ASan + UBSan build
+        L = ctypes.CDLL(_build.ensure(_build.selected_so()))
         p, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.oracle_set_threads.argtypes = [ci]
         L.oracle_set_threads.restype = None

@@ -1,6 +1,6 @@
 """ACCO per-shard optimizer path for AMD MI355X: HIP kernels behind a C ABI, and a thin binding."""
 from .binding import (ACCO_BF16, ACCO_F32, AccoError, AdamW, Counter, acco_accumulate,
-                      acco_accumulate_bf16,
+                      acco_accumulate_bf16, acco_accumulate_batch,
                       acco_accumulate_first, acco_accumulate_publish, acco_accumulate_second,
                       acco_cast_params, acco_commit_step,
                       acco_estimate_step, acco_lr_cosine, acco_reduce_commit_step, acco_reduce_estimate_step,
@@ -16,7 +16,7 @@ from .schemes import SchemeOwner, SCHEMES
 from . import layout
 
 __all__ = ["ACCO_BF16", "ACCO_F32", "AccoError", "AdamW", "Counter", "acco_accumulate",
-           "acco_accumulate_bf16",
+           "acco_accumulate_bf16", "acco_accumulate_batch",
            "acco_accumulate_first", "acco_accumulate_publish", "acco_accumulate_second",
            "acco_cast_params", "acco_commit_step", "acco_estimate_step",
            "acco_lr_cosine", "acco_reduce_commit_step", "acco_reduce_estimate_step", "acco_reduce_shards",

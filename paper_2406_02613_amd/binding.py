@@ -18,9 +18,14 @@ ACCO_ERR_NULL, ACCO_ERR_SIZE, ACCO_ERR_ALIGN = -1, -2, -3
 ACCO_ERR_ARG, ACCO_ERR_ALIAS, ACCO_ERR_DEVICE = -4, -5, -6
 ACCO_BF16, ACCO_F32 = 0, 1
 ACCO_MAX_WORKERS = 64
+# acco_batch_op
+(BATCH_ACCUMULATE_INIT, BATCH_ACCUMULATE, BATCH_ACCUMULATE_PUBLISH, BATCH_FIRST,
+ BATCH_FIRST_PUBLISH, BATCH_SECOND, BATCH_SECOND_PUBLISH, BATCH_PUBLISH,
+ BATCH_RUNNING_BF16) = range(9)
 
 EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first",
-           "acco_accumulate_second", "acco_accumulate_bf16", "acco_cast_params", "acco_reduce_shards",
+           "acco_accumulate_second", "acco_accumulate_bf16", "acco_accumulate_batch",
+           "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
@@ -75,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.acco_accumulate_first.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_accumulate_bf16.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_accumulate_second.argtypes = [p, p, p, p, i64, pi64, p]
+        pp = ctypes.POINTER(p)
+        L.acco_accumulate_batch.argtypes = [ci, ci, pp, pp, pp, pp, i64, pi64, p]
         L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
                                                 p, p, i64, ctypes.POINTER(AdamW), i64, play, p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
@@ -275,6 +282,39 @@ def acco_accumulate_second(stash_bf16, grad_bf16, *, acc=None, comm_bf16=None,
                                       _dev(grad_bf16, torch.bfloat16, n, "grad_bf16"), n,
                                       None if count is None else count.ref(), _stream())
     _check(rc, "acco_accumulate_second")
+
+
+def acco_accumulate_batch(op: int, n: int, *, acc: Optional[Sequence] = None,
+                          out_bf16: Optional[Sequence] = None,
+                          stash_bf16: Optional[Sequence] = None,
+                          grad_bf16: Optional[Sequence] = None,
+                          counts: Optional[Sequence[Counter]] = None) -> None:
+    """One accumulation step of several workers in one launch; each array argument is a
+    sequence with one tensor per worker.  The workers' counters are updated as by the single
+    calls."""
+    import torch
+    cols = (("acc", acc, torch.float32), ("out_bf16", out_bf16, torch.bfloat16),
+            ("stash_bf16", stash_bf16, torch.bfloat16), ("grad_bf16", grad_bf16, torch.bfloat16))
+    W = max(len(c) for _, c, _ in cols if c is not None)
+    arrays = []
+    for name, col, dt in cols:
+        if col is None:
+            arrays.append(None)
+            continue
+        if len(col) != W:
+            raise ValueError(f"{name}: one tensor per worker")
+        arrays.append((ctypes.c_void_p * W)(*[_dev(t, dt, n, f"{name}[{i}]")
+                                              for i, t in enumerate(col)]))
+    cnts = None
+    if counts is not None:
+        if len(counts) != W:
+            raise ValueError("counts: one per worker")
+        cnts = (ctypes.c_int64 * W)(*[c.value for c in counts])
+    rc = lib().acco_accumulate_batch(int(op), W, *arrays, int(n), cnts, _stream())
+    _check(rc, "acco_accumulate_batch")
+    if counts is not None:
+        for c, x in zip(counts, cnts):
+            c.value = x
 
 
 def acco_cast_params(out_bf16, src) -> None:

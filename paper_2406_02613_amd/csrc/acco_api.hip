@@ -20,12 +20,26 @@ using namespace acco;
 
 // ------------------------------------------------------------------ launch shapes
 
+// threads, vectors in flight, workgroups per CU and the resident-wavefront bound of one entry
+// point, packed into one word so that a launch always sees a consistent set
 struct LaunchShape {
-    std::atomic<int> threads;
-    std::atomic<int> vectors;  // U: 16-byte vectors per thread per array in flight
-    std::atomic<int> wg_per_cu;
-    std::atomic<int> resident;  // wavefronts resident per CU at most (0 = hardware limit)
+    int threads;
+    int vectors;    // U: 16-byte vectors per thread per array in flight
+    int wg_per_cu;
+    int resident;   // wavefronts resident per CU at most (0 = hardware limit)
 };
+
+inline uint64_t pack_shape(const LaunchShape& s)
+{
+    return (uint64_t)(uint16_t)s.threads | ((uint64_t)(uint8_t)s.vectors << 16) |
+           ((uint64_t)(uint8_t)s.wg_per_cu << 24) | ((uint64_t)(uint8_t)s.resident << 32);
+}
+
+inline LaunchShape unpack_shape(uint64_t w)
+{
+    return LaunchShape{(int)(w & 0xFFFF), (int)((w >> 16) & 0xFF), (int)((w >> 24) & 0xFF),
+                       (int)((w >> 32) & 0xFF)};
+}
 
 enum Entry {
     kAccumulate = 0,
@@ -50,11 +64,7 @@ enum Entry {
 // outstanding to cover the memory latency with 8-12 of them, and fewer concurrent wavefronts
 // keep fewer DRAM pages open at a time.  Values from sweeps at 31M, 125M and 875M elements
 // (same optimum at all three; no effect on cache-resident sizes).
-struct ShapeDefault {
-    int threads, vectors, wg_per_cu, resident;
-};
-
-constexpr ShapeDefault kDefaults[kEntries] = {
+constexpr LaunchShape kDefaults[kEntries] = {
     {64, 1, 0, 24},  // accumulate          (+1-2 %)
     {64, 1, 0, 0},   // cast                (any bound is slower)
     {64, 1, 0, 16},  // reduce              (+3 %)
@@ -69,16 +79,12 @@ constexpr ShapeDefault kDefaults[kEntries] = {
     {64, 1, 0, 0},   // probe
 };
 
-LaunchShape g_shape[kEntries];
+std::atomic<uint64_t> g_shape[kEntries];
 
 void reset_shapes()
 {
-    for (int e = 0; e < kEntries; ++e) {
-        g_shape[e].threads.store(kDefaults[e].threads, std::memory_order_relaxed);
-        g_shape[e].vectors.store(kDefaults[e].vectors, std::memory_order_relaxed);
-        g_shape[e].wg_per_cu.store(kDefaults[e].wg_per_cu, std::memory_order_relaxed);
-        g_shape[e].resident.store(kDefaults[e].resident, std::memory_order_relaxed);
-    }
+    for (int e = 0; e < kEntries; ++e)
+        g_shape[e].store(pack_shape(kDefaults[e]), std::memory_order_relaxed);
 }
 
 // the settings hold their defaults before any entry point can run
@@ -121,12 +127,13 @@ unsigned lds_for_groups(int groups)
     return (unsigned)(kLdsPerCu / groups / kLdsGranule * kLdsGranule);
 }
 
-Geometry geometry(Entry e, int64_t nvec, bool bounded)
+Geometry geometry(Entry e, int64_t nvec, bool bounded, int rows = 1)
 {
-    Geometry g;
-    g.threads = g_shape[e].threads.load(std::memory_order_relaxed);
-    g.vectors = g_shape[e].vectors.load(std::memory_order_relaxed);
-    const int     per_cu = g_shape[e].wg_per_cu.load(std::memory_order_relaxed);
+    const LaunchShape shape = unpack_shape(g_shape[e].load(std::memory_order_relaxed));
+    Geometry          g;
+    g.threads = shape.threads;
+    g.vectors = shape.vectors;
+    const int     per_cu = shape.wg_per_cu;
     const int64_t tile   = (int64_t)g.threads * g.vectors;
     g.tiles              = (nvec + tile - 1) / tile;
     const int64_t want   = g.tiles < 1 ? 1 : g.tiles;  // the scalar tail still needs workgroup 0
@@ -135,40 +142,68 @@ Geometry geometry(Entry e, int64_t nvec, bool bounded)
     const int64_t most   = (((int64_t)1 << 32) - 1) / g.threads;
     const int64_t asked  = per_cu > 0 ? (int64_t)per_cu * cu_count() : most;
     const int64_t cap    = asked < most ? asked : most;
-    g.grid               = dim3((unsigned)(want < cap ? want : cap));
-    const int resident   = g_shape[e].resident.load(std::memory_order_relaxed);
+    g.grid               = dim3((unsigned)(want < cap ? want : cap), (unsigned)rows);
+    const int resident   = shape.resident;
     const int groups     = resident / (g.threads / 64);       // workgroups per CU
     g.lds_bytes = (bounded && resident > 0) ? lds_for_groups(groups < 3 ? 3 : groups) : 0u;
     return g;
 }
 
+// Launch of an Op source (Single<Op>: one Op; Batch<Op>: `rows` workers, one Op each, built on
+// the device from a pointer table) over n elements per row.
 // bounded = false: ignore the entry's bound on resident wavefronts (kernels that write more
 // than they read want the full occupancy)
-template <class Op>
-int launch(Entry e, const Op& op, int64_t n, hipStream_t stream, bool bounded = true)
+template <class Src>
+int launch_source(Entry e, const Src& src, int rows, int64_t n, hipStream_t stream, bool bounded)
 {
+    typedef typename Src::Op Op;
     const int64_t  nvec = n / Op::kElems;
-    const Geometry g    = geometry(e, nvec, bounded);
+    const Geometry g    = geometry(e, nvec, bounded, rows);
     if (g.vectors == 1 && (int64_t)g.grid.x >= g.tiles) {
-        hipLaunchKernelGGL((flat_kernel<Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
+        hipLaunchKernelGGL((flat_kernel<Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
                            n);
         return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
     }
     switch (g.vectors) {
         case 1:
-            hipLaunchKernelGGL((stream_kernel<1, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<1, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
                                g.tiles, n);
             break;
         case 2:
-            hipLaunchKernelGGL((stream_kernel<2, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<2, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
                                g.tiles, n);
             break;
         default:
-            hipLaunchKernelGGL((stream_kernel<4, Op>), g.grid, dim3(g.threads), g.lds_bytes, stream, op, nvec,
+            hipLaunchKernelGGL((stream_kernel<4, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
                                g.tiles, n);
             break;
     }
     return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
+}
+
+template <class Op>
+int launch(Entry e, const Op& op, int64_t n, hipStream_t stream, bool bounded = true)
+{
+    return launch_source(e, Single<Op>{op}, 1, n, stream, bounded);
+}
+
+// workers [0, count) of the three pointer columns, kBatchMax per launch
+template <class Op>
+int launch_batch(Entry e, void* const* a, const void* const* b, const void* const* c, int count,
+                 int64_t n, hipStream_t stream, bool bounded = true)
+{
+    for (int w0 = 0; w0 < count; w0 += kBatchMax) {
+        const int rows = count - w0 < kBatchMax ? count - w0 : kBatchMax;
+        Batch<Op> src;
+        std::memset(&src, 0, sizeof src);
+        for (int r = 0; r < rows; ++r) {
+            src.tab.a[r] = a[w0 + r];
+            src.tab.b[r] = b != nullptr ? b[w0 + r] : nullptr;
+            src.tab.c[r] = c != nullptr ? c[w0 + r] : nullptr;
+        }
+        if (int rc = launch_source(e, src, rows, n, stream, bounded)) return rc;
+    }
+    return ACCO_OK;
 }
 
 // ------------------------------------------------------------------ validation helpers
@@ -341,6 +376,108 @@ ACCO_API int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint1
                             : launch(kSecond, SecondPublishOp{comm_bf16, stash_bf16, grad_bf16}, n, s);
     }
     if (rc == ACCO_OK && count != nullptr) *count = 2;
+    return rc;
+}
+
+ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
+                                   uint16_t* const* out_bf16, const uint16_t* const* stash_bf16,
+                                   const uint16_t* const* grad_bf16, int64_t n, int64_t* counts,
+                                   void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
+    if (op < ACCO_BATCH_ACCUMULATE_INIT || op > ACCO_BATCH_RUNNING_BF16) return ACCO_ERR_ARG;
+    // which columns the operation uses, and which one it writes
+    const bool uses_acc   = op == ACCO_BATCH_ACCUMULATE_INIT || op == ACCO_BATCH_ACCUMULATE ||
+                          op == ACCO_BATCH_ACCUMULATE_PUBLISH || op == ACCO_BATCH_SECOND ||
+                          op == ACCO_BATCH_PUBLISH;
+    const bool uses_out   = !(op == ACCO_BATCH_ACCUMULATE_INIT || op == ACCO_BATCH_ACCUMULATE ||
+                            op == ACCO_BATCH_SECOND);
+    const bool uses_stash = op == ACCO_BATCH_SECOND || op == ACCO_BATCH_SECOND_PUBLISH;
+    const bool uses_grad  = op != ACCO_BATCH_PUBLISH;
+    const bool writes_acc = uses_acc && !uses_out;
+    if ((uses_acc && acc == nullptr) || (uses_out && out_bf16 == nullptr) ||
+        (uses_stash && stash_bf16 == nullptr) || (uses_grad && grad_bf16 == nullptr))
+        return ACCO_ERR_NULL;
+
+    // every buffer of the call as a byte range; written ranges must not meet any other range
+    struct Range {
+        const void* p;
+        int64_t     bytes;
+        bool        written;
+    };
+    Range ranges[4 * ACCO_MAX_WORKERS];
+    int   nr = 0;
+    for (int w = 0; w < workers; ++w) {
+        const void* cols[4]  = {uses_acc ? (const void*)acc[w] : nullptr,
+                                uses_out ? (const void*)out_bf16[w] : nullptr,
+                                uses_stash ? (const void*)stash_bf16[w] : nullptr,
+                                uses_grad ? (const void*)grad_bf16[w] : nullptr};
+        const bool  used[4]  = {uses_acc, uses_out, uses_stash, uses_grad};
+        const bool  wr[4]    = {writes_acc, uses_out, false, false};
+        const int64_t esz[4] = {4, 2, 2, 2};
+        for (int k = 0; k < 4; ++k) {
+            if (!used[k]) continue;
+            if (n > 0 && cols[k] == nullptr) return ACCO_ERR_NULL;
+            if (!aligned16(cols[k])) return ACCO_ERR_ALIGN;
+            ranges[nr++] = Range{cols[k], n * esz[k], wr[k]};
+        }
+    }
+    for (int i = 0; i < nr; ++i)
+        for (int j = i + 1; j < nr; ++j)
+            if ((ranges[i].written || ranges[j].written) &&
+                overlap(ranges[i].p, ranges[i].bytes, ranges[j].p, ranges[j].bytes))
+                return ACCO_ERR_ALIAS;
+    const bool starts  = op == ACCO_BATCH_ACCUMULATE_INIT || op == ACCO_BATCH_FIRST ||
+                        op == ACCO_BATCH_FIRST_PUBLISH;
+    const bool seconds = op == ACCO_BATCH_SECOND || op == ACCO_BATCH_SECOND_PUBLISH;
+    if (counts != nullptr && op != ACCO_BATCH_PUBLISH && !starts)
+        for (int w = 0; w < workers; ++w) {
+            if (seconds ? counts[w] != 1
+                        : (counts[w] < 0 || counts[w] == std::numeric_limits<int64_t>::max()))
+                return ACCO_ERR_ARG;
+        }
+
+    int rc = ACCO_OK;
+    if (n > 0) {
+        hipStream_t        s = static_cast<hipStream_t>(stream);
+        void* const*       A = reinterpret_cast<void* const*>(acc);
+        void* const*       O = reinterpret_cast<void* const*>(out_bf16);
+        const void* const* R = reinterpret_cast<const void* const*>(acc);
+        const void* const* S = reinterpret_cast<const void* const*>(stash_bf16);
+        const void* const* G = reinterpret_cast<const void* const*>(grad_bf16);
+        switch (op) {
+            case ACCO_BATCH_ACCUMULATE_INIT:
+                rc = launch_batch<AccumulateOp<true>>(kAccumulate, A, G, nullptr, workers, n, s, false);
+                break;
+            case ACCO_BATCH_ACCUMULATE:
+                rc = launch_batch<AccumulateOp<false>>(kAccumulate, A, G, nullptr, workers, n, s);
+                break;
+            case ACCO_BATCH_ACCUMULATE_PUBLISH:
+                rc = launch_batch<AccumulatePublishOp<false, false>>(kAccumulatePublish, O, G, R, workers, n, s);
+                break;
+            case ACCO_BATCH_FIRST:
+                rc = launch_batch<StashOp<false>>(kStash, O, G, nullptr, workers, n, s);
+                break;
+            case ACCO_BATCH_FIRST_PUBLISH:
+                rc = launch_batch<StashOp<true>>(kStash, O, G, nullptr, workers, n, s);
+                break;
+            case ACCO_BATCH_SECOND:
+                rc = launch_batch<SecondOp>(kSecond, A, G, S, workers, n, s, false);
+                break;
+            case ACCO_BATCH_SECOND_PUBLISH:
+                rc = launch_batch<SecondPublishOp>(kSecond, O, G, S, workers, n, s);
+                break;
+            case ACCO_BATCH_PUBLISH:
+                rc = launch_batch<CastOp>(kCast, O, nullptr, R, workers, n, s);
+                break;
+            default:  // ACCO_BATCH_RUNNING_BF16: in place, each lane reads its elements first
+                rc = launch_batch<SecondPublishOp>(kSecond, O, G, reinterpret_cast<const void* const*>(out_bf16), workers, n, s);
+                break;
+        }
+    }
+    if (rc == ACCO_OK && counts != nullptr && op != ACCO_BATCH_PUBLISH)
+        for (int w = 0; w < workers; ++w) counts[w] = starts ? 1 : counts[w] + 1;
     return rc;
 }
 
@@ -847,7 +984,7 @@ ACCO_API const char* acco_status_string(int status)
 
 ACCO_API int acco_version(void)
 {
-    return 200;  // 0.2.0
+    return 300;  // 0.3.0
 }
 
 ACCO_API void acco_reset_launch_settings(void)
@@ -862,10 +999,14 @@ ACCO_API int acco_set_resident_waves(const char* entry, int waves_per_cu)
     if (waves_per_cu != 0 && (waves_per_cu < 3 || waves_per_cu > 32)) return ACCO_ERR_ARG;
     for (int e = 0; e < kEntries; ++e) {
         if (std::strcmp(entry, kEntryNames[e]) == 0) {
-            const int per_group = g_shape[e].threads.load(std::memory_order_relaxed) / 64;
-            if (waves_per_cu != 0 && waves_per_cu / per_group < 3) return ACCO_ERR_ARG;
-            g_shape[e].resident.store(waves_per_cu, std::memory_order_relaxed);
-            return ACCO_OK;
+            uint64_t old = g_shape[e].load(std::memory_order_relaxed);
+            for (;;) {
+                LaunchShape sh = unpack_shape(old);
+                if (waves_per_cu != 0 && waves_per_cu / (sh.threads / 64) < 3) return ACCO_ERR_ARG;
+                sh.resident = waves_per_cu;
+                if (g_shape[e].compare_exchange_weak(old, pack_shape(sh), std::memory_order_relaxed))
+                    return ACCO_OK;
+            }
         }
     }
     return ACCO_ERR_ARG;
@@ -881,10 +1022,15 @@ ACCO_API int acco_set_launch_shape(const char* entry, int threads, int vectors_i
     if (workgroups_per_cu < 0 || workgroups_per_cu > 64) return ACCO_ERR_ARG;
     for (int e = 0; e < kEntries; ++e) {
         if (std::strcmp(entry, kEntryNames[e]) == 0) {
-            g_shape[e].threads.store(threads, std::memory_order_relaxed);
-            g_shape[e].vectors.store(vectors_in_flight, std::memory_order_relaxed);
-            g_shape[e].wg_per_cu.store(workgroups_per_cu, std::memory_order_relaxed);
-            return ACCO_OK;
+            uint64_t old = g_shape[e].load(std::memory_order_relaxed);
+            for (;;) {
+                LaunchShape sh = unpack_shape(old);
+                sh.threads     = threads;
+                sh.vectors     = vectors_in_flight;
+                sh.wg_per_cu   = workgroups_per_cu;
+                if (g_shape[e].compare_exchange_weak(old, pack_shape(sh), std::memory_order_relaxed))
+                    return ACCO_OK;
+            }
         }
     }
     return ACCO_ERR_ARG;

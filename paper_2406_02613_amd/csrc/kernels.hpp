@@ -11,6 +11,9 @@
 //                  vectors of every input issued before the first use (kept selectable
 //                  through acco_set_launch_shape; slower at every size measured).
 // The elements after the last whole vector are done one by one by workgroup 0.
+// Both drivers take the Op from a "source": Single<Op> holds one Op; Batch<Op> holds a table
+// of pointers for up to kBatchMax workers and builds the Op of worker blockIdx.y from it, so
+// that the same accumulation step of several workers runs as ONE launch (grid.y = workers).
 //
 // Arithmetic: fp32, one IEEE operation per written operation (compiled with
 // -ffp-contract=off; the fused multiply-adds below are explicit), correctly
@@ -27,6 +30,7 @@ typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 constexpr int kReduceChunk = 8;   // worker shards summed per launch
+constexpr int kBatchMax    = 16;  // workers' accumulations served by one batched launch
 constexpr int kMaxThreads = 512;  // per workgroup: leaves 256 VGPRs per lane for loads in flight
 
 // ------------------------------------------------------------------ state addressing
@@ -149,12 +153,38 @@ __device__ __forceinline__ void st(T* p, T x)
 
 // Op supplies: kElems (elements per vector: 4, or 8 for all-bf16 kernels); struct In;
 //              In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
-//              void scalar(int64_t elem) const.
-template <int U, class Op>
-__global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Op op, const int64_t nvec,
+//              void scalar(int64_t elem) const;
+//              static Op make(const BatchPtrs&, int worker)   (accumulation Ops only).
+
+// Pointer table of a batched launch: a, b, c are the (up to) three arrays of the Op, one
+// entry per worker.
+struct BatchPtrs {
+    void*       a[kBatchMax];
+    const void* b[kBatchMax];
+    const void* c[kBatchMax];
+};
+
+template <class O>
+struct Single {
+    typedef O Op;
+    O         op;
+    __device__ __forceinline__ const O& get(unsigned) const { return op; }
+};
+
+template <class O>
+struct Batch {
+    typedef O Op;
+    BatchPtrs tab;
+    __device__ __forceinline__ O get(unsigned worker) const { return O::make(tab, (int)worker); }
+};
+
+template <int U, class Src>
+__global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Src src, const int64_t nvec,
                                                              const int64_t ntiles, const int64_t n)
 {
-    const int64_t tile = (int64_t)blockDim.x * U;
+    typedef typename Src::Op Op;
+    const Op                 op   = src.get(blockIdx.y);
+    const int64_t            tile = (int64_t)blockDim.x * U;
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const int64_t   base = t * tile + threadIdx.x;
         typename Op::In in[U];
@@ -177,11 +207,13 @@ __global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Op op, const 
 
 // One vector per thread, one tile per workgroup, no loop: the shape that measured
 // fastest for these streams (the hardware's workgroup dispatcher does the striding).
-template <class Op>
-__global__ void __launch_bounds__(kMaxThreads) flat_kernel(const Op op, const int64_t nvec,
+template <class Src>
+__global__ void __launch_bounds__(kMaxThreads) flat_kernel(const Src src, const int64_t nvec,
                                                            const int64_t n)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    typedef typename Src::Op Op;
+    const Op                 op = src.get(blockIdx.y);
+    const int64_t            i  = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nvec) op.apply(i, op.load(i));
     if (blockIdx.x == 0) {
         const int64_t j = nvec * Op::kElems + threadIdx.x;
@@ -196,6 +228,10 @@ struct AccumulateOp {
     static constexpr int kElems = 4;
     float*          acc;
     const uint16_t* grad;
+    static __device__ __forceinline__ AccumulateOp make(const BatchPtrs& t, int w)
+    {
+        return AccumulateOp{static_cast<float*>(t.a[w]), static_cast<const uint16_t*>(t.b[w])};
+    }
     struct In {
         f4 a;
         u2 g;
@@ -227,6 +263,13 @@ struct AccumulatePublishOp {
     float*          acc;
     const uint16_t* grad;
     uint16_t*       comm;
+    // batched form: the accumulator is only read (KEEP is not offered there)
+    static __device__ __forceinline__ AccumulatePublishOp make(const BatchPtrs& t, int w)
+    {
+        return AccumulatePublishOp{const_cast<float*>(static_cast<const float*>(t.c[w])),
+                                   static_cast<const uint16_t*>(t.b[w]),
+                                   static_cast<uint16_t*>(t.a[w])};
+    }
     struct In {
         f4 a;
         u2 g;
@@ -274,6 +317,10 @@ struct StashOp {
     static constexpr int kElems = 8;
     uint16_t*            dst;
     const uint16_t*      src;
+    static __device__ __forceinline__ StashOp make(const BatchPtrs& t, int w)
+    {
+        return StashOp{static_cast<uint16_t*>(t.a[w]), static_cast<const uint16_t*>(t.b[w])};
+    }
     struct In {
         u4 x;
     };
@@ -302,6 +349,11 @@ struct SecondOp {
     float*               acc;
     const uint16_t*      stash;
     const uint16_t*      grad;
+    static __device__ __forceinline__ SecondOp make(const BatchPtrs& t, int w)
+    {
+        return SecondOp{static_cast<float*>(t.a[w]), static_cast<const uint16_t*>(t.c[w]),
+                        static_cast<const uint16_t*>(t.b[w])};
+    }
     struct In {
         u2 s, g;
     };
@@ -328,6 +380,11 @@ struct SecondPublishOp {
     uint16_t*            comm;
     const uint16_t*      stash;
     const uint16_t*      grad;
+    static __device__ __forceinline__ SecondPublishOp make(const BatchPtrs& t, int w)
+    {
+        return SecondPublishOp{static_cast<uint16_t*>(t.a[w]), static_cast<const uint16_t*>(t.c[w]),
+                               static_cast<const uint16_t*>(t.b[w])};
+    }
     struct In {
         u4 s, g;
     };
@@ -357,6 +414,10 @@ struct CastOp {
     static constexpr int kElems = 4;
     uint16_t*    out;
     const float* src;
+    static __device__ __forceinline__ CastOp make(const BatchPtrs& t, int w)
+    {
+        return CastOp{static_cast<uint16_t*>(t.a[w]), static_cast<const float*>(t.c[w])};
+    }
     struct In {
         f4 x;
     };

@@ -28,13 +28,20 @@ Options that give the same values with fewer bytes over HBM:
                  which writes the bf16 communication buffer directly (the caller says which
                  micro-batch is the last one: ``last=True``);
   fused_reduce   reduce + estimate and reduce + commit each run as one kernel
-                 (acco_reduce_estimate_step / acco_reduce_commit_step).
+                 (acco_reduce_estimate_step / acco_reduce_commit_step);
+  batched        workers that are at the same step of their accumulation share one launch
+                 (acco_accumulate_batch) when their gradients are handed over together
+                 (add_microbatches / add_microbatch_rows).
 """
 from __future__ import annotations
 
-from typing import List
+from typing import Callable, List, Optional
 
 from . import binding as B
+
+# names under which the calls of a round are reported to ShardOwner.trace, one per kernel
+# variant (they differ in the bytes they move): see _label()
+OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first")
 
 
 class ShardOwner:
@@ -42,7 +49,8 @@ class ShardOwner:
                  fused_bf16_out: bool = True, fused_publish: bool = False,
                  fused_reduce: bool = False, blocked_state: bool = False,
                  block_elems: int = 8192, bf16_stash: bool = False,
-                 bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False):
+                 bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False,
+                 batched: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -51,6 +59,7 @@ class ShardOwner:
         # rate of the update they estimate / commit
         self.lr_schedule = lr_schedule
         self.comm_bf16 = comm_bf16
+        self.batched = bool(batched)
         self.fused_bf16_out = fused_bf16_out
         self.fused_publish = fused_publish and comm_bf16
         self.fused_reduce = fused_reduce
@@ -77,16 +86,46 @@ class ShardOwner:
                           [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)])
         self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                            if comm_bf16 else [])
-        self.stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
-                            if self.bf16_stash and not self.adopt_first else [None] * workers)
+        self._own_stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
+                                 if self.bf16_stash and not self.adopt_first else [None] * workers)
+        self.stash: List = list(self._own_stash)
         self.theta_tilde_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.theta_bf16 = torch.empty(n, dtype=bf16, device=dev)
         self.count = [B.Counter(0) for _ in range(workers)]   # N_i of the running accumulation
         self.total = B.Counter(0)                             # micro-batches summed in gsum
         self.step = B.Counter(0)                              # committed updates
+        # optional observer of every library call of a round: trace(label, fn, *args, **kw) must
+        # return fn(*args, **kw); a benchmark brackets the call with events here, so that what it
+        # times is this very sequence and not a copy of it
+        self.trace: Optional[Callable] = None
         self._fresh = [True] * workers                        # next accumulate starts a new sum
         self._published = [False] * workers                   # comm[w] already written this stage
         self._stashed = [False] * workers                     # the sum so far sits in stash[w]
+
+    def _call(self, label: str, fn, *args, **kw):
+        if self.trace is None:
+            return fn(*args, **kw)
+        return self.trace(label, fn, *args, **kw)
+
+    def set_options(self, **opts) -> None:
+        """Switch fused_bf16_out / fused_publish / fused_reduce / bf16_stash / adopt_first between
+        rounds (no accumulation may be under way): the values of a round do not depend on them,
+        only the calls it is made of.  Buffers are those of the constructor: a stash can only be
+        switched on if it was allocated then."""
+        if not all(self._fresh):
+            raise ValueError("options can only change between stages")
+        for k, val in opts.items():
+            if k not in OPTIONS:
+                raise ValueError(f"unknown option {k!r}")
+            setattr(self, k, bool(val))
+        self.fused_publish = self.fused_publish and self.comm_bf16
+        self.bf16_stash = self.bf16_stash and self.comm_bf16 and not self.bf16_accumulate
+        self.adopt_first = self.adopt_first and self.bf16_stash
+        if self.bf16_stash and not self.adopt_first and any(t is None for t in self._own_stash):
+            raise ValueError("this owner was built without stash buffers")
+        self.stash = [None] * self.W if self.adopt_first else list(self._own_stash)
+        if not self.fused_bf16_out and self.state is not None:
+            raise ValueError("the unfused parameter cast needs a planar theta")
 
     # planar access to the state, whatever its layout
     def set_state(self, name: str, planar) -> None:
@@ -99,48 +138,125 @@ class ShardOwner:
         return self.state.planar(name) if self.state is not None else getattr(self, name)
 
     # computation stream
+    def _step_of(self, worker: int, last: bool) -> str:
+        """Which accumulation step the next micro-batch of `worker` is (also its trace label)."""
+        publish = last and self.fused_publish
+        fresh = self._fresh[worker]
+        if self.bf16_accumulate:
+            return "accumulate_bf16_init" if fresh else "accumulate_bf16"
+        if self.adopt_first and fresh and not publish:
+            return "adopt"
+        if self.bf16_stash and fresh:
+            return "accumulate_first_publish" if publish else "accumulate_first"
+        if self.bf16_stash and self._stashed[worker]:
+            return "accumulate_second_publish" if publish else "accumulate_second"
+        if publish:
+            return "accumulate_publish_init" if fresh else "accumulate_publish"
+        return "accumulate_init" if fresh else "accumulate"
+
+    # step -> (batched operation, uses acc, output column, uses stash)
+    _BATCH = {
+        "accumulate_init": (B.BATCH_ACCUMULATE_INIT, True, None, False),
+        "accumulate": (B.BATCH_ACCUMULATE, True, None, False),
+        "accumulate_publish": (B.BATCH_ACCUMULATE_PUBLISH, True, "comm", False),
+        "accumulate_publish_init": (B.BATCH_FIRST_PUBLISH, False, "comm", False),
+        "accumulate_first": (B.BATCH_FIRST, False, "stash", False),
+        "accumulate_first_publish": (B.BATCH_FIRST_PUBLISH, False, "comm", False),
+        "accumulate_second": (B.BATCH_SECOND, True, None, True),
+        "accumulate_second_publish": (B.BATCH_SECOND_PUBLISH, False, "comm", True),
+        "accumulate_bf16_init": (B.BATCH_FIRST, False, "comm", False),
+        "accumulate_bf16": (B.BATCH_RUNNING_BF16, False, "comm", False),
+    }
+
+    def _run_step(self, step: str, workers: List[int], grads: List) -> None:
+        """Enqueue accumulation step `step` for the listed workers (one gradient each) and do
+        the owner's bookkeeping for them."""
+        if step == "adopt":
+            # first micro-batch, used where it lies: no device work, only the bookkeeping
+            for w, g in zip(workers, grads):
+                if g.numel() != self.n or g.dtype != self.torch.bfloat16:
+                    raise ValueError("grad_bf16: wrong size or dtype")
+                self.stash[w] = g
+                self.count[w].value = 1
+        else:
+            if self.adopt_first and step.startswith("accumulate_second") and self.n > 0:
+                for w, g in zip(workers, grads):
+                    if g.data_ptr() == self.stash[w].data_ptr():
+                        raise ValueError("the buffer adopted as the first micro-batch was reused")
+            if self.batched and len(workers) > 1:
+                op, use_acc, out, use_stash = self._BATCH[step]
+                cols = {}
+                if use_acc:
+                    cols["acc"] = [self.acc[w] for w in workers]
+                if out is not None:
+                    cols["out_bf16"] = [getattr(self, out)[w] for w in workers]
+                if use_stash:
+                    cols["stash_bf16"] = [self.stash[w] for w in workers]
+                self._call(f"{step}*{len(workers)}", B.acco_accumulate_batch, op, self.n,
+                           grad_bf16=list(grads), counts=[self.count[w] for w in workers], **cols)
+            else:
+                for w, g in zip(workers, grads):
+                    self._run_single(step, w, g)
+        for w in workers:
+            if step.startswith("accumulate_bf16") or "publish" in step:
+                self._published[w] = True
+            self._stashed[w] = step in ("adopt", "accumulate_first")
+            self._fresh[w] = False
+
+    def _run_single(self, step: str, w: int, g) -> None:
+        cnt = self.count[w]
+        if step in ("accumulate_bf16_init", "accumulate_bf16"):
+            self._call(step, B.acco_accumulate_bf16, self.comm[w], g, step.endswith("init"), cnt)
+        elif step in ("accumulate_first", "accumulate_first_publish"):
+            # kept as bf16; if it is also the last micro-batch, it IS the published sum
+            publish = step.endswith("publish")
+            self._call(step, B.acco_accumulate_first, self.comm[w] if publish else self.stash[w],
+                       g, publish, cnt)
+        elif step == "accumulate_second_publish":
+            self._call(step, B.acco_accumulate_second, self.stash[w], g, comm_bf16=self.comm[w],
+                       count=cnt)
+        elif step == "accumulate_second":
+            self._call(step, B.acco_accumulate_second, self.stash[w], g, acc=self.acc[w], count=cnt)
+        elif step in ("accumulate_publish_init", "accumulate_publish"):
+            self._call(step, B.acco_accumulate_publish, self.acc[w], g, self.comm[w],
+                       step.endswith("init"), False, cnt)
+        else:
+            self._call(step, B.acco_accumulate, self.acc[w], g, step.endswith("init"), cnt)
+
     def add_microbatch(self, worker: int, grad_bf16, last: bool = False) -> None:
         """Accumulate one micro-batch gradient.  ``last`` marks the final micro-batch of the
         stage for this worker (used only with fused_publish)."""
-        publish = last and self.fused_publish
-        if self.bf16_accumulate:
-            B.acco_accumulate_bf16(self.comm[worker], grad_bf16, self._fresh[worker],
-                                   self.count[worker])
-            self._published[worker] = True
-        elif self.adopt_first and self._fresh[worker] and not publish:
-            # first micro-batch, used where it lies: no device work, only the bookkeeping
-            if grad_bf16.numel() != self.n or grad_bf16.dtype != self.torch.bfloat16:
-                raise ValueError("grad_bf16: wrong size or dtype")
-            self.stash[worker] = grad_bf16
-            self.count[worker].value = 1
-            self._stashed[worker] = True
-        elif self.bf16_stash and self._fresh[worker]:
-            # first micro-batch: kept as bf16; if it is also the last, it IS the published sum
-            B.acco_accumulate_first(self.comm[worker] if publish else self.stash[worker],
-                                    grad_bf16, publish, self.count[worker])
-            self._published[worker] = publish
-            self._stashed[worker] = not publish
-        elif self.bf16_stash and self._stashed[worker]:
-            # second micro-batch: stash + grad in fp32, to the accumulator or straight out
-            if (self.adopt_first and self.n > 0
-                    and grad_bf16.data_ptr() == self.stash[worker].data_ptr()):
-                raise ValueError("the buffer adopted as the first micro-batch was reused")
-            if publish:
-                B.acco_accumulate_second(self.stash[worker], grad_bf16,
-                                         comm_bf16=self.comm[worker], count=self.count[worker])
-                self._published[worker] = True
-            else:
-                B.acco_accumulate_second(self.stash[worker], grad_bf16, acc=self.acc[worker],
-                                         count=self.count[worker])
-            self._stashed[worker] = False
-        elif publish:
-            B.acco_accumulate_publish(self.acc[worker], grad_bf16, self.comm[worker],
-                                      self._fresh[worker], False, self.count[worker])
-            self._published[worker] = True
+        self._run_step(self._step_of(worker, last), [worker], [grad_bf16])
+
+    def add_microbatches(self, items) -> None:
+        """Accumulate one micro-batch gradient for each of several workers:
+        items = [(worker, grad_bf16, last), ...], every worker at most once.  With
+        ``batched`` the workers that are at the same step of their accumulation share one launch."""
+        groups = {}
+        seen = set()
+        for worker, grad, last in items:
+            if worker in seen:
+                raise ValueError("a worker appears twice in one call")
+            seen.add(worker)
+            ws, gs = groups.setdefault(self._step_of(worker, last), ([], []))
+            ws.append(worker)
+            gs.append(grad)
+        for step, (ws, gs) in groups.items():
+            self._run_step(step, ws, gs)
+
+    def add_microbatch_rows(self, rows) -> None:
+        """A whole stage's gradients, rows[worker] = that worker's micro-batch gradients in order
+        (the last one of a row is marked as such)."""
+        if len(rows) != self.W:
+            raise ValueError("one row per worker")
+        if self.batched:
+            for k in range(max(len(r) for r in rows)):
+                self.add_microbatches([(w, r[k], k == len(r) - 1) for w, r in enumerate(rows)
+                                       if k < len(r)])
         else:
-            B.acco_accumulate(self.acc[worker], grad_bf16, self._fresh[worker],
-                              self.count[worker])
-        self._fresh[worker] = False
+            for w, r in enumerate(rows):
+                for k, g in enumerate(r):
+                    self.add_microbatch(w, g, last=(k == len(r) - 1))
 
     def _publish(self):
         for w in range(self.W):
@@ -149,13 +265,21 @@ class ShardOwner:
                                  "worker at least one gradient per accumulation)")
         if not self.comm_bf16:
             return self.acc
-        for w in range(self.W):
-            if self._published[w]:
-                continue
-            if self._stashed[w]:      # one micro-batch only, not marked last: publish the stash
-                B.acco_accumulate_first(self.comm[w], self.stash[w], True)
+        todo = [w for w in range(self.W) if not self._published[w]]
+        stashed = [w for w in todo if self._stashed[w]]     # one micro-batch only, not marked last
+        summed = [w for w in todo if not self._stashed[w]]
+        for ws, label, op, src in ((stashed, "accumulate_first_publish", B.BATCH_FIRST_PUBLISH,
+                                    "grad_bf16"), (summed, "cast", B.BATCH_PUBLISH, "acc")):
+            if self.batched and len(ws) > 1:
+                col = [self.stash[w] if src == "grad_bf16" else self.acc[w] for w in ws]
+                self._call(f"{label}*{len(ws)}", B.acco_accumulate_batch, op, self.n,
+                           out_bf16=[self.comm[w] for w in ws], **{src: col})
+            elif src == "grad_bf16":
+                for w in ws:
+                    self._call(label, B.acco_accumulate_first, self.comm[w], self.stash[w], True)
             else:
-                B.acco_cast_params(self.comm[w], self.acc[w])
+                for w in ws:
+                    self._call(label, B.acco_cast_params, self.comm[w], self.acc[w])
         return self.comm
 
     def _hp(self) -> B.AdamW:
@@ -179,29 +303,32 @@ class ShardOwner:
     def stage1(self) -> None:
         shards = self._publish()
         if self.fused_reduce:
-            B.acco_reduce_estimate_step(self.theta, self.m, self.v, self.gsum, shards,
-                                        self._counts(), self.total, self._hp(), self.step.value,
-                                        theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
+            self._call("reduce_estimate", B.acco_reduce_estimate_step, self.theta, self.m, self.v,
+                       self.gsum, shards, self._counts(), self.total, self._hp(), self.step.value,
+                       theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
         else:
-            B.acco_reduce_shards(self.gsum, shards, False, self._counts(), self.total, n=self.n)
-            B.acco_estimate_step(self.theta, self.m, self.v, self.gsum, self._hp(), self.step.value,
-                                 self.total.value, theta_tilde_bf16=self.theta_tilde_bf16,
-                                 n=self.n)
+            self._call("reduce_init", B.acco_reduce_shards, self.gsum, shards, False,
+                       self._counts(), self.total, n=self.n)
+            self._call("estimate", B.acco_estimate_step, self.theta, self.m, self.v, self.gsum,
+                       self._hp(), self.step.value, self.total.value,
+                       theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
         self._end_stage()
 
     def stage2(self) -> None:
         shards = self._publish()
         out = self.theta_bf16 if self.fused_bf16_out else None
         if self.fused_reduce:
-            B.acco_reduce_commit_step(self.theta, self.m, self.v, self.gsum, shards,
-                                      self._counts(), self.total, self._hp(), self.step,
-                                      theta_bf16=out, n=self.n)
+            self._call("reduce_commit_bf16" if out is not None else "reduce_commit",
+                       B.acco_reduce_commit_step, self.theta, self.m, self.v, self.gsum, shards,
+                       self._counts(), self.total, self._hp(), self.step, theta_bf16=out, n=self.n)
         else:
-            B.acco_reduce_shards(self.gsum, shards, True, self._counts(), self.total, n=self.n)
-            B.acco_commit_step(self.theta, self.m, self.v, self.gsum, self._hp(), self.step,
-                               self.total.value, theta_bf16=out, n=self.n)
+            self._call("reduce_accumulate", B.acco_reduce_shards, self.gsum, shards, True,
+                       self._counts(), self.total, n=self.n)
+            self._call("commit_bf16" if out is not None else "commit", B.acco_commit_step,
+                       self.theta, self.m, self.v, self.gsum, self._hp(), self.step,
+                       self.total.value, theta_bf16=out, n=self.n)
         if not self.fused_bf16_out:
             if self.state is not None:
                 raise ValueError("the unfused parameter cast needs a planar theta")
-            B.acco_cast_params(self.theta_bf16, self.theta)
+            self._call("cast", B.acco_cast_params, self.theta_bf16, self.theta)
         self._end_stage()

@@ -1,20 +1,17 @@
-"""The two streams of Alg. 1 on one GPU: a computation stream that keeps accumulating
-micro-batch gradients and a communication stream that runs the shard owner's stage
-(publish, reduce, estimate / commit) in parallel, with the paper's hand-off:
+"""The two streams of Alg. 1 on one GPU (Alg. 1, computation stream / communication stream).
 
-  computation stream                         communication stream
-  Stage 1: while not Ready_for_Stage_2:      Stage 1: (N~, g~) <- Buffer
-             g += grad F(theta); N += 1               reduce, theta~ = Opt(theta, sum g~ / sum N~)
-           theta~ <- Buffer; Buffer <- (N, g)          Buffer <- theta~ ; Ready_for_Stage_2
-  Stage 2: while not Ready_for_Stage_1:      Stage 2: (N, g) <- Buffer
-             g~ += grad F(theta~); N~ += 1             reduce onto the stage-1 sum, commit theta
-           theta <- Buffer; Buffer <- (N~, g~)         Buffer <- theta ; Ready_for_Stage_1
+A computation stream keeps accumulating micro-batch gradients on whichever parameter version
+it was last handed, while a communication stream runs the shard owner's stage in parallel:
+publish, reduce, then the speculative estimate (first stage of a round) or the committed update
+(second stage).  The streams meet only at the hand-off: when the owner's stage is done it raises
+a ready flag; the computation stream, on seeing it, takes the new parameters, gives up what it
+has accumulated so far together with its count, and starts the next accumulation.  How many
+micro-batches a stage accumulates is therefore decided at run time by how long the other stream
+takes - the method's "accumulate while you communicate".
 
-The number of micro-batches a stage accumulates is therefore decided at run time by how long
-the other stream takes ("accumulate while you communicate").  This GPU plays worker 0 and the
-owner of the shard; the other W-1 workers are represented by their published bf16 buffers
-and counts, which the caller provides.  Ready flags are HIP events on the communication
-stream that the host polls after each micro-batch.
+This GPU plays worker 0 and the owner of the shard; the other W-1 workers are represented by
+their published bf16 buffers and counts, which the caller provides.  The ready flags are HIP
+events on the communication stream that the host polls after each micro-batch.
 
 Host-side sequencing only; all arithmetic is in the C-ABI library.
 """

@@ -41,9 +41,8 @@ _device = None
 def host_lib() -> ctypes.CDLL:
     global _host
     if _host is None:
-        if not os.path.exists(_build.HOST_SO):
-            _build.build_host()
-        lib = ctypes.CDLL(_build.HOST_SO)
+        # rebuilt when the source changed; ACCO_SANITIZE=1 selects the ASan + UBSan build
+        lib = ctypes.CDLL(_build.ensure_host(_build.selected_host_so()))
         lib.synth_host_stream_key.restype = ctypes.c_uint64
         lib.synth_host_stream_key.argtypes = [ctypes.c_uint64] + [ctypes.c_uint32] * 5
         lib.synth_host_hash.restype = ctypes.c_uint64
@@ -262,19 +261,26 @@ class Workload:
         else:
             device_normal_f32(out, self.theta_key(), j0, self.theta_param)
 
-    def sample_slices(self, block: int = 4096, period: int = 1 << 24,
-                      edge: int = 65536) -> List[Tuple[int, int]]:
+    def sample_slices(self, block: int = 4106, edge: int = 65536) -> List[Tuple[int, int]]:
         """Index ranges [a, b) on which a full-size run is checked element by element:
-        the head, the tail (with any ragged remainder) and periodic interior blocks."""
+        the head, the tail (with any ragged remainder) and interior blocks.
+
+        Interior block k starts at k * period, period = 8192 q + 4099 with q chosen so that a
+        shard has at least eight interior blocks (q = 2048, about 2^24 elements apart, from
+        151M elements on).  The period is odd, so it shares no factor with the power-of-two
+        strides of the layouts and launch shapes (vectors of 4 and 8 elements, tiles of 256 to
+        8192, state blocks of 8192): the starts walk through all residues, and since
+        period mod 8192 = 4099 < block, consecutive blocks cover abutting stretches of the
+        8192-element state blocks - every in-block offset is checked within any two consecutive
+        samples, and every other sample straddles a state-block boundary."""
         n = self.n
-        if n <= 4 * edge:
+        if n <= (1 << 21):                      # the oracle does such a shard whole in seconds
             return [(0, n)]
+        period = max(1, min(2048, n // 9 // 8192)) * 8192 + 4099
         out = [(0, edge)]
         a = period
         while a + block < n - edge:
-            # odd offsets so that blocks do not sit on vector or tile boundaries
-            off = a + 3
-            out.append((off, off + block + 5))
+            out.append((a, a + block))
             a += period
         out.append((n - edge - 37, n))
         return out

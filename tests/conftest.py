@@ -14,12 +14,14 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session", autouse=True)
 def _native_libraries():
-    """Load what is built; build only what is missing (hipcc cross-compiles without a GPU)."""
+    """Load what is built; rebuild what is missing or older than its sources (a hash of the
+    sources and flags is kept beside each library), so that a test never runs a stale binary.
+    hipcc cross-compiles without a GPU."""
     from paper_2406_02613_amd import build as acco_build
     from synth import build as synth_build
-    if not os.path.exists(acco_build.ACCO_SO):
+    if not acco_build.is_current():
         acco_build.build_acco()
-    if not os.path.exists(synth_build.DEVICE_SO):
+    if not synth_build.device_current():
         synth_build.build_device()
     yield
 

@@ -423,3 +423,56 @@ def test_probe_entry_points_validate_like_the_rest():
     assert L.acco_probe_triad(vp(A), vp(Bp), vp(A), vp(D), 4, NONE) == B.ACCO_ERR_ALIAS
     assert L.acco_probe_triad(vp(A), vp(Bp), vp(C), vp(D), -1, NONE) == B.ACCO_ERR_SIZE
     assert L.acco_probe_triad(vp(A), vp(Bp), vp(C), vp(D), 0, NONE) == 0
+
+
+def test_accumulate_batch_validation_and_counters():
+    L = B.lib()
+    f = L.acco_accumulate_batch
+    acc = _shards(A, Bp)
+    out = _shards(C, D)
+    stash = _shards(E, F)
+    grad = _shards(0x70000, 0x80000)
+    cnt = (ctypes.c_int64 * 2)(5, 7)
+    ops = B
+    # unknown operation, worker count out of range, bad n
+    assert f(9, 2, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG
+    assert f(-1, 2, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG
+    assert f(ops.BATCH_ACCUMULATE, 0, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_SIZE
+    assert f(ops.BATCH_ACCUMULATE, 65, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_SIZE
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, out, stash, grad, -1, cnt, NONE) == B.ACCO_ERR_SIZE
+    # a column the operation uses is missing; columns it does not use may be NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, NONE, NONE, NONE, grad, 0, cnt, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, NONE, 0, cnt, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, NONE, grad, 0, cnt, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_PUBLISH, 2, acc, NONE, NONE, NONE, 0, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, _shards(0x70000, 0), 4, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, Bp + 4), NONE, NONE, grad, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
+    # a written buffer meets another buffer of the call: same worker, or another worker's
+    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, A + 16), NONE, NONE, grad, 64, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, C), NONE, grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, 0x70000), NONE, grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_SECOND, 2, acc, NONE, _shards(E, A), grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
+    # read-only buffers may be shared between workers
+    assert f(ops.BATCH_FIRST, 2, NONE, out, NONE, _shards(0x70000, 0x70000), 0, NONE, NONE) == 0
+    # counters: errors leave them alone; each operation's rule
+    assert (cnt[0], cnt[1]) == (5, 7)
+    assert f(ops.BATCH_SECOND, 2, acc, NONE, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG   # not 1
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, cnt, NONE) == 0
+    assert (cnt[0], cnt[1]) == (6, 8)
+    assert f(ops.BATCH_ACCUMULATE_PUBLISH, 2, acc, out, NONE, grad, 0, cnt, NONE) == 0
+    assert (cnt[0], cnt[1]) == (7, 9)
+    assert f(ops.BATCH_RUNNING_BF16, 2, NONE, out, NONE, grad, 0, cnt, NONE) == 0
+    assert (cnt[0], cnt[1]) == (8, 10)
+    assert f(ops.BATCH_PUBLISH, 2, acc, out, NONE, NONE, 0, cnt, NONE) == 0
+    assert (cnt[0], cnt[1]) == (8, 10)
+    for op in (ops.BATCH_ACCUMULATE_INIT, ops.BATCH_FIRST, ops.BATCH_FIRST_PUBLISH):
+        cnt[0], cnt[1] = 3, 4
+        assert f(op, 2, acc, out, NONE, grad, 0, cnt, NONE) == 0 and (cnt[0], cnt[1]) == (1, 1)
+    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, stash, grad, 0, cnt, NONE) == 0
+    assert (cnt[0], cnt[1]) == (2, 2)
+    neg = (ctypes.c_int64 * 2)(1, -1)
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, neg, NONE) == B.ACCO_ERR_ARG
+    # 64 workers (four launches of 16) are accepted
+    many = _shards(*[0x100000 + 0x1000 * k for k in range(64)])
+    gmany = _shards(*[0x900000 + 0x1000 * k for k in range(64)])
+    assert f(ops.BATCH_FIRST, 64, NONE, many, NONE, gmany, 0, NONE, NONE) == 0

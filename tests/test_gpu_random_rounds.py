@@ -1,7 +1,7 @@
 """Randomly drawn configurations of the whole path (shard length, worker count, launch shape,
 bound on resident wavefronts, state layout, communication dtype, hyper-parameters, update index,
 micro-batch counts, which fused entry points are used, whether the first gradient is adopted in
-place) against the oracle's binary32 form: two
+place, whether the workers' accumulation steps share launches) against the oracle's binary32 form: two
 rounds each, every output compared bit for bit."""
 import numpy as np
 import pytest
@@ -42,17 +42,19 @@ def test_random_configurations_are_bit_exact(seed):
                      float(rng.choice([0.0, 0.01, 0.1, 0.3])))
             step0 = int(rng.choice([0, 1, 7, 99, 4999]))
             ks = [[int(rng.integers(1, 5)) for _ in range(W)] for _ in range(2)]
-            stash, fp, fr, adopt = (bool(rng.integers(0, 2)) for _ in range(4))
+            stash, fp, fr, adopt, batched = (bool(rng.integers(0, 2)) for _ in range(5))
             b16acc = (not f32comm) and rng.integers(0, 5) == 0
             print(f"seed {seed} case {it}: n={n} W={W} shape={shape} bound={bound} "
                   f"blocked={blocked}/{block} f32comm={f32comm} hyper={hyper} step0={step0} "
-                  f"stash={stash} adopt={adopt} publish={fp} reduce={fr} bf16acc={b16acc}", flush=True)
+                  f"stash={stash} adopt={adopt} publish={fp} reduce={fr} bf16acc={b16acc} "
+                  f"batched={batched}", flush=True)
             theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
             m = (rng.standard_normal(n) * 1e-4).astype(np.float32)
             v = (m.astype(np.float64) ** 2 * rng.uniform(0.5, 4, n)).astype(np.float32)
             own = A.ShardOwner(n, W, A.make_hyper(*hyper), comm_bf16=not f32comm, fused_publish=fp,
                                fused_reduce=fr, blocked_state=blocked, block_elems=block,
-                               bf16_stash=stash, bf16_accumulate=bool(b16acc), adopt_first=adopt)
+                               bf16_stash=stash, bf16_accumulate=bool(b16acc), adopt_first=adopt,
+                               batched=batched)
             for name, x in (("theta", theta), ("m", m), ("v", v)):
                 own.set_state(name, torch.from_numpy(x.copy()).cuda())
             own.step.value = step0
@@ -61,11 +63,15 @@ def test_random_configurations_are_bit_exact(seed):
                                      acc_dtype="bf16" if b16acc else "f32")
             for _ in range(2):
                 for stage in (0, 1):
+                    rows = []
                     for w in range(W):
+                        row = []
                         for k in range(ks[stage][w]):
                             g = oracle.cast((rng.standard_normal(n) * 1e-3).astype(np.float32))
-                            own.add_microbatch(w, bf16_tensor(g), last=(k == ks[stage][w] - 1))
+                            row.append(bf16_tensor(g))
                             ref.add_microbatch(w, g)
+                        rows.append(row)
+                    own.add_microbatch_rows(rows)
                     if stage == 0:
                         own.stage1()
                         ref.stage1()

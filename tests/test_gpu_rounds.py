@@ -32,7 +32,7 @@ def gpu_hyper(A, w):
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
-                 bf16_acc=False, schedules=None, adopt=False):
+                 bf16_acc=False, schedules=None, adopt=False, batched=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -43,7 +43,7 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
                          fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash,
                          bf16_accumulate=bf16_acc,
                          lr_schedule=None if schedules is None else schedules[0],
-                         adopt_first=adopt)
+                         adopt_first=adopt, batched=batched)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -189,6 +189,27 @@ def test_a_stage_without_a_gradient_from_every_worker_is_refused():
     assert own.step.value == 0 and own.total.value == 0
 
 
+def test_one_launch_for_all_workers_changes_no_bits():
+    """batched: workers at the same step of their accumulation share one launch."""
+    tiny = synth.WORKLOADS["tiny"]
+    run_workload(tiny, batched=True)                               # base entry points
+    run_workload(tiny, batched=True, stash=True, fused_publish=True, fused_reduce=True,
+                 blocked=True)
+    w = synth.Workload(name="ragged", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
+                       k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
+    run_workload(w, batched=True)                                  # unequal counts: groups change
+    run_workload(w, batched=True, fused_publish=True)
+    run_workload(w, batched=True, stash=True)
+    run_workload(w, batched=True, stash=True, fused_publish=True, fused_reduce=True, blocked=True)
+    run_workload(w, batched=True, stash=True, adopt=True, fused_publish=True, fused_reduce=True)
+    run_workload(w, batched=True, bf16_acc=True, fused_reduce=True)
+    run_workload(w, batched=True, comm_bf16=False, rounds=2)
+    wide = synth.Workload(name="wide", n=70_001, workers=20, rounds=2, grad_std=1e-3,
+                          k_range=(2, 5), seed=8)                  # more workers than one launch holds
+    run_workload(wide, batched=True, stash=True, fused_publish=True, fused_reduce=True)
+    run_workload(wide, batched=True)
+
+
 def test_tiny_with_blocked_state():
     w = synth.WORKLOADS["tiny"]
     run_workload(w, blocked=True)
@@ -227,11 +248,18 @@ def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
 
 
 def test_seven_billion_scale_shard_fused_path_as_benched():
-    # the configuration bench.py times by default: fused publish, fused reduce + step
+    # the configuration bench.py times by default: bf16 stash, fused publish, fused reduce + step,
+    # interleaved state, one accumulate launch for all workers
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
-                 stash=True, rounds=3)
+                 stash=True, batched=True, rounds=3)
 
 
 def test_seven_billion_hetero_blocked_state_fused_path():
     run_workload(synth.WORKLOADS["7b_hetero"], fused_publish=True, fused_reduce=True,
-                 blocked=True, stash=True, rounds=2)
+                 blocked=True, stash=True, batched=True, rounds=2)
+
+
+def test_smaller_workloads_on_the_benched_path():
+    for name, rounds in (("gpt2s", 3), ("1b", 2)):
+        run_workload(synth.WORKLOADS[name], fused_publish=True, fused_reduce=True, blocked=True,
+                     stash=True, batched=True, rounds=rounds)

@@ -80,3 +80,33 @@ def test_workload_tables():
     assert sl[0][0] == 0 and sl[-1][1] == w["7b_hetero"].n
     assert all(a < b for a, b in sl) and all(sl[i][1] <= sl[i + 1][0] for i in range(len(sl) - 1))
     assert sum(b - a for a, b in sl) < 1 << 20
+
+
+def test_sampled_ranges_cover_every_phase_of_the_layouts():
+    """Full-size runs are checked on sampled index ranges; the interior samples must not sit at
+    one fixed phase of the state blocks, tiles or vectors."""
+    for name in ("gpt2s", "1b", "7b", "7b_hetero"):
+        w = synth.WORKLOADS[name]
+        sl = w.sample_slices()
+        assert sl[0][0] == 0 and sl[-1][1] == w.n                     # head and (ragged) tail
+        assert all(a < b for a, b in sl)
+        assert all(sl[k][1] <= sl[k + 1][0] for k in range(len(sl) - 1))   # ascending, disjoint
+        inner = sl[1:-1]
+        assert len(inner) >= 8
+        hit = np.zeros(8192, bool)
+        for a, b in inner:
+            hit[np.arange(a, b) % 8192] = True
+        assert hit.all()                                              # every in-block offset
+        starts = {a % 256 for a, _ in inner}
+        assert len(starts) == len(inner) if len(inner) <= 256 else len(starts) == 256
+        straddle = sum((a // 8192) != ((b - 1) // 8192) for a, b in inner)
+        assert straddle >= len(inner) // 3                            # state-block boundaries
+        assert any(a % 4 for a, _ in inner) and any(a % 8 == 0 for a, _ in inner)
+        assert sum(b - a for a, b in sl) < 400_000                    # the oracle's share stays small
+    # the interleaved state buffer (16 bytes per element index) passes 2^32 bytes at element
+    # 2^28: samples on both sides of it in the two largest workloads
+    for name in ("7b", "7b_hetero"):
+        inner = synth.WORKLOADS[name].sample_slices()[1:-1]
+        assert any(b < (1 << 28) for _, b in inner) and sum(a > (1 << 28) for a, _ in inner) > 20
+    # small shards are checked whole
+    assert synth.WORKLOADS["tiny"].sample_slices() == [(0, 1 << 20)]
