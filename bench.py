@@ -482,19 +482,23 @@ def summarize_rocprof(raw):
                                f"{100 * v['frac_of_peak']:.1f} % of 8 TB/s")
                 out.append(f"  whole round: {line['ms_per_step']:.3f} ms -> {line['value']:.4g} shard "
                            f"elements/s; checked against the oracle: {line.get('checked')}")
-                # rocprofv3's average against the events', kernel by kernel
-                by_label = collections.defaultdict(list)
-                for r in rows:
-                    lab = _label_of(r["Name"], 0, n)
-                    if lab:
-                        by_label[lab.rstrip("0123456789")].append(r)
-                out += ["", "Agreement of the two clocks (rocprofv3 average over ALL launches of the "
-                            "kernel in the process vs HIP events over the timed rounds):"]
-                for k, v in ks.items():
-                    cand = by_label.get(k.split("*")[0] + ("*" if "*" in k else ""))
-                    if cand and len(cand) == 1:
-                        out.append(f"  {k:30s} rocprofv3 {float(cand[0]['AverageNs']) / 1e6:.4f} ms   "
-                                   f"events {v['avg_ms']:.4f} ms")
+                # rocprofv3's own durations against the events', kernel by kernel (from the
+                # per-dispatch trace, where a batched launch shows its worker count as grid.y)
+                tr = glob.glob(os.path.join(raw, tag, "*_kernel_trace.csv"))
+                if tr:
+                    dur = collections.defaultdict(list)
+                    for r in csv.DictReader(open(tr[0])):
+                        lab = _label_of(r["Kernel_Name"], 0, n)
+                        if lab:
+                            if "*" in lab:
+                                lab = lab.split("*")[0] + "*" + r["Grid_Size_Y"]
+                            dur[lab].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+                    out += ["", "Agreement of the two clocks (rocprofv3: average over ALL launches of that "
+                                "kernel and worker count in the process; events: the timed rounds):"]
+                    for k, v in ks.items():
+                        if k in dur:
+                            out.append(f"  {k:30s} rocprofv3 {sum(dur[k]) / len(dur[k]) / 1e6:.4f} ms "
+                                       f"({len(dur[k])} launches)   events {v['avg_ms']:.4f} ms")
             sa = line.get("standalone_step_kernels")
             if isinstance(sa, dict):
                 out += ["", "acco_commit_step / acco_estimate_step on their own after the timed region "
