@@ -23,10 +23,10 @@
  *   *_f32  the same update in binary32, each operation individually rounded,
  *          with the bias corrections folded into host scalars (the precision
  *          the paper fixes for the sharded states).
- * Readings taken where the paper is silent (estimate does not advance m, v or
- * the step index; epsilon added after the bias-corrected square root; decay
- * multiplies theta(t); division by the total micro-batch count) are listed in
- * the repository's design document.
+ * Readings taken where the paper is silent: the estimate does not advance m, v or
+ * the step index; epsilon is added after the bias-corrected square root; the decay
+ * multiplies theta(t); the gradient sum is divided by the total micro-batch count.
+ * Each is repeated at the function it concerns.
  *
  * Pins: every function here is pinned by tests that do not call back into this
  * file's formulas (closed forms, exhaustive bf16 tables, torch CPU routines,

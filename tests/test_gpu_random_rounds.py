@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from parity import bf16_tensor, bit_mismatches, bits_of
+from parity import adam_state, bf16_tensor, bit_mismatches, bits_of
 
 pytestmark = pytest.mark.gpu
 
@@ -48,9 +48,10 @@ def test_random_configurations_are_bit_exact(seed):
                   f"blocked={blocked}/{block} f32comm={f32comm} hyper={hyper} step0={step0} "
                   f"stash={stash} adopt={adopt} publish={fp} reduce={fr} bf16acc={b16acc} "
                   f"batched={batched}", flush=True)
-            theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
-            m = (rng.standard_normal(n) * 1e-4).astype(np.float32)
-            v = (m.astype(np.float64) ** 2 * rng.uniform(0.5, 4, n)).astype(np.float32)
+            # every other case starts from a state no run of Adam need have produced (m and v
+            # unrelated, |m|/sqrt(v) up to 1e3, zero and denormal v); all comparisons below are
+            # bit for bit with the binary32 form, so no tolerance is involved
+            theta, m, v, _ = adam_state(rng, n, "wide" if it % 2 else "warm")
             own = A.ShardOwner(n, W, A.make_hyper(*hyper), comm_bf16=not f32comm, fused_publish=fp,
                                fused_reduce=fr, blocked_state=blocked, block_elems=block,
                                bf16_stash=stash, bf16_accumulate=bool(b16acc), adopt_first=adopt,
