@@ -763,13 +763,23 @@ def main():
     owner.trace = None
     ms_per_step = t_start.elapsed_time(t_end) / args.steps
 
+    # the same rounds once more without the per-kernel event pairs: what the instrumentation
+    # costs (nothing at 875M elements; a third of the round on the cache-resident tiny workload)
+    u0, u1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    u0.record()
+    for r in range(args.steps):
+        run_round(owner, w, grads)
+    u1.record()
+    torch.cuda.synchronize()
+    plain_ms_per_step = u0.elapsed_time(u1) / args.steps
+
     # ---- outside the timed region: is the state the timed rounds left the right one?
     checks = []
     replay = None
     if not args.no_check:
         replay = OracleReplay(w, "bf16" if args.bf16_accumulate else "f32")
         snap = replay.snapshot(torch, owner)
-        replay.run(args.warmup + args.steps)
+        replay.run(args.warmup + 2 * args.steps)
         checks.append(dict(replay.compare(snap), after="timed rounds"))
 
     # The same round on the five base entry points only (acco_accumulate, acco_cast_params as the
@@ -916,7 +926,8 @@ def main():
                    "one_accumulate_launch_for_all_workers": batched,
                    "launches_per_step": sum(k["calls_per_step"] for k in kernels.values()),
                    "bytes_per_elem_per_step": bytes_per_round,
-                   "host_wall_ms_per_step": wall * 1e3 / args.steps},
+                   "host_wall_ms_per_step": wall * 1e3 / args.steps,
+                   "ms_per_step_without_per_kernel_events": plain_ms_per_step},
         "round_GB/s": round(bytes_per_round * w.n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
         "kernels": kernels,

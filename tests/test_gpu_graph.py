@@ -83,3 +83,46 @@ def test_speculative_stage_recorded_in_a_graph_replays_like_eager_calls():
         assert np.array_equal(captured["gsum"].cpu().numpy().view(np.uint32), gsum_h.view(np.uint32))
     for t, b in zip((theta, m, v), before):            # the speculative stage commits nothing
         assert torch.equal(t.view(torch.int32), b.view(torch.int32))
+
+
+def test_batched_accumulation_launches_replay_from_a_graph():
+    """acco_accumulate_batch passes its pointer table by value: a recorded launch keeps working on
+    the same buffers with new contents, like the single calls."""
+    import paper_2406_02613_amd as A
+    B = A.binding
+    n, W = 70_001, 5
+    rng = np.random.default_rng(78)
+    grads = [[torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(W)] for _ in range(2)]
+    stash = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(W)]
+    comm = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(W)]
+
+    def stage():
+        B.acco_accumulate_batch(B.BATCH_FIRST, n, out_bf16=stash, grad_bf16=grads[0])
+        B.acco_accumulate_batch(B.BATCH_SECOND_PUBLISH, n, out_bf16=comm, stash_bf16=stash,
+                                grad_bf16=grads[1])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        stage()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stage()
+    for replay in range(3):
+        print("batched graph replay", replay, flush=True)
+        host = [[oracle.cast((rng.standard_normal(n) * 1e-3).astype(np.float32)) for _ in range(W)]
+                for _ in range(2)]
+        for k in range(2):
+            for w in range(W):
+                grads[k][w].copy_(bf16_tensor(host[k][w]))              # eager work between replays
+        for c in comm:
+            c.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for w in range(W):
+            acc = np.empty(n, np.float32)
+            oracle.accumulate(acc, host[0][w], init=True)
+            oracle.accumulate(acc, host[1][w], init=False)
+            assert np.array_equal(bits_of(comm[w]), oracle.cast(acc)), (replay, w)
