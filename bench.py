@@ -97,6 +97,11 @@ def parse():
     ap.add_argument("--base-path", action="store_true",
                     help="the five base entry points only (= all three --unfused-* flags "
                          "except the fused bf16 output of the commit)")
+    ap.add_argument("--planar-comm", action="store_true",
+                    help="W separate communication buffers instead of the interleaved blocks of "
+                         "one buffer")
+    ap.add_argument("--comm-block-elems", type=int, default=16384,
+                    help="elements per block of the interleaved communication buffers")
     ap.add_argument("--per-worker-launches", action="store_true",
                     help="one accumulate launch per worker and micro-batch instead of one launch "
                          "for all workers that are at the same point of their accumulation")
@@ -395,23 +400,23 @@ def cpu_baseline(w, target_seconds, acc_dtype="f32"):
 
 # kernel-name fragment -> label of bench.py's kernel table ("*" = one launch over several workers)
 KERNEL_LABELS = (
-    ("Batch<acco::StashOp<false>", "accumulate_first*"),
-    ("Batch<acco::StashOp<true>", "accumulate_first_publish*"),
-    ("Batch<acco::SecondPublishOp", "accumulate_second_publish*"),
+    ("Batch<acco::StashOp<false,", "accumulate_first*"),
+    ("Batch<acco::StashOp<true,", "accumulate_first_publish*"),
+    ("Batch<acco::SecondPublishOp<", "accumulate_second_publish*"),
     ("Batch<acco::SecondOp", "accumulate_second*"),
     ("Batch<acco::AccumulateOp<true>", "accumulate_init*"),
     ("Batch<acco::AccumulateOp<false>", "accumulate*"),
-    ("Batch<acco::AccumulatePublishOp<false, false>", "accumulate_publish*"),
-    ("Batch<acco::CastOp", "cast*"),
-    ("Single<acco::StashOp<false>", "accumulate_first"),
-    ("Single<acco::StashOp<true>", "accumulate_first_publish"),
-    ("Single<acco::SecondPublishOp", "accumulate_second_publish"),
+    ("Batch<acco::AccumulatePublishOp<false, false,", "accumulate_publish*"),
+    ("Batch<acco::CastOp<", "cast*"),
+    ("Single<acco::StashOp<false,", "accumulate_first"),
+    ("Single<acco::StashOp<true,", "accumulate_first_publish"),
+    ("Single<acco::SecondPublishOp<", "accumulate_second_publish"),
     ("Single<acco::SecondOp", "accumulate_second"),
     ("Single<acco::AccumulateOp<true>", "accumulate_init"),
     ("Single<acco::AccumulateOp<false>", "accumulate"),
-    ("Single<acco::AccumulatePublishOp<false, false>", "accumulate_publish"),
-    ("Single<acco::AccumulatePublishOp<true, false>", "accumulate_publish_init"),
-    ("Single<acco::CastOp", "cast"),
+    ("Single<acco::AccumulatePublishOp<false, false,", "accumulate_publish"),
+    ("Single<acco::AccumulatePublishOp<true, false,", "accumulate_publish_init"),
+    ("Single<acco::CastOp<", "cast"),
     ("ReduceAdamOp<false, true, false, true, false, true", "reduce_estimate"),
     ("ReduceAdamOp<true, true, true, false, false, true", "reduce_commit_bf16"),
     ("ReduceAdamOp<true, true, true, false, false, false", "reduce_commit"),
@@ -726,11 +731,16 @@ def main():
                      fused_reduce=not (args.unfused_reduce or args.base_path),
                      bf16_stash=stash and not args.bf16_accumulate, adopt_first=False)
     batched = not args.per_worker_launches
+    # interleaved communication buffers are written by the batched launches only
+    main_opts["interleaved_comm"] = not (args.planar_comm or args.bf16_accumulate
+                                         or args.base_path or not batched)
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          blocked_state=blocked, block_elems=args.block_elems,
                          bf16_stash=not args.bf16_accumulate,        # allocate the stash buffers
-                         bf16_accumulate=args.bf16_accumulate, batched=batched)
+                         bf16_accumulate=args.bf16_accumulate, batched=batched,
+                         interleaved_comm=main_opts["interleaved_comm"],
+                         comm_block_elems=args.comm_block_elems)
     owner.set_options(**main_opts)
     scratch = (owner.acc if owner.acc else
                [torch.empty(w.n, dtype=torch.float32, device="cuda") for _ in range(2)])
@@ -788,7 +798,8 @@ def main():
     base_round = adopted_round = None
     extras = not args.no_extras and not args.bf16_accumulate
     if extras and not args.base_path:
-        owner.set_options(fused_publish=False, fused_reduce=False, bf16_stash=False)
+        owner.set_options(fused_publish=False, fused_reduce=False, bf16_stash=False,
+                          interleaved_comm=False)
         owner.batched = False
         base_round, done = time_rounds(torch, owner, w, grads, max(2, min(5, args.steps)))
         if replay is not None:
@@ -924,6 +935,9 @@ def main():
                    "accumulator_dtype": "bf16" if args.bf16_accumulate else "f32",
                    "fused_reduce": main_opts["fused_reduce"],
                    "one_accumulate_launch_for_all_workers": batched,
+                   "communication_buffers": (f"interleaved in blocks of {args.comm_block_elems} "
+                                             "elements" if main_opts["interleaved_comm"]
+                                             else "planar, one allocation per worker"),
                    "launches_per_step": sum(k["calls_per_step"] for k in kernels.values()),
                    "bytes_per_elem_per_step": bytes_per_round,
                    "host_wall_ms_per_step": wall * 1e3 / args.steps,

@@ -88,7 +88,17 @@ typedef struct acco_adamw_t {
  *   step then runs at 6.4-6.6 TB/s every time; with four distant planar arrays at 5.4-6.4
  *   depending on where they happen to be allocated).  All four arrays share the one layout.
  *   block_elems: a power of two >= 4; block_stride: a multiple of 4, >= block_elems.
- * The worker shards and every bf16 / fp32 output stay planar.
+ * The fp32 and bf16 outputs of the step entry points stay planar.
+ *
+ * The same description serves a second purpose: the W workers' bf16 communication buffers
+ * interleaved block by block in ONE buffer - [worker 0 block][worker 1 block]...[worker W-1
+ * block] repeated, shard w's pointer = base + w * block_elems, block_stride = W * block_elems.
+ * acco_accumulate_batch writes such buffers (out_layout) and the reduction entry points read
+ * them (shard_layout).  On MI355X, W = 8 buffers of 875M elements in 16384-element blocks,
+ * alternating with eight separate buffers inside one process: reduce + estimate 4.51 ms against
+ * 4.58-4.92 (depending on where the eight buffers happen to lie), reduce + commit 5.91 against
+ * 6.05-6.47, second micro-batch + publish 6.53 against 6.32; the round 31.85 ms against 32.36.
+ * For a bf16 array block_elems must be >= 8; a blocked shard layout requires bf16 shards.
  */
 typedef struct acco_layout_t {
     int64_t block_elems;
@@ -174,8 +184,12 @@ int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stas
  *            acc, bf16[n] for the others), read before the call returns; an array the
  *            operation does not use may be NULL
  *   counts   host, int64[workers], nullable, in/out: the workers' micro-batch counters
- * Errors: as the single calls; in addition no buffer the call writes may overlap any other
- *         buffer of the call, of the same or of another worker (ACCO_ERR_ALIAS).
+ *   out_layout  host, nullable: layout shared by all out_bf16[w] (NULL = planar); accepted for
+ *            the operations that write out_bf16 other than ACCO_BATCH_RUNNING_BF16
+ * Errors: as the single calls; in addition no buffer the call writes may share an element with
+ *         any other buffer of the call, of the same or of another worker (ACCO_ERR_ALIAS; two
+ *         outputs of the same blocked layout may interleave), and a layout where none is
+ *         accepted is ACCO_ERR_ARG.
  */
 typedef enum acco_batch_op {
     ACCO_BATCH_ACCUMULATE_INIT    = 0,
@@ -191,7 +205,8 @@ typedef enum acco_batch_op {
 
 int acco_accumulate_batch(int op, int workers, float* const* acc, uint16_t* const* out_bf16,
                           const uint16_t* const* stash_bf16, const uint16_t* const* grad_bf16,
-                          int64_t n, int64_t* counts, void* stream);
+                          int64_t n, int64_t* counts, const acco_layout_t* out_layout,
+                          void* stream);
 
 /*
  * The accumulation of Alg. 1 with the running sum itself held in bf16, the precision the
@@ -231,12 +246,14 @@ int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, void* stre
  *   total     host, nullable, in/out: accumulate ? *total + sum(counts) : sum(counts).
  *             counts and total are given together or not at all.
  *   gsum_layout  host, nullable: layout of gsum (NULL = planar)
+ *   shard_layout host, nullable: layout shared by all shards (NULL = planar; bf16 shards only)
  * Errors: NULLs, bad n/workers/dtype/flag, misalignment, gsum overlapping a
- *         shard, negative count, total overflow.
+ *         shard, negative count, total overflow, a blocked layout for fp32 shards.
  */
 int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype, int64_t n,
                        int accumulate, const int64_t* counts, int64_t* total,
-                       const acco_layout_t* gsum_layout, void* stream);
+                       const acco_layout_t* gsum_layout, const acco_layout_t* shard_layout,
+                       void* stream);
 
 /*
  * Stage (1) of eq. (ACCO): the speculative parameters
@@ -280,13 +297,15 @@ int acco_commit_step(float* theta, float* m, float* v, const float* gsum, uint16
  * Same values as the two separate calls; saves re-reading gsum.
  *   gsum    device, fp32[n], out
  *   counts  host, int64[workers], required;  total  host, out, required: sum(counts) >= 1
+ *   shard_layout  as in acco_reduce_shards
  * Other arguments and errors as acco_reduce_shards and acco_estimate_step.
  */
 int acco_reduce_estimate_step(const float* theta, const float* m, const float* v, float* gsum,
                               const void* const* shards, int workers, int dtype,
                               const int64_t* counts, int64_t* total, float* theta_tilde_f32,
                               uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
-                              int64_t step, const acco_layout_t* state_layout, void* stream);
+                              int64_t step, const acco_layout_t* state_layout,
+                              const acco_layout_t* shard_layout, void* stream);
 
 /*
  * acco_reduce_shards(accumulate = 1) fused with acco_commit_step: stage 2 in one pass.
@@ -302,7 +321,8 @@ int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
                             const void* const* shards, int workers, int dtype,
                             const int64_t* counts, int64_t* total, uint16_t* theta_bf16, int64_t n,
                             const acco_adamw_t* hp, int64_t* step,
-                            const acco_layout_t* state_layout, void* stream);
+                            const acco_layout_t* state_layout, const acco_layout_t* shard_layout,
+                            void* stream);
 
 /*
  * Plain SGD with decoupled weight decay as Opt - the optimizer of the paper's convergence

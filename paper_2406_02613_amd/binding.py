@@ -68,10 +68,11 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(_build.ACCO_SO)
         p, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         pi64 = ctypes.POINTER(ctypes.c_int64)
+        play = ctypes.POINTER(Layout)
         L.acco_accumulate.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_cast_params.argtypes = [p, p, i64, p]
-        play = ctypes.POINTER(Layout)
-        L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, play, p]
+        L.acco_reduce_shards.argtypes = [p, ctypes.POINTER(p), ci, ci, i64, ci, pi64, pi64, play, play,
+                                         p]
         L.acco_estimate_step.argtypes = [p, p, p, p, p, p, i64, ctypes.POINTER(AdamW), i64, i64,
                                          play, p]
         L.acco_commit_step.argtypes = [p, p, p, p, p, i64, ctypes.POINTER(AdamW), pi64, i64, play,
@@ -81,11 +82,12 @@ def lib() -> ctypes.CDLL:
         L.acco_accumulate_bf16.argtypes = [p, p, i64, ci, pi64, p]
         L.acco_accumulate_second.argtypes = [p, p, p, p, i64, pi64, p]
         pp = ctypes.POINTER(p)
-        L.acco_accumulate_batch.argtypes = [ci, ci, pp, pp, pp, pp, i64, pi64, p]
+        L.acco_accumulate_batch.argtypes = [ci, ci, pp, pp, pp, pp, i64, pi64, play, p]
         L.acco_reduce_estimate_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64,
-                                                p, p, i64, ctypes.POINTER(AdamW), i64, play, p]
+                                                p, p, i64, ctypes.POINTER(AdamW), i64, play, play,
+                                                p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
-                                              i64, ctypes.POINTER(AdamW), pi64, play, p]
+                                              i64, ctypes.POINTER(AdamW), pi64, play, play, p]
         L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
         L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
@@ -156,17 +158,19 @@ def _dev(t, dtype, n: int, name: str) -> int:
     return t.data_ptr()
 
 
-def _state(tensors, names, n=None):
-    """Pointers, logical length and layout of state arrays (theta, m, v, gsum).
+def _state(tensors, names, n=None, dtype=None):
+    """Pointers, logical length and layout of arrays that share a layout (theta, m, v, gsum; or
+    the workers' communication buffers).
 
-    Each tensor is either 1-D contiguous fp32 (planar) or a 2-D fp32 view of shape
-    (blocks, block_elems) with strides (block_stride, 1) - a component of a block-interleaved
-    buffer.  All tensors passed together must have the same form."""
+    Each tensor is either 1-D contiguous (planar) or a 2-D view of shape (blocks, block_elems)
+    with strides (block_stride, 1) - a component of a block-interleaved buffer.  All tensors
+    passed together must have the same form.  dtype: torch.float32 unless given."""
     import torch
+    dtype = torch.float32 if dtype is None else dtype
     t0 = tensors[0]
     if t0.dim() == 1:
         n = t0.numel() if n is None else int(n)
-        return [_dev(t, torch.float32, n, nm) for t, nm in zip(tensors, names)], n, None
+        return [_dev(t, dtype, n, nm) for t, nm in zip(tensors, names)], n, None
     if t0.dim() != 2:
         raise ValueError(f"{names[0]}: expected a 1-D tensor or a (blocks, block_elems) view")
     nblk, blk = t0.shape
@@ -179,8 +183,8 @@ def _state(tensors, names, n=None):
     for t, nm in zip(tensors, names):
         if not t.is_cuda or t.device.index != torch.cuda.current_device():
             raise ValueError(f"{nm}: must live on the current GPU")
-        if t.dtype != torch.float32:
-            raise TypeError(f"{nm}: expected torch.float32, got {t.dtype}")
+        if t.dtype != dtype:
+            raise TypeError(f"{nm}: expected {dtype}, got {t.dtype}")
         if t.dim() != 2 or tuple(t.shape) != (nblk, blk) or t.stride(1) != 1 or \
                 (nblk > 1 and t.stride(0) != stride):
             raise ValueError(f"{nm}: all state views must share shape (blocks, block_elems) and "
@@ -290,27 +294,31 @@ def acco_accumulate_batch(op: int, n: int, *, acc: Optional[Sequence] = None,
                           grad_bf16: Optional[Sequence] = None,
                           counts: Optional[Sequence[Counter]] = None) -> None:
     """One accumulation step of several workers in one launch; each array argument is a
-    sequence with one tensor per worker.  The workers' counters are updated as by the single
-    calls."""
+    sequence with one tensor per worker.  out_bf16 may be planar tensors or the views of an
+    interleaved buffer (state.InterleavedShards); the layout is derived from their strides.
+    The workers' counters are updated as by the single calls."""
     import torch
     cols = (("acc", acc, torch.float32), ("out_bf16", out_bf16, torch.bfloat16),
             ("stash_bf16", stash_bf16, torch.bfloat16), ("grad_bf16", grad_bf16, torch.bfloat16))
     W = max(len(c) for _, c, _ in cols if c is not None)
-    arrays = []
+    arrays, layout = [], None
     for name, col, dt in cols:
         if col is None:
             arrays.append(None)
             continue
         if len(col) != W:
             raise ValueError(f"{name}: one tensor per worker")
-        arrays.append((ctypes.c_void_p * W)(*[_dev(t, dt, n, f"{name}[{i}]")
-                                              for i, t in enumerate(col)]))
+        if name == "out_bf16":
+            ptrs, _, layout = _state(list(col), [f"{name}[{i}]" for i in range(W)], n, dt)
+        else:
+            ptrs = [_dev(t, dt, n, f"{name}[{i}]") for i, t in enumerate(col)]
+        arrays.append((ctypes.c_void_p * W)(*ptrs))
     cnts = None
     if counts is not None:
         if len(counts) != W:
             raise ValueError("counts: one per worker")
         cnts = (ctypes.c_int64 * W)(*[c.value for c in counts])
-    rc = lib().acco_accumulate_batch(int(op), W, *arrays, int(n), cnts, _stream())
+    rc = lib().acco_accumulate_batch(int(op), W, *arrays, int(n), cnts, _lay(layout), _stream())
     _check(rc, "acco_accumulate_batch")
     if counts is not None:
         for c, x in zip(counts, cnts):
@@ -325,31 +333,9 @@ def acco_cast_params(out_bf16, src) -> None:
     _check(rc, "acco_cast_params")
 
 
-def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
-                       counts: Optional[Sequence[int]] = None,
-                       total: Optional[Counter] = None, n: Optional[int] = None) -> None:
-    import torch
-    (gsum_ptr,), n, layout = _state([gsum], ["gsum"], n)
-    W = len(shards)
-    if W < 1:
-        raise AccoError(ACCO_ERR_SIZE, "acco_reduce_shards")
-    dt = shards[0].dtype
-    if dt not in (torch.bfloat16, torch.float32):
-        raise TypeError("shards: expected bfloat16 or float32 tensors")
-    ptrs = (ctypes.c_void_p * W)(*[_dev(s, dt, n, f"shards[{i}]") for i, s in enumerate(shards)])
-    cnts = None
-    if counts is not None:
-        if len(counts) != W:
-            raise ValueError("counts: one per shard")
-        cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
-    rc = lib().acco_reduce_shards(gsum_ptr, ptrs, W,
-                                  ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32, n,
-                                  int(bool(accumulate)), cnts,
-                                  None if total is None else total.ref(), _lay(layout), _stream())
-    _check(rc, "acco_reduce_shards")
-
-
-def _shard_args(shards: Sequence, n: int, counts: Sequence[int], where: str):
+def _shard_ptrs(shards: Sequence, n: int, where: str):
+    """Device pointers, dtype code and layout of the worker shards (planar tensors or the views
+    of an interleaved bf16 buffer)."""
     import torch
     W = len(shards)
     if W < 1:
@@ -357,11 +343,33 @@ def _shard_args(shards: Sequence, n: int, counts: Sequence[int], where: str):
     dt = shards[0].dtype
     if dt not in (torch.bfloat16, torch.float32):
         raise TypeError("shards: expected bfloat16 or float32 tensors")
+    ptrs, _, layout = _state(list(shards), [f"shards[{i}]" for i in range(W)], n, dt)
+    return ((ctypes.c_void_p * W)(*ptrs), W, ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32,
+            layout)
+
+
+def acco_reduce_shards(gsum, shards: Sequence, accumulate: bool,
+                       counts: Optional[Sequence[int]] = None,
+                       total: Optional[Counter] = None, n: Optional[int] = None) -> None:
+    (gsum_ptr,), n, layout = _state([gsum], ["gsum"], n)
+    ptrs, W, dt, shard_layout = _shard_ptrs(shards, n, "acco_reduce_shards")
+    cnts = None
+    if counts is not None:
+        if len(counts) != W:
+            raise ValueError("counts: one per shard")
+        cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
+    rc = lib().acco_reduce_shards(gsum_ptr, ptrs, W, dt, n, int(bool(accumulate)), cnts,
+                                  None if total is None else total.ref(), _lay(layout),
+                                  _lay(shard_layout), _stream())
+    _check(rc, "acco_reduce_shards")
+
+
+def _shard_args(shards: Sequence, n: int, counts: Sequence[int], where: str):
+    ptrs, W, dt, shard_layout = _shard_ptrs(shards, n, where)
     if len(counts) != W:
         raise ValueError("counts: one per shard")
-    ptrs = (ctypes.c_void_p * W)(*[_dev(s, dt, n, f"shards[{i}]") for i, s in enumerate(shards)])
     cnts = (ctypes.c_int64 * W)(*[int(c) for c in counts])
-    return ptrs, cnts, W, (ACCO_BF16 if dt == torch.bfloat16 else ACCO_F32)
+    return ptrs, cnts, W, dt, shard_layout
 
 
 def acco_reduce_estimate_step(theta, m, v, gsum, shards: Sequence, counts: Sequence[int],
@@ -370,12 +378,12 @@ def acco_reduce_estimate_step(theta, m, v, gsum, shards: Sequence, counts: Seque
     import torch
     f32 = torch.float32
     st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
-    ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_estimate_step")
+    ptrs, cnts, W, dt, sl = _shard_args(shards, n, counts, "acco_reduce_estimate_step")
     rc = lib().acco_reduce_estimate_step(
         st[0], st[1], st[2], st[3], ptrs, W, dt, cnts, total.ref(),
         _opt(theta_tilde_f32, f32, n, "theta_tilde_f32"),
         _opt(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"), n, ctypes.byref(hp),
-        int(step), _lay(layout), _stream())
+        int(step), _lay(layout), _lay(sl), _stream())
     _check(rc, "acco_reduce_estimate_step")
 
 
@@ -384,11 +392,11 @@ def acco_reduce_commit_step(theta, m, v, gsum, shards: Sequence, counts: Sequenc
                             n: Optional[int] = None) -> None:
     import torch
     st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
-    ptrs, cnts, W, dt = _shard_args(shards, n, counts, "acco_reduce_commit_step")
+    ptrs, cnts, W, dt, sl = _shard_args(shards, n, counts, "acco_reduce_commit_step")
     rc = lib().acco_reduce_commit_step(
         st[0], st[1], st[2], st[3], ptrs, W, dt, cnts, total.ref(),
         _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n, ctypes.byref(hp), step.ref(),
-        _lay(layout), _stream())
+        _lay(layout), _lay(sl), _stream())
     _check(rc, "acco_reduce_commit_step")
 
 

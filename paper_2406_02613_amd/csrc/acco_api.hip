@@ -190,12 +190,14 @@ int launch(Entry e, const Op& op, int64_t n, hipStream_t stream, bool bounded = 
 // workers [0, count) of the three pointer columns, kBatchMax per launch
 template <class Op>
 int launch_batch(Entry e, void* const* a, const void* const* b, const void* const* c, int count,
-                 int64_t n, hipStream_t stream, bool bounded = true)
+                 int64_t n, hipStream_t stream, const typename Op::Shared& shared = {},
+                 bool bounded = true)
 {
     for (int w0 = 0; w0 < count; w0 += kBatchMax) {
         const int rows = count - w0 < kBatchMax ? count - w0 : kBatchMax;
         Batch<Op> src;
-        std::memset(&src, 0, sizeof src);
+        std::memset(&src.tab, 0, sizeof src.tab);
+        src.shared = shared;
         for (int r = 0; r < rows; ++r) {
             src.tab.a[r] = a[w0 + r];
             src.tab.b[r] = b != nullptr ? b[w0 + r] : nullptr;
@@ -275,6 +277,69 @@ AdamScalars fold(const acco_adamw_t& hp, int64_t step, int64_t total_count)
     return s;
 }
 
+// ------------------------------------------------------------------ state layout
+
+struct StateLayout {
+    bool    blocked = false;
+    int     vshift  = 0;   // log2(vectors per block)
+    int64_t block   = 0;   // elements per block
+    int64_t stride  = 0;   // elements between block starts
+};
+
+int parse_layout(const acco_layout_t* l, StateLayout* out)
+{
+    *out = StateLayout{};
+    if (l == nullptr || l->block_elems == 0) return ACCO_OK;
+    const int64_t b = l->block_elems, st = l->block_stride;
+    if (b < 4 || b > ((int64_t)1 << 30) || (b & (b - 1)) != 0) return ACCO_ERR_ARG;
+    if (st < b || st % 4 != 0 || st > ((int64_t)1 << 40)) return ACCO_ERR_ARG;
+    out->blocked = true;
+    out->block   = b;
+    out->stride  = st;
+    int sh       = 0;
+    while (((int64_t)4 << sh) < b) ++sh;
+    out->vshift = sh;
+    return ACCO_OK;
+}
+
+// bytes from the first to one past the last element of an array of n elements of esz bytes
+int64_t state_extent(const StateLayout& L, int64_t n, int64_t esz = 4)
+{
+    if (n <= 0) return 0;
+    if (!L.blocked) return n * esz;
+    const int64_t nblk = (n + L.block - 1) / L.block;
+    return ((nblk - 1) * L.stride + (n - (nblk - 1) * L.block)) * esz;
+}
+
+// do two arrays of the same layout and element size share an element?
+bool state_overlap(const void* a, const void* b, const StateLayout& L, int64_t n, int64_t esz = 4)
+{
+    const int64_t ext = state_extent(L, n, esz);
+    if (!overlap(a, ext, b, ext)) return false;
+    if (!L.blocked) return true;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    const uint64_t  period = (uint64_t)L.stride * esz, blk = (uint64_t)L.block * esz;
+    const uint64_t  dist   = (pa > pb ? pa - pb : pb - pa) % period;
+    return dist < blk || period - dist < blk;
+}
+
+// a planar buffer against a laid-out array (conservative for blocked layouts: whole extent)
+bool planar_overlaps_state(const void* p, int64_t bytes, const void* state, const StateLayout& L,
+                           int64_t n, int64_t esz = 4)
+{
+    return overlap(p, bytes, state, state_extent(L, n, esz));
+}
+
+template <class F>
+int with_layout(const StateLayout& L, F&& f)
+{
+    if (L.blocked) return f(StateAddr<true>{L.vshift, L.stride / 4});
+    return f(StateAddr<false>{});
+}
+
+template <class At>
+constexpr bool is_blocked = std::is_same<At, StateAddr<true>>::value;
+
 }  // namespace
 
 // ------------------------------------------------------------------ entry points
@@ -319,8 +384,8 @@ ACCO_API int acco_accumulate_bf16(uint16_t* acc_bf16, const uint16_t* grad_bf16,
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
         // in place: every lane reads its own elements of the running sum before it writes them
-        rc = init ? launch(kStash, StashOp<false>{acc_bf16, grad_bf16}, n, s)
-                  : launch(kSecond, SecondPublishOp{acc_bf16, acc_bf16, grad_bf16}, n, s);
+        rc = init ? launch(kStash, StashOp<false>{acc_bf16, grad_bf16, {}}, n, s)
+                  : launch(kSecond, SecondPublishOp<>{acc_bf16, acc_bf16, grad_bf16, {}}, n, s);
     }
     if (rc == ACCO_OK && count != nullptr) *count = init ? 1 : *count + 1;
     return rc;
@@ -333,7 +398,7 @@ ACCO_API int acco_cast_params(uint16_t* out_bf16, const float* src, int64_t n, v
     if (!aligned16(out_bf16) || !aligned16(src)) return ACCO_ERR_ALIGN;
     if (overlap(out_bf16, n * 2, src, n * 4)) return ACCO_ERR_ALIAS;
     if (n == 0) return ACCO_OK;
-    return launch(kCast, CastOp{out_bf16, src}, n, static_cast<hipStream_t>(stream));
+    return launch(kCast, CastOp<>{out_bf16, src, {}}, n, static_cast<hipStream_t>(stream));
 }
 
 
@@ -348,8 +413,8 @@ ACCO_API int acco_accumulate_first(uint16_t* stash_bf16, const uint16_t* grad_bf
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        rc = publish ? launch(kStash, StashOp<true>{stash_bf16, grad_bf16}, n, s)
-                     : launch(kStash, StashOp<false>{stash_bf16, grad_bf16}, n, s);
+        rc = publish ? launch(kStash, StashOp<true>{stash_bf16, grad_bf16, {}}, n, s)
+                     : launch(kStash, StashOp<false>{stash_bf16, grad_bf16, {}}, n, s);
     }
     if (rc == ACCO_OK && count != nullptr) *count = 1;
     return rc;
@@ -373,7 +438,7 @@ ACCO_API int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint1
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
         rc = acc != nullptr ? launch(kSecond, SecondOp{acc, stash_bf16, grad_bf16}, n, s, false)
-                            : launch(kSecond, SecondPublishOp{comm_bf16, stash_bf16, grad_bf16}, n, s);
+                            : launch(kSecond, SecondPublishOp<>{comm_bf16, stash_bf16, grad_bf16, {}}, n, s);
     }
     if (rc == ACCO_OK && count != nullptr) *count = 2;
     return rc;
@@ -382,7 +447,7 @@ ACCO_API int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint1
 ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
                                    uint16_t* const* out_bf16, const uint16_t* const* stash_bf16,
                                    const uint16_t* const* grad_bf16, int64_t n, int64_t* counts,
-                                   void* stream)
+                                   const acco_layout_t* out_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
@@ -399,12 +464,19 @@ ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
     if ((uses_acc && acc == nullptr) || (uses_out && out_bf16 == nullptr) ||
         (uses_stash && stash_bf16 == nullptr) || (uses_grad && grad_bf16 == nullptr))
         return ACCO_ERR_NULL;
+    StateLayout OL;
+    if (int rc = parse_layout(out_layout, &OL)) return rc;
+    // a blocked output: only where there is an output, not for the in-place running sum, and
+    // in blocks that hold whole 8-element vectors
+    if (OL.blocked && (!uses_out || op == ACCO_BATCH_RUNNING_BF16 || OL.block < 8))
+        return ACCO_ERR_ARG;
 
     // every buffer of the call as a byte range; written ranges must not meet any other range
     struct Range {
         const void* p;
-        int64_t     bytes;
+        int64_t     bytes;   // extent
         bool        written;
+        bool        laid;    // follows out_layout
     };
     Range ranges[4 * ACCO_MAX_WORKERS];
     int   nr = 0;
@@ -420,14 +492,18 @@ ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
             if (!used[k]) continue;
             if (n > 0 && cols[k] == nullptr) return ACCO_ERR_NULL;
             if (!aligned16(cols[k])) return ACCO_ERR_ALIGN;
-            ranges[nr++] = Range{cols[k], n * esz[k], wr[k]};
+            const bool laid = k == 1 && OL.blocked;
+            ranges[nr++] = Range{cols[k], laid ? state_extent(OL, n, 2) : n * esz[k], wr[k], laid};
         }
     }
     for (int i = 0; i < nr; ++i)
-        for (int j = i + 1; j < nr; ++j)
-            if ((ranges[i].written || ranges[j].written) &&
-                overlap(ranges[i].p, ranges[i].bytes, ranges[j].p, ranges[j].bytes))
-                return ACCO_ERR_ALIAS;
+        for (int j = i + 1; j < nr; ++j) {
+            if (!ranges[i].written && !ranges[j].written) continue;
+            const bool hit = (ranges[i].laid && ranges[j].laid)
+                                 ? state_overlap(ranges[i].p, ranges[j].p, OL, n, 2)
+                                 : overlap(ranges[i].p, ranges[i].bytes, ranges[j].p, ranges[j].bytes);
+            if (hit) return ACCO_ERR_ALIAS;
+        }
     const bool starts  = op == ACCO_BATCH_ACCUMULATE_INIT || op == ACCO_BATCH_FIRST ||
                         op == ACCO_BATCH_FIRST_PUBLISH;
     const bool seconds = op == ACCO_BATCH_SECOND || op == ACCO_BATCH_SECOND_PUBLISH;
@@ -446,33 +522,37 @@ ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
         const void* const* R = reinterpret_cast<const void* const*>(acc);
         const void* const* S = reinterpret_cast<const void* const*>(stash_bf16);
         const void* const* G = reinterpret_cast<const void* const*>(grad_bf16);
+        const int          W = workers;
         switch (op) {
             case ACCO_BATCH_ACCUMULATE_INIT:
-                rc = launch_batch<AccumulateOp<true>>(kAccumulate, A, G, nullptr, workers, n, s, false);
+                rc = launch_batch<AccumulateOp<true>>(kAccumulate, A, G, nullptr, W, n, s, {}, false);
                 break;
             case ACCO_BATCH_ACCUMULATE:
-                rc = launch_batch<AccumulateOp<false>>(kAccumulate, A, G, nullptr, workers, n, s);
-                break;
-            case ACCO_BATCH_ACCUMULATE_PUBLISH:
-                rc = launch_batch<AccumulatePublishOp<false, false>>(kAccumulatePublish, O, G, R, workers, n, s);
-                break;
-            case ACCO_BATCH_FIRST:
-                rc = launch_batch<StashOp<false>>(kStash, O, G, nullptr, workers, n, s);
-                break;
-            case ACCO_BATCH_FIRST_PUBLISH:
-                rc = launch_batch<StashOp<true>>(kStash, O, G, nullptr, workers, n, s);
+                rc = launch_batch<AccumulateOp<false>>(kAccumulate, A, G, nullptr, W, n, s);
                 break;
             case ACCO_BATCH_SECOND:
-                rc = launch_batch<SecondOp>(kSecond, A, G, S, workers, n, s, false);
+                rc = launch_batch<SecondOp>(kSecond, A, G, S, W, n, s, {}, false);
                 break;
-            case ACCO_BATCH_SECOND_PUBLISH:
-                rc = launch_batch<SecondPublishOp>(kSecond, O, G, S, workers, n, s);
+            case ACCO_BATCH_RUNNING_BF16:  // in place: each lane reads its elements first
+                rc = launch_batch<SecondPublishOp<>>(kSecond, O, G, reinterpret_cast<const void* const*>(out_bf16), W, n, s);
                 break;
-            case ACCO_BATCH_PUBLISH:
-                rc = launch_batch<CastOp>(kCast, O, nullptr, R, workers, n, s);
-                break;
-            default:  // ACCO_BATCH_RUNNING_BF16: in place, each lane reads its elements first
-                rc = launch_batch<SecondPublishOp>(kSecond, O, G, reinterpret_cast<const void* const*>(out_bf16), workers, n, s);
+            default:
+                // the operations with an output that may be laid out in blocks
+                rc = with_layout(OL, [&](auto oat) {
+                    constexpr bool B = is_blocked<decltype(oat)>;
+                    switch (op) {
+                        case ACCO_BATCH_ACCUMULATE_PUBLISH:
+                            return launch_batch<AccumulatePublishOp<false, false, B>>(kAccumulatePublish, O, G, R, W, n, s, oat);
+                        case ACCO_BATCH_FIRST:
+                            return launch_batch<StashOp<false, B>>(kStash, O, G, nullptr, W, n, s, oat);
+                        case ACCO_BATCH_FIRST_PUBLISH:
+                            return launch_batch<StashOp<true, B>>(kStash, O, G, nullptr, W, n, s, oat);
+                        case ACCO_BATCH_SECOND_PUBLISH:
+                            return launch_batch<SecondPublishOp<B>>(kSecond, O, G, S, W, n, s, oat);
+                        default:  // ACCO_BATCH_PUBLISH
+                            return launch_batch<CastOp<B>>(kCast, O, nullptr, R, W, n, s, oat);
+                    }
+                });
                 break;
         }
     }
@@ -483,69 +563,6 @@ ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
 
 namespace {
 
-// ------------------------------------------------------------------ state layout
-
-struct StateLayout {
-    bool    blocked = false;
-    int     vshift  = 0;   // log2(vectors per block)
-    int64_t block   = 0;   // elements per block
-    int64_t stride  = 0;   // elements between block starts
-};
-
-int parse_layout(const acco_layout_t* l, StateLayout* out)
-{
-    *out = StateLayout{};
-    if (l == nullptr || l->block_elems == 0) return ACCO_OK;
-    const int64_t b = l->block_elems, st = l->block_stride;
-    if (b < 4 || b > ((int64_t)1 << 30) || (b & (b - 1)) != 0) return ACCO_ERR_ARG;
-    if (st < b || st % 4 != 0 || st > ((int64_t)1 << 40)) return ACCO_ERR_ARG;
-    out->blocked = true;
-    out->block   = b;
-    out->stride  = st;
-    int sh       = 0;
-    while (((int64_t)4 << sh) < b) ++sh;
-    out->vshift = sh;
-    return ACCO_OK;
-}
-
-// bytes from the first to one past the last element of a state array of n elements
-int64_t state_extent(const StateLayout& L, int64_t n)
-{
-    if (n <= 0) return 0;
-    if (!L.blocked) return n * 4;
-    const int64_t nblk = (n + L.block - 1) / L.block;
-    return ((nblk - 1) * L.stride + (n - (nblk - 1) * L.block)) * 4;
-}
-
-// do two state arrays of the same layout share an element?
-bool state_overlap(const void* a, const void* b, const StateLayout& L, int64_t n)
-{
-    const int64_t ext = state_extent(L, n);
-    if (!overlap(a, ext, b, ext)) return false;
-    if (!L.blocked) return true;
-    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
-    const uint64_t  period = (uint64_t)L.stride * 4, blk = (uint64_t)L.block * 4;
-    const uint64_t  dist   = (pa > pb ? pa - pb : pb - pa) % period;
-    return dist < blk || period - dist < blk;
-}
-
-// a planar buffer against a state array (conservative for blocked layouts: whole extent)
-bool planar_overlaps_state(const void* p, int64_t bytes, const void* state, const StateLayout& L,
-                           int64_t n)
-{
-    return overlap(p, bytes, state, state_extent(L, n));
-}
-
-template <class F>
-int with_layout(const StateLayout& L, F&& f)
-{
-    if (L.blocked) return f(StateAddr<true>{L.vshift, L.stride / 4});
-    return f(StateAddr<false>{});
-}
-
-template <class At>
-constexpr bool is_blocked = std::is_same<At, StateAddr<true>>::value;
-
 ShardPtrs chunk_ptrs(const void* const* shards, int begin, int end)
 {
     ShardPtrs ptrs;
@@ -554,29 +571,51 @@ ShardPtrs chunk_ptrs(const void* const* shards, int begin, int end)
     return ptrs;
 }
 
+// The shards' own layout: only bf16 shards (the communication buffers) may be blocked.
+template <bool BF16, class F>
+int with_shard_layout(const StateLayout& SL, F&& f)
+{
+    if constexpr (BF16) {
+        if (SL.blocked) return f(StateAddr<true>{SL.vshift, SL.stride / 4});
+    }
+    return f(StateAddr<false>{});
+}
+
 // plain reduction of shards [0, workers) into gsum, kReduceChunk at a time
 template <bool BF16>
-int launch_reduce(float* gsum, const StateLayout& L, const void* const* shards, int workers,
-                  int64_t n, bool accumulate, hipStream_t stream)
+int launch_reduce(float* gsum, const StateLayout& L, const StateLayout& SL,
+                  const void* const* shards, int workers, int64_t n, bool accumulate,
+                  hipStream_t stream)
 {
     for (int w0 = 0; w0 < workers; w0 += kReduceChunk) {
         const int       end  = w0 + kReduceChunk < workers ? w0 + kReduceChunk : workers;
         const bool      acc  = accumulate || w0 > 0;
         const ShardPtrs ptrs = chunk_ptrs(shards, w0, end);
         const int       rc   = with_layout(L, [&](auto at) {
-            constexpr bool B = is_blocked<decltype(at)>;
-            if (acc)
-                return launch(kReduce, ReduceOp<kReduceChunk, BF16, true, B>{gsum, ptrs, end - w0, at}, n, stream);
-            return launch(kReduce, ReduceOp<kReduceChunk, BF16, false, B>{gsum, ptrs, end - w0, at}, n, stream);
+            return with_shard_layout<BF16>(SL, [&](auto sat) {
+                constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+                if (acc)
+                    return launch(kReduce, ReduceOp<kReduceChunk, BF16, true, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
+                return launch(kReduce, ReduceOp<kReduceChunk, BF16, false, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
+            });
         });
         if (rc != ACCO_OK) return rc;
     }
     return ACCO_OK;
 }
 
+// the shards' layout argument: blocked layouts are for bf16 shards, in blocks of whole vectors
+int parse_shard_layout(const acco_layout_t* l, int dtype, StateLayout* out)
+{
+    if (int rc = parse_layout(l, out)) return rc;
+    if (out->blocked && dtype != ACCO_BF16) return ACCO_ERR_ARG;
+    return ACCO_OK;
+}
+
 // shards: non-NULL (n > 0), aligned, none overlapping the state arrays listed
 int check_shards_vs_state(const void* const* shards, int workers, int dtype, int64_t n,
-                          const void* const* state, int nstate, const StateLayout& L)
+                          const void* const* state, int nstate, const StateLayout& L,
+                          const StateLayout& SL)
 {
     if (workers < 1 || workers > ACCO_MAX_WORKERS) return ACCO_ERR_SIZE;
     if (dtype != ACCO_BF16 && dtype != ACCO_F32) return ACCO_ERR_ARG;
@@ -585,7 +624,8 @@ int check_shards_vs_state(const void* const* shards, int workers, int dtype, int
         if (n > 0 && shards[w] == nullptr) return ACCO_ERR_NULL;
         if (!aligned16(shards[w])) return ACCO_ERR_ALIGN;
         for (int k = 0; k < nstate; ++k)
-            if (planar_overlaps_state(shards[w], n * esz, state[k], L, n)) return ACCO_ERR_ALIAS;
+            if (planar_overlaps_state(shards[w], state_extent(SL, n, esz), state[k], L, n))
+                return ACCO_ERR_ALIAS;
     }
     return ACCO_OK;
 }
@@ -594,17 +634,19 @@ int check_shards_vs_state(const void* const* shards, int workers, int dtype, int
 
 ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int workers, int dtype,
                                 int64_t n, int accumulate, const int64_t* counts, int64_t* total,
-                                const acco_layout_t* gsum_layout, void* stream)
+                                const acco_layout_t* gsum_layout,
+                                const acco_layout_t* shard_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || (n > 0 && gsum == nullptr)) return ACCO_ERR_NULL;
     if (accumulate != 0 && accumulate != 1) return ACCO_ERR_ARG;
     if ((counts == nullptr) != (total == nullptr)) return ACCO_ERR_NULL;
     if (!aligned16(gsum)) return ACCO_ERR_ALIGN;
-    StateLayout L;
+    StateLayout L, SL;
     if (int rc = parse_layout(gsum_layout, &L)) return rc;
+    if (int rc = parse_shard_layout(shard_layout, dtype, &SL)) return rc;
     const void* st[1] = {gsum};
-    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 1, L)) return rc;
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 1, L, SL)) return rc;
     int64_t new_total = 0;
     if (counts != nullptr)
         if (int rc = sum_counts(counts, workers, accumulate ? *total : 0, &new_total)) return rc;
@@ -612,8 +654,8 @@ ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int work
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        rc = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, L, shards, workers, n, accumulate, s)
-                                : launch_reduce<false>(gsum, L, shards, workers, n, accumulate, s);
+        rc = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, L, SL, shards, workers, n, accumulate, s)
+                                : launch_reduce<false>(gsum, L, SL, shards, workers, n, accumulate, s);
     }
     if (rc == ACCO_OK && total != nullptr) *total = new_total;
     return rc;
@@ -721,13 +763,13 @@ ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
         if (init && keep_acc)
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, true>{acc, grad_bf16, comm_bf16}, n, s, false);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, true>{acc, grad_bf16, comm_bf16, {}}, n, s, false);
         else if (init)
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, false>{acc, grad_bf16, comm_bf16}, n, s, false);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<true, false>{acc, grad_bf16, comm_bf16, {}}, n, s, false);
         else if (keep_acc)
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, true>{acc, grad_bf16, comm_bf16}, n, s);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, true>{acc, grad_bf16, comm_bf16, {}}, n, s);
         else
-            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, false>{acc, grad_bf16, comm_bf16}, n, s);
+            rc = launch(kAccumulatePublish, AccumulatePublishOp<false, false>{acc, grad_bf16, comm_bf16, {}}, n, s);
     }
     if (rc == ACCO_OK && count != nullptr) *count = init ? 1 : *count + 1;
     return rc;
@@ -739,44 +781,48 @@ namespace {
 // worker count go through the plain reduction first.
 template <bool BF16>
 int launch_reduce_estimate(const float* theta, const float* m, const float* v, float* gsum,
-                           const StateLayout& L, const void* const* shards, int workers,
-                           float* o32, uint16_t* o16, int64_t n, const AdamScalars& sc,
-                           hipStream_t s)
+                           const StateLayout& L, const StateLayout& SL,
+                           const void* const* shards, int workers, float* o32, uint16_t* o16,
+                           int64_t n, const AdamScalars& sc, hipStream_t s)
 {
     const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, shards, lead, n, false, s)) return rc;
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, s)) return rc;
     const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
     const int       cnt  = workers - lead;
     return with_layout(L, [&](auto at) {
-        constexpr bool B = is_blocked<decltype(at)>;
-        auto go = [&](auto acc_tag) {
-            constexpr bool ACC = decltype(acc_tag)::value;
-            if (o32 != nullptr && o16 != nullptr)
-                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at}, n, s);
-            if (o32 != nullptr)
-                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at}, n, s);
-            return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at}, n, s);
-        };
-        return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
+        return with_shard_layout<BF16>(SL, [&](auto sat) {
+            constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+            auto go = [&](auto acc_tag) {
+                constexpr bool ACC = decltype(acc_tag)::value;
+                if (o32 != nullptr && o16 != nullptr)
+                    return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at, sat}, n, s);
+                if (o32 != nullptr)
+                    return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at, sat}, n, s);
+                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at, sat}, n, s);
+            };
+            return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
+        });
     });
 }
 
 template <bool BF16>
 int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const StateLayout& L,
-                         const void* const* shards, int workers, uint16_t* o16, int64_t n,
-                         const AdamScalars& sc, hipStream_t s)
+                         const StateLayout& SL, const void* const* shards, int workers,
+                         uint16_t* o16, int64_t n, const AdamScalars& sc, hipStream_t s)
 {
     const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, shards, lead, n, true, s)) return rc;
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, true, s)) return rc;
     const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
     const int       cnt  = workers - lead;
     return with_layout(L, [&](auto at) {
-        constexpr bool B = is_blocked<decltype(at)>;
-        if (o16 != nullptr)
-            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at}, n, s);
-        return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at}, n, s);
+        return with_shard_layout<BF16>(SL, [&](auto sat) {
+            constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+            if (o16 != nullptr)
+                return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B, S>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at, sat}, n, s);
+            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B, S>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at, sat}, n, s);
+        });
     });
 }
 
@@ -787,21 +833,23 @@ ACCO_API int acco_reduce_estimate_step(const float* theta, const float* m, const
                                        int dtype, const int64_t* counts, int64_t* total,
                                        float* theta_tilde_f32, uint16_t* theta_tilde_bf16,
                                        int64_t n, const acco_adamw_t* hp, int64_t step,
-                                       const acco_layout_t* state_layout, void* stream)
+                                       const acco_layout_t* state_layout,
+                                       const acco_layout_t* shard_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || counts == nullptr || total == nullptr) return ACCO_ERR_NULL;
     if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
-    StateLayout L;
+    StateLayout L, SL;
     if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = parse_shard_layout(shard_layout, dtype, &SL)) return rc;
     if (int rc = check_step_buffers(theta, m, v, gsum, theta_tilde_f32, theta_tilde_bf16, n, L))
         return rc;
     const void* st[4] = {theta, m, v, gsum};
-    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L)) return rc;
-    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L, SL)) return rc;
+    const int64_t ext = state_extent(SL, n, dtype == ACCO_BF16 ? 2 : 4);
     for (int w = 0; w < workers; ++w)
-        if (overlap(theta_tilde_f32, n * 4, shards[w], n * esz) ||
-            overlap(theta_tilde_bf16, n * 2, shards[w], n * esz))
+        if (overlap(theta_tilde_f32, n * 4, shards[w], ext) ||
+            overlap(theta_tilde_bf16, n * 2, shards[w], ext))
             return ACCO_ERR_ALIAS;
     int64_t new_total = 0;
     if (int rc = sum_counts(counts, workers, 0, &new_total)) return rc;
@@ -812,8 +860,8 @@ ACCO_API int acco_reduce_estimate_step(const float* theta, const float* m, const
         hipStream_t       s  = static_cast<hipStream_t>(stream);
         const AdamScalars sc = fold(*hp, step, new_total);
         rc = dtype == ACCO_BF16
-                 ? launch_reduce_estimate<true>(theta, m, v, gsum, L, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
-                 : launch_reduce_estimate<false>(theta, m, v, gsum, L, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
+                 ? launch_reduce_estimate<true>(theta, m, v, gsum, L, SL, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
+                 : launch_reduce_estimate<false>(theta, m, v, gsum, L, SL, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
     }
     if (rc == ACCO_OK) *total = new_total;
     return rc;
@@ -823,19 +871,21 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
                                      const void* const* shards, int workers, int dtype,
                                      const int64_t* counts, int64_t* total, uint16_t* theta_bf16,
                                      int64_t n, const acco_adamw_t* hp, int64_t* step,
-                                     const acco_layout_t* state_layout, void* stream)
+                                     const acco_layout_t* state_layout,
+                                     const acco_layout_t* shard_layout, void* stream)
 {
     if (int rc = check_n(n)) return rc;
     if (shards == nullptr || counts == nullptr || total == nullptr || step == nullptr)
         return ACCO_ERR_NULL;
-    StateLayout L;
+    StateLayout L, SL;
     if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = parse_shard_layout(shard_layout, dtype, &SL)) return rc;
     if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
     const void* st[4] = {theta, m, v, gsum};
-    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L)) return rc;
-    const int64_t esz = dtype == ACCO_BF16 ? 2 : 4;
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L, SL)) return rc;
+    const int64_t ext = state_extent(SL, n, dtype == ACCO_BF16 ? 2 : 4);
     for (int w = 0; w < workers; ++w)
-        if (overlap(theta_bf16, n * 2, shards[w], n * esz)) return ACCO_ERR_ALIAS;
+        if (overlap(theta_bf16, n * 2, shards[w], ext)) return ACCO_ERR_ALIAS;
     int64_t new_total = 0;
     if (int rc = sum_counts(counts, workers, *total, &new_total)) return rc;
     if (int rc = check_hyper(hp, *step, new_total)) return rc;
@@ -845,8 +895,8 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
         hipStream_t       s  = static_cast<hipStream_t>(stream);
         const AdamScalars sc = fold(*hp, *step, new_total);
         rc = dtype == ACCO_BF16
-                 ? launch_reduce_commit<true>(theta, m, v, gsum, L, shards, workers, theta_bf16, n, sc, s)
-                 : launch_reduce_commit<false>(theta, m, v, gsum, L, shards, workers, theta_bf16, n, sc, s);
+                 ? launch_reduce_commit<true>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s)
+                 : launch_reduce_commit<false>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s);
     }
     if (rc == ACCO_OK) {
         *total = new_total;
@@ -984,7 +1034,7 @@ ACCO_API const char* acco_status_string(int status)
 
 ACCO_API int acco_version(void)
 {
-    return 300;  // 0.3.0
+    return 400;  // 0.4.0
 }
 
 ACCO_API void acco_reset_launch_settings(void)

@@ -154,7 +154,8 @@ __device__ __forceinline__ void st(T* p, T x)
 // Op supplies: kElems (elements per vector: 4, or 8 for all-bf16 kernels); struct In;
 //              In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
 //              void scalar(int64_t elem) const;
-//              static Op make(const BatchPtrs&, int worker)   (accumulation Ops only).
+//              struct Shared; static Op make(const BatchPtrs&, int worker, const Shared&)
+//              (accumulation Ops only).
 
 // Pointer table of a batched launch: a, b, c are the (up to) three arrays of the Op, one
 // entry per worker.
@@ -173,10 +174,16 @@ struct Single {
 
 template <class O>
 struct Batch {
-    typedef O Op;
-    BatchPtrs tab;
-    __device__ __forceinline__ O get(unsigned worker) const { return O::make(tab, (int)worker); }
+    typedef O          Op;
+    BatchPtrs          tab;
+    typename O::Shared shared;   // what all workers' Ops have in common (e.g. the output layout)
+    __device__ __forceinline__ O get(unsigned worker) const
+    {
+        return O::make(tab, (int)worker, shared);
+    }
 };
+
+struct NoShared {};
 
 template <int U, class Src>
 __global__ void __launch_bounds__(kMaxThreads) stream_kernel(const Src src, const int64_t nvec,
@@ -228,7 +235,8 @@ struct AccumulateOp {
     static constexpr int kElems = 4;
     float*          acc;
     const uint16_t* grad;
-    static __device__ __forceinline__ AccumulateOp make(const BatchPtrs& t, int w)
+    typedef NoShared Shared;
+    static __device__ __forceinline__ AccumulateOp make(const BatchPtrs& t, int w, const Shared&)
     {
         return AccumulateOp{static_cast<float*>(t.a[w]), static_cast<const uint16_t*>(t.b[w])};
     }
@@ -256,19 +264,23 @@ struct AccumulateOp {
 };
 
 // Last micro-batch of an accumulation fused with the publish: comm = bf16(acc + grad)
-// (INIT: comm = bf16(grad)).  KEEP also stores the fp32 sum back to acc.
-template <bool INIT, bool KEEP>
+// (INIT: comm = bf16(grad)).  KEEP also stores the fp32 sum back to acc.  OB: comm has a
+// blocked layout (the workers' communication buffers interleaved block by block in one buffer).
+template <bool INIT, bool KEEP, bool OB = false>
 struct AccumulatePublishOp {
     static constexpr int kElems = 4;
     float*          acc;
     const uint16_t* grad;
     uint16_t*       comm;
+    StateAddr<OB>   oat;
+    typedef StateAddr<OB> Shared;
     // batched form: the accumulator is only read (KEEP is not offered there)
-    static __device__ __forceinline__ AccumulatePublishOp make(const BatchPtrs& t, int w)
+    static __device__ __forceinline__ AccumulatePublishOp make(const BatchPtrs& t, int w,
+                                                               const Shared& sh)
     {
         return AccumulatePublishOp{const_cast<float*>(static_cast<const float*>(t.c[w])),
                                    static_cast<const uint16_t*>(t.b[w]),
-                                   static_cast<uint16_t*>(t.a[w])};
+                                   static_cast<uint16_t*>(t.a[w]), sh};
     }
     struct In {
         f4 a;
@@ -286,14 +298,14 @@ struct AccumulatePublishOp {
         const f4 g = unpack_bf16x4(in.g);
         const f4 s = INIT ? g : in.a + g;
         if (KEEP) st(reinterpret_cast<f4*>(acc) + i, s);
-        st(reinterpret_cast<u2*>(comm) + i, pack_bf16x4(s));
+        st(reinterpret_cast<u2*>(comm) + oat.vec(i), pack_bf16x4(s));
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
         const float g = __uint_as_float((uint32_t)grad[j] << 16);
         const float s = INIT ? g : acc[j] + g;
         if (KEEP) acc[j] = s;
-        comm[j] = (uint16_t)to_bf16_bits(s);
+        comm[oat.elem(j)] = (uint16_t)to_bf16_bits(s);
     }
 };
 
@@ -311,15 +323,18 @@ __device__ __forceinline__ uint32_t quiet_bf16x2(uint32_t p)
     return p | lo | hi;
 }
 
-// stash = grad, or (QUIET) comm = bf16(float(grad)) for a one-micro-batch accumulation
-template <bool QUIET>
+// stash = grad, or (QUIET) comm = bf16(float(grad)) for a one-micro-batch accumulation.
+// An 8-element vector is two consecutive 4-element vectors of the (possibly blocked) output.
+template <bool QUIET, bool OB = false>
 struct StashOp {
     static constexpr int kElems = 8;
     uint16_t*            dst;
     const uint16_t*      src;
-    static __device__ __forceinline__ StashOp make(const BatchPtrs& t, int w)
+    StateAddr<OB>        oat;
+    typedef StateAddr<OB> Shared;
+    static __device__ __forceinline__ StashOp make(const BatchPtrs& t, int w, const Shared& sh)
     {
-        return StashOp{static_cast<uint16_t*>(t.a[w]), static_cast<const uint16_t*>(t.b[w])};
+        return StashOp{static_cast<uint16_t*>(t.a[w]), static_cast<const uint16_t*>(t.b[w]), sh};
     }
     struct In {
         u4 x;
@@ -334,12 +349,12 @@ struct StashOp {
     {
         u4 x = in.x;
         if (QUIET) x = (u4){quiet_bf16x2(x.x), quiet_bf16x2(x.y), quiet_bf16x2(x.z), quiet_bf16x2(x.w)};
-        st(reinterpret_cast<u4*>(dst) + i, x);
+        st(reinterpret_cast<u4*>(reinterpret_cast<u2*>(dst) + oat.vec(2 * i)), x);
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
         const uint32_t h = src[j];
-        dst[j]           = (uint16_t)(QUIET ? (quiet_bf16x2(h) & 0xFFFFu) : h);
+        dst[oat.elem(j)] = (uint16_t)(QUIET ? (quiet_bf16x2(h) & 0xFFFFu) : h);
     }
 };
 
@@ -349,7 +364,8 @@ struct SecondOp {
     float*               acc;
     const uint16_t*      stash;
     const uint16_t*      grad;
-    static __device__ __forceinline__ SecondOp make(const BatchPtrs& t, int w)
+    typedef NoShared Shared;
+    static __device__ __forceinline__ SecondOp make(const BatchPtrs& t, int w, const Shared&)
     {
         return SecondOp{static_cast<float*>(t.a[w]), static_cast<const uint16_t*>(t.c[w]),
                         static_cast<const uint16_t*>(t.b[w])};
@@ -375,15 +391,19 @@ struct SecondOp {
 };
 
 // second and last micro-batch fused with the publish: comm = bf16(float(stash) + float(grad))
+template <bool OB = false>
 struct SecondPublishOp {
     static constexpr int kElems = 8;
     uint16_t*            comm;
     const uint16_t*      stash;
     const uint16_t*      grad;
-    static __device__ __forceinline__ SecondPublishOp make(const BatchPtrs& t, int w)
+    StateAddr<OB>        oat;
+    typedef StateAddr<OB> Shared;
+    static __device__ __forceinline__ SecondPublishOp make(const BatchPtrs& t, int w,
+                                                           const Shared& sh)
     {
         return SecondPublishOp{static_cast<uint16_t*>(t.a[w]), static_cast<const uint16_t*>(t.c[w]),
-                               static_cast<const uint16_t*>(t.b[w])};
+                               static_cast<const uint16_t*>(t.b[w]), sh};
     }
     struct In {
         u4 s, g;
@@ -399,24 +419,28 @@ struct SecondPublishOp {
     {
         const u2 lo = pack_bf16x4(unpack_bf16x4((u2){in.s.x, in.s.y}) + unpack_bf16x4((u2){in.g.x, in.g.y}));
         const u2 hi = pack_bf16x4(unpack_bf16x4((u2){in.s.z, in.s.w}) + unpack_bf16x4((u2){in.g.z, in.g.w}));
-        st(reinterpret_cast<u4*>(comm) + i, (u4){lo.x, lo.y, hi.x, hi.y});
+        st(reinterpret_cast<u4*>(reinterpret_cast<u2*>(comm) + oat.vec(2 * i)),
+           (u4){lo.x, lo.y, hi.x, hi.y});
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        comm[j] = (uint16_t)to_bf16_bits(__uint_as_float((uint32_t)stash[j] << 16) +
-                                         __uint_as_float((uint32_t)grad[j] << 16));
+        comm[oat.elem(j)] = (uint16_t)to_bf16_bits(__uint_as_float((uint32_t)stash[j] << 16) +
+                                                   __uint_as_float((uint32_t)grad[j] << 16));
     }
 };
 
 // ------------------------------------------------------------------ cast
 
+template <bool OB = false>
 struct CastOp {
     static constexpr int kElems = 4;
-    uint16_t*    out;
-    const float* src;
-    static __device__ __forceinline__ CastOp make(const BatchPtrs& t, int w)
+    uint16_t*     out;
+    const float*  src;
+    StateAddr<OB> oat;
+    typedef StateAddr<OB> Shared;
+    static __device__ __forceinline__ CastOp make(const BatchPtrs& t, int w, const Shared& sh)
     {
-        return CastOp{static_cast<uint16_t*>(t.a[w]), static_cast<const float*>(t.c[w])};
+        return CastOp{static_cast<uint16_t*>(t.a[w]), static_cast<const float*>(t.c[w]), sh};
     }
     struct In {
         f4 x;
@@ -429,11 +453,11 @@ struct CastOp {
     }
     __device__ __forceinline__ void apply(int64_t i, const In& in) const
     {
-        st(reinterpret_cast<u2*>(out) + i, pack_bf16x4(in.x));
+        st(reinterpret_cast<u2*>(out) + oat.vec(i), pack_bf16x4(in.x));
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        out[j] = (uint16_t)to_bf16_bits(src[j]);
+        out[oat.elem(j)] = (uint16_t)to_bf16_bits(src[j]);
     }
 };
 
@@ -444,14 +468,16 @@ struct ShardPtrs {
 };
 
 // Sum of up to WMAX worker shards per launch, ascending worker order.  ACC: start
-// from the value already in gsum, else from shard 0 as it is.
-template <int WMAX, bool BF16, bool ACC, bool BLOCKED>
+// from the value already in gsum, else from shard 0 as it is.  SB: the shards have a blocked
+// layout of their own (the workers' buffers interleaved block by block in one buffer).
+template <int WMAX, bool BF16, bool ACC, bool BLOCKED, bool SB = false>
 struct ReduceOp {
     static constexpr int kElems = 4;
     float*             gsum;
     ShardPtrs          shards;
     int                workers;  // 1 .. WMAX
-    StateAddr<BLOCKED> at;       // layout of gsum (the shards are always planar)
+    StateAddr<BLOCKED> at;       // layout of gsum
+    StateAddr<SB>      sat;      // layout of every shard
     struct In {
         f4 s;
         f4 x[BF16 ? 1 : WMAX];
@@ -465,9 +491,9 @@ struct ReduceOp {
         for (int w = 0; w < WMAX; ++w) {
             if (w < workers) {
                 if (BF16)
-                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + i);
+                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + sat.vec(i));
                 else
-                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + i);
+                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + sat.vec(i));
             }
         }
         return in;
@@ -486,12 +512,12 @@ struct ReduceOp {
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        const int64_t a = at.elem(j);
+        const int64_t a = at.elem(j), b = sat.elem(j);
         float         s = ACC ? gsum[a] : 0.0f;
         for (int w = 0; w < workers; ++w) {
             const float x =
-                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
-                     : static_cast<const float*>(shards.p[w])[j];
+                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
+                     : static_cast<const float*>(shards.p[w])[b];
             s = (!ACC && w == 0) ? x : s + x;
         }
         gsum[a] = s;
@@ -574,7 +600,7 @@ struct AdamOp {
 // the gradient sum is formed in registers (same order as ReduceOp), optionally stored to
 // gsum (stage 1 keeps it for stage 2), and consumed by the update in the same pass.
 template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16,
-          bool BLOCKED>
+          bool BLOCKED, bool SB = false>
 struct ReduceAdamOp {
     static constexpr int kElems = 4;
     const float*       theta;
@@ -590,6 +616,7 @@ struct ReduceAdamOp {
     uint16_t*          out_bf16;
     AdamScalars        s;
     StateAddr<BLOCKED> at;
+    StateAddr<SB>      sat;   // layout of every shard
     struct In {
         f4 t, m, v, g;
         f4 x[BF16 ? 1 : kReduceChunk];
@@ -607,9 +634,9 @@ struct ReduceAdamOp {
         for (int w = 0; w < kReduceChunk; ++w) {
             if (w < workers) {
                 if (BF16)
-                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + i);
+                    in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + sat.vec(i));
                 else
-                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + i);
+                    in.x[w] = ld(reinterpret_cast<const f4*>(shards.p[w]) + sat.vec(i));
             }
         }
         return in;
@@ -638,12 +665,12 @@ struct ReduceAdamOp {
     }
     __device__ __forceinline__ void scalar(int64_t j) const
     {
-        const int64_t a = at.elem(j);
+        const int64_t a = at.elem(j), b = sat.elem(j);
         float         g = ACC ? gsum[a] : 0.0f;
         for (int w = 0; w < workers; ++w) {
             const float x =
-                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[j] << 16)
-                     : static_cast<const float*>(shards.p[w])[j];
+                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
+                     : static_cast<const float*>(shards.p[w])[b];
             g = (!ACC && w == 0) ? x : g + x;
         }
         if (WRITE_GSUM) gsum[a] = g;

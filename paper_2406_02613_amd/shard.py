@@ -31,7 +31,11 @@ Options that give the same values with fewer bytes over HBM:
                  (acco_reduce_estimate_step / acco_reduce_commit_step);
   batched        workers that are at the same step of their accumulation share one launch
                  (acco_accumulate_batch) when their gradients are handed over together
-                 (add_microbatches / add_microbatch_rows).
+                 (add_microbatches / add_microbatch_rows);
+  interleaved_comm  the W bf16 communication buffers are the interleaved blocks of one buffer
+                 (state.InterleavedShards) instead of W separate ones: same values, placed so
+                 that the publish and reduce kernels stream them faster.  Every write to them
+                 then goes through acco_accumulate_batch, which takes the layout.
 """
 from __future__ import annotations
 
@@ -41,7 +45,8 @@ from . import binding as B
 
 # names under which the calls of a round are reported to ShardOwner.trace, one per kernel
 # variant (they differ in the bytes they move): see _label()
-OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first")
+OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first",
+           "interleaved_comm")
 
 
 class ShardOwner:
@@ -50,7 +55,8 @@ class ShardOwner:
                  fused_reduce: bool = False, blocked_state: bool = False,
                  block_elems: int = 8192, bf16_stash: bool = False,
                  bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False,
-                 batched: bool = False):
+                 batched: bool = False, interleaved_comm: bool = False,
+                 comm_block_elems: int = 16384):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -84,8 +90,14 @@ class ShardOwner:
             self.gsum = torch.empty(n, dtype=f32, device=dev)
         self.acc: List = ([] if bf16_accumulate else
                           [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)])
-        self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
-                           if comm_bf16 else [])
+        # the communication buffers: W separate ones and / or the interleaved blocks of one
+        # buffer, each allocated when first selected
+        self._dev, self._comm_block = dev, int(comm_block_elems)
+        self._comm_planar: Optional[List] = None
+        self._comm_slab = None
+        self.interleaved_comm = False
+        self.comm: List = []
+        self._select_comm(bool(interleaved_comm))
         self._own_stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
                                  if self.bf16_stash and not self.adopt_first else [None] * workers)
         self.stash: List = list(self._own_stash)
@@ -102,6 +114,28 @@ class ShardOwner:
         self._published = [False] * workers                   # comm[w] already written this stage
         self._stashed = [False] * workers                     # the sum so far sits in stash[w]
 
+    def _select_comm(self, interleaved: bool) -> None:
+        if not self.comm_bf16:
+            self.interleaved_comm, self.comm = False, []
+            return
+        if interleaved and self.bf16_accumulate:
+            raise ValueError("bf16 running sums are updated in place: planar buffers only")
+        self.interleaved_comm = interleaved
+        if interleaved:
+            if self._comm_slab is None:
+                from .state import InterleavedShards
+                self._comm_slab = InterleavedShards(self.n, self.W, self._comm_block, self._dev)
+            self.comm = list(self._comm_slab.shards)
+        else:
+            if self._comm_planar is None:
+                self._comm_planar = [self.torch.empty(self.n, dtype=self.torch.bfloat16,
+                                                      device=self._dev) for _ in range(self.W)]
+            self.comm = self._comm_planar
+
+    def comm_planar(self, w: int):
+        """Worker w's published buffer as a planar tensor of n elements (a copy if interleaved)."""
+        return self._comm_slab.planar(w) if self.interleaved_comm else self.comm[w]
+
     def _call(self, label: str, fn, *args, **kw):
         if self.trace is None:
             return fn(*args, **kw)
@@ -117,7 +151,10 @@ class ShardOwner:
         for k, val in opts.items():
             if k not in OPTIONS:
                 raise ValueError(f"unknown option {k!r}")
-            setattr(self, k, bool(val))
+            if k == "interleaved_comm":
+                self._select_comm(bool(val))
+            else:
+                setattr(self, k, bool(val))
         self.fused_publish = self.fused_publish and self.comm_bf16
         self.bf16_stash = self.bf16_stash and self.comm_bf16 and not self.bf16_accumulate
         self.adopt_first = self.adopt_first and self.bf16_stash
@@ -183,8 +220,8 @@ class ShardOwner:
                 for w, g in zip(workers, grads):
                     if g.data_ptr() == self.stash[w].data_ptr():
                         raise ValueError("the buffer adopted as the first micro-batch was reused")
-            if self.batched and len(workers) > 1:
-                op, use_acc, out, use_stash = self._BATCH[step]
+            op, use_acc, out, use_stash = self._BATCH[step]
+            if (self.batched and len(workers) > 1) or (self.interleaved_comm and out == "comm"):
                 cols = {}
                 if use_acc:
                     cols["acc"] = [self.acc[w] for w in workers]
@@ -270,7 +307,7 @@ class ShardOwner:
         summed = [w for w in todo if not self._stashed[w]]
         for ws, label, op, src in ((stashed, "accumulate_first_publish", B.BATCH_FIRST_PUBLISH,
                                     "grad_bf16"), (summed, "cast", B.BATCH_PUBLISH, "acc")):
-            if self.batched and len(ws) > 1:
+            if ws and ((self.batched and len(ws) > 1) or self.interleaved_comm):
                 col = [self.stash[w] if src == "grad_bf16" else self.acc[w] for w in ws]
                 self._call(f"{label}*{len(ws)}", B.acco_accumulate_batch, op, self.n,
                            out_bf16=[self.comm[w] for w in ws], **{src: col})

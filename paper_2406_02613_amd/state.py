@@ -36,3 +36,31 @@ class BlockedState:
     def planar(self, name: str):
         """A planar copy (n elements) of component ``name``."""
         return getattr(self, name).reshape(-1)[:self.n].clone()
+
+
+DEFAULT_COMM_BLOCK_ELEMS = 16384  # 32 KiB of bf16 per worker and block: the fastest of 4 Ki .. 64 Ki
+
+
+class InterleavedShards:
+    """The W workers' bf16 communication buffers interleaved block by block in one buffer of
+    shape (blocks, W, block_elems): ``shard(w)`` is the (blocks, block_elems) view of worker w
+    with strides (W * block_elems, 1), which acco_accumulate_batch writes (out_layout) and the
+    reduction entry points read (shard_layout); the binding derives the layout from the strides.
+    Allocation only - no arithmetic."""
+
+    def __init__(self, n: int, workers: int, block_elems: int = DEFAULT_COMM_BLOCK_ELEMS,
+                 device="cuda"):
+        import torch
+        if block_elems < 8 or block_elems & (block_elems - 1):
+            raise ValueError("block_elems must be a power of two >= 8")
+        self.n, self.W, self.block = int(n), int(workers), int(block_elems)
+        self.blocks = (self.n + self.block - 1) // self.block
+        self.buf = torch.zeros(self.blocks, self.W, self.block, dtype=torch.bfloat16, device=device)
+        self.shards = [self.buf[:, w, :] for w in range(self.W)]
+
+    def shard(self, w: int):
+        return self.shards[w]
+
+    def planar(self, w: int):
+        """A planar copy (n elements) of worker w's buffer."""
+        return self.shards[w].reshape(-1)[:self.n].clone()

@@ -81,29 +81,29 @@ def test_reduce_validation_and_count_totals():
     cnt = (ctypes.c_int64 * 2)(3, 4)
     tot = ctypes.c_int64(100)
     r = L.acco_reduce_shards
-    assert r(NONE, s2, 2, 0, 4, 0, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_NULL
-    assert r(vp(A), NONE, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_NULL
-    assert r(vp(A), s2, 0, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_SIZE
-    assert r(vp(A), s2, 65, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_SIZE
-    assert r(vp(A), s2, 2, 7, 0, 0, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_ARG
-    assert r(vp(A), s2, 2, 0, 0, 3, cnt, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_ARG
-    assert r(vp(A), s2, 2, 0, 0, 0, cnt, NONE, NONE, NONE) == B.ACCO_ERR_NULL      # counts w/o total
-    assert r(vp(A), s2, 2, 0, 0, 0, NONE, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_NULL
-    assert r(vp(A), _shards(Bp, 0), 2, 0, 4, 0, NONE, NONE, NONE, NONE) == B.ACCO_ERR_NULL
-    assert r(vp(A), _shards(Bp, C + 2), 2, 0, 0, 0, NONE, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
-    assert r(vp(A), _shards(Bp, A), 2, 0, 8, 0, NONE, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert r(NONE, s2, 2, 0, 4, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), NONE, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), s2, 0, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert r(vp(A), s2, 65, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert r(vp(A), s2, 2, 7, 0, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 3, cnt, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 0, cnt, NONE, NONE, NONE, NONE) == B.ACCO_ERR_NULL      # counts w/o total
+    assert r(vp(A), s2, 2, 0, 0, 0, NONE, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), _shards(Bp, 0), 2, 0, 4, 0, NONE, NONE, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), _shards(Bp, C + 2), 2, 0, 0, 0, NONE, NONE, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert r(vp(A), _shards(Bp, A), 2, 0, 8, 0, NONE, NONE, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
     neg = (ctypes.c_int64 * 2)(3, -1)
-    assert r(vp(A), s2, 2, 0, 0, 0, neg, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 0, neg, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_ARG
     big = (ctypes.c_int64 * 2)(2 ** 62, 2 ** 62)
-    assert r(vp(A), s2, 2, 0, 0, 0, big, ctypes.byref(tot), NONE, NONE) == B.ACCO_ERR_ARG
+    assert r(vp(A), s2, 2, 0, 0, 0, big, ctypes.byref(tot), NONE, NONE, NONE) == B.ACCO_ERR_ARG
     assert tot.value == 100
     # stage 1: total = sum(counts); stage 2: total += sum(counts)
-    assert r(vp(A), s2, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE) == 0 and tot.value == 7
+    assert r(vp(A), s2, 2, 0, 0, 0, cnt, ctypes.byref(tot), NONE, NONE, NONE) == 0 and tot.value == 7
     cnt2 = (ctypes.c_int64 * 2)(5, 6)
-    assert r(vp(A), s2, 2, 1, 0, 1, cnt2, ctypes.byref(tot), NONE, NONE) == 0 and tot.value == 18
+    assert r(vp(A), s2, 2, 1, 0, 1, cnt2, ctypes.byref(tot), NONE, NONE, NONE) == 0 and tot.value == 18
     # 64 workers are accepted
     many = _shards(*[Bp + 0x1000 * k for k in range(64)])
-    assert r(vp(A), many, 64, 0, 0, 0, NONE, NONE, NONE, NONE) == 0
+    assert r(vp(A), many, 64, 0, 0, 0, NONE, NONE, NONE, NONE, NONE) == 0
 
 
 GOOD = B.make_hyper(6e-4, 0.9, 0.95, 1e-8, 0.1)
@@ -243,32 +243,32 @@ def test_fused_reduce_steps_validation_and_counters():
     est, com = L.acco_reduce_estimate_step, L.acco_reduce_commit_step
     G, H = 0x70000, 0x80000
     # estimate
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), NONE, 0, hp, 0, NONE, NONE) == B.ACCO_ERR_NULL
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, NONE, vp(G), NONE, 0, hp, 0, NONE, NONE) == B.ACCO_ERR_NULL
-    assert est(vp(A), vp(Bp), vp(C), NONE, s2, 2, 0, cnt, tr, vp(G), NONE, 4, hp, 0, NONE, NONE) == B.ACCO_ERR_NULL
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, NONE, NONE, 4, hp, 0, NONE, NONE) == B.ACCO_ERR_NULL
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 0, 0, cnt, tr, vp(G), NONE, 0, hp, 0, NONE, NONE) == B.ACCO_ERR_SIZE
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 3, cnt, tr, vp(G), NONE, 0, hp, 0, NONE, NONE) == B.ACCO_ERR_ARG
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), NONE, 0, hp, -1, NONE, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), NONE, 0, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, NONE, vp(G), NONE, 0, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), NONE, s2, 2, 0, cnt, tr, vp(G), NONE, 4, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, NONE, NONE, 4, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 0, 0, cnt, tr, vp(G), NONE, 0, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 3, cnt, tr, vp(G), NONE, 0, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), NONE, 0, hp, -1, NONE, NONE, NONE) == B.ACCO_ERR_ARG
     zero = (ctypes.c_int64 * 2)(0, 0)
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, zero, tr, vp(G), NONE, 0, hp, 0, NONE, NONE) == B.ACCO_ERR_ARG
-    assert est(vp(A), vp(Bp), vp(C), vp(A), s2, 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), NONE, 8, hp, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert est(vp(A), vp(Bp), vp(C), vp(D), _shards(E, D), 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, zero, tr, vp(G), NONE, 0, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(A), vp(Bp), vp(C), vp(A), s2, 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), NONE, 8, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert est(vp(A), vp(Bp), vp(C), vp(D), _shards(E, D), 2, 0, cnt, tr, vp(G), NONE, 8, hp, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
     assert tot.value == 50
-    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), vp(H), 0, hp, 0, NONE, NONE) == 0
+    assert est(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), vp(H), 0, hp, 0, NONE, NONE, NONE) == 0
     assert tot.value == 7                     # stage 1: the total starts afresh
     # commit
     step = ctypes.c_int64(9)
     sr = ctypes.byref(step)
-    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, NONE, NONE, NONE) == B.ACCO_ERR_NULL
-    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), 0, hp, sr, NONE, NONE) == B.ACCO_ERR_NULL
-    assert com(vp(A), vp(Bp), vp(A), vp(D), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert com(vp(A), vp(Bp), vp(C), vp(D), _shards(E, Bp), 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), 8, hp, sr, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert com(vp(A), vp(Bp), vp(C), vp(D + 4), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, NONE, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, tr, vp(G), 0, hp, sr, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert com(vp(A), vp(Bp), vp(A), vp(D), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D), _shards(E, Bp), 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(E), 8, hp, sr, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(A), vp(Bp), vp(C), vp(D + 4), s2, 2, 0, cnt, tr, vp(G), 8, hp, sr, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
     assert tot.value == 7 and step.value == 9
-    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, sr, NONE, NONE) == 0
+    assert com(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, cnt, tr, vp(G), 0, hp, sr, NONE, NONE, NONE) == 0
     assert tot.value == 14 and step.value == 10      # stage 2 adds onto the stage-1 total
 
 
@@ -337,8 +337,8 @@ def test_state_layout_validation_and_interleaved_aliasing_rules():
                NONE) == 0
     # reduce accepts a layout for gsum
     s2 = _shards(0x8000000, 0x9000000)
-    assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 4 * blk), NONE) == 0
-    assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 3), NONE) == B.ACCO_ERR_ARG
+    assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 4 * blk), NONE, NONE) == 0
+    assert L.acco_reduce_shards(vp(g), s2, 2, 0, 0, 0, NONE, NONE, lay(blk, 3), NONE, NONE) == B.ACCO_ERR_ARG
 
 
 def test_cosine_schedule_closed_forms_and_oracle():
@@ -435,44 +435,109 @@ def test_accumulate_batch_validation_and_counters():
     cnt = (ctypes.c_int64 * 2)(5, 7)
     ops = B
     # unknown operation, worker count out of range, bad n
-    assert f(9, 2, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG
-    assert f(-1, 2, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG
-    assert f(ops.BATCH_ACCUMULATE, 0, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_SIZE
-    assert f(ops.BATCH_ACCUMULATE, 65, acc, out, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_SIZE
-    assert f(ops.BATCH_ACCUMULATE, 2, acc, out, stash, grad, -1, cnt, NONE) == B.ACCO_ERR_SIZE
+    assert f(9, 2, acc, out, stash, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_ARG
+    assert f(-1, 2, acc, out, stash, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_ARG
+    assert f(ops.BATCH_ACCUMULATE, 0, acc, out, stash, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert f(ops.BATCH_ACCUMULATE, 65, acc, out, stash, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, out, stash, grad, -1, cnt, NONE, NONE) == B.ACCO_ERR_SIZE
     # a column the operation uses is missing; columns it does not use may be NULL
-    assert f(ops.BATCH_ACCUMULATE, 2, NONE, NONE, NONE, grad, 0, cnt, NONE) == B.ACCO_ERR_NULL
-    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, NONE, 0, cnt, NONE) == B.ACCO_ERR_NULL
-    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, NONE, grad, 0, cnt, NONE) == B.ACCO_ERR_NULL
-    assert f(ops.BATCH_PUBLISH, 2, acc, NONE, NONE, NONE, 0, NONE, NONE) == B.ACCO_ERR_NULL
-    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, _shards(0x70000, 0), 4, NONE, NONE) == B.ACCO_ERR_NULL
-    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, Bp + 4), NONE, NONE, grad, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert f(ops.BATCH_ACCUMULATE, 2, NONE, NONE, NONE, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, NONE, 0, cnt, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, NONE, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_PUBLISH, 2, acc, NONE, NONE, NONE, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, _shards(0x70000, 0), 4, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, Bp + 4), NONE, NONE, grad, 0, NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
     # a written buffer meets another buffer of the call: same worker, or another worker's
-    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, A + 16), NONE, NONE, grad, 64, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, C), NONE, grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, 0x70000), NONE, grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
-    assert f(ops.BATCH_SECOND, 2, acc, NONE, _shards(E, A), grad, 8, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_ACCUMULATE, 2, _shards(A, A + 16), NONE, NONE, grad, 64, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, C), NONE, grad, 8, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_FIRST, 2, NONE, _shards(C, 0x70000), NONE, grad, 8, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert f(ops.BATCH_SECOND, 2, acc, NONE, _shards(E, A), grad, 8, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
     # read-only buffers may be shared between workers
-    assert f(ops.BATCH_FIRST, 2, NONE, out, NONE, _shards(0x70000, 0x70000), 0, NONE, NONE) == 0
+    assert f(ops.BATCH_FIRST, 2, NONE, out, NONE, _shards(0x70000, 0x70000), 0, NONE, NONE, NONE) == 0
     # counters: errors leave them alone; each operation's rule
     assert (cnt[0], cnt[1]) == (5, 7)
-    assert f(ops.BATCH_SECOND, 2, acc, NONE, stash, grad, 0, cnt, NONE) == B.ACCO_ERR_ARG   # not 1
-    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, cnt, NONE) == 0
+    assert f(ops.BATCH_SECOND, 2, acc, NONE, stash, grad, 0, cnt, NONE, NONE) == B.ACCO_ERR_ARG   # not 1
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, cnt, NONE, NONE) == 0
     assert (cnt[0], cnt[1]) == (6, 8)
-    assert f(ops.BATCH_ACCUMULATE_PUBLISH, 2, acc, out, NONE, grad, 0, cnt, NONE) == 0
+    assert f(ops.BATCH_ACCUMULATE_PUBLISH, 2, acc, out, NONE, grad, 0, cnt, NONE, NONE) == 0
     assert (cnt[0], cnt[1]) == (7, 9)
-    assert f(ops.BATCH_RUNNING_BF16, 2, NONE, out, NONE, grad, 0, cnt, NONE) == 0
+    assert f(ops.BATCH_RUNNING_BF16, 2, NONE, out, NONE, grad, 0, cnt, NONE, NONE) == 0
     assert (cnt[0], cnt[1]) == (8, 10)
-    assert f(ops.BATCH_PUBLISH, 2, acc, out, NONE, NONE, 0, cnt, NONE) == 0
+    assert f(ops.BATCH_PUBLISH, 2, acc, out, NONE, NONE, 0, cnt, NONE, NONE) == 0
     assert (cnt[0], cnt[1]) == (8, 10)
     for op in (ops.BATCH_ACCUMULATE_INIT, ops.BATCH_FIRST, ops.BATCH_FIRST_PUBLISH):
         cnt[0], cnt[1] = 3, 4
-        assert f(op, 2, acc, out, NONE, grad, 0, cnt, NONE) == 0 and (cnt[0], cnt[1]) == (1, 1)
-    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, stash, grad, 0, cnt, NONE) == 0
+        assert f(op, 2, acc, out, NONE, grad, 0, cnt, NONE, NONE) == 0 and (cnt[0], cnt[1]) == (1, 1)
+    assert f(ops.BATCH_SECOND_PUBLISH, 2, NONE, out, stash, grad, 0, cnt, NONE, NONE) == 0
     assert (cnt[0], cnt[1]) == (2, 2)
     neg = (ctypes.c_int64 * 2)(1, -1)
-    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, neg, NONE) == B.ACCO_ERR_ARG
+    assert f(ops.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, neg, NONE, NONE) == B.ACCO_ERR_ARG
     # 64 workers (four launches of 16) are accepted
     many = _shards(*[0x100000 + 0x1000 * k for k in range(64)])
     gmany = _shards(*[0x900000 + 0x1000 * k for k in range(64)])
-    assert f(ops.BATCH_FIRST, 64, NONE, many, NONE, gmany, 0, NONE, NONE) == 0
+    assert f(ops.BATCH_FIRST, 64, NONE, many, NONE, gmany, 0, NONE, NONE, NONE) == 0
+
+
+def test_layouts_of_interleaved_communication_buffers():
+    """out_layout of acco_accumulate_batch and shard_layout of the reduction entry points: the
+    workers' bf16 buffers as the interleaved blocks of one buffer."""
+    L = B.lib()
+    f = L.acco_accumulate_batch
+
+    def lay(b, st):
+        return ctypes.byref(B.Layout(b, st))
+
+    blk, W, n = 64, 2, 1000
+    base = 0x4000000
+    out = _shards(base, base + 2 * blk)                       # worker w at base + w * blk bf16
+    grad = _shards(0x70000, 0x80000)
+    stash = _shards(0x90000, 0xA0000)
+    acc = _shards(0xB0000, 0xC0000)
+    il = lay(blk, W * blk)
+    # interleaved outputs overlap in extent but share no element: accepted, with every
+    # operation that writes out_bf16 ...
+    for op in (B.BATCH_FIRST, B.BATCH_FIRST_PUBLISH, B.BATCH_SECOND_PUBLISH,
+               B.BATCH_ACCUMULATE_PUBLISH, B.BATCH_PUBLISH):
+        cnt = (ctypes.c_int64 * 2)(1, 1)
+        assert f(op, 2, acc, out, stash, grad, 0, cnt, il, NONE) == 0, op
+    # ... the same pointers without the layout are overlapping planar buffers
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, grad, n, NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    # two workers on the same block slot, or half a block apart, do collide
+    assert f(B.BATCH_FIRST, 2, NONE, _shards(base, base), NONE, grad, n, NONE, il, NONE) == B.ACCO_ERR_ALIAS
+    assert f(B.BATCH_FIRST, 2, NONE, _shards(base, base + blk), NONE, grad, n, NONE, il, NONE) == \
+        B.ACCO_ERR_ALIAS
+    # an input inside the interleaved buffer's extent is refused
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, _shards(0x70000, base + 8 * blk), n, NONE, il,
+             NONE) == B.ACCO_ERR_ALIAS
+    # no layout where there is no output, nor for the in-place running sum, nor blocks < 8
+    assert f(B.BATCH_ACCUMULATE, 2, acc, NONE, NONE, grad, 0, NONE, il, NONE) == B.ACCO_ERR_ARG
+    assert f(B.BATCH_RUNNING_BF16, 2, NONE, out, NONE, grad, 0, NONE, il, NONE) == B.ACCO_ERR_ARG
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, grad, 0, NONE, lay(4, 8), NONE) == B.ACCO_ERR_ARG
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, grad, 0, NONE, lay(48, 96), NONE) == B.ACCO_ERR_ARG
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, grad, 0, NONE, lay(blk, blk - 8), NONE) == B.ACCO_ERR_ARG
+    assert f(B.BATCH_FIRST, 2, NONE, out, NONE, grad, 0, NONE, lay(0, 0), NONE) == 0     # planar
+
+    # the reduction side
+    hp = ctypes.byref(GOOD)
+    th, m, v, g, o16 = (0x10000000 * k for k in range(1, 6))
+    cnt = (ctypes.c_int64 * 2)(3, 4)
+    tot, step = ctypes.c_int64(0), ctypes.c_int64(0)
+    tr, sr = ctypes.byref(tot), ctypes.byref(step)
+    red, est, com = L.acco_reduce_shards, L.acco_reduce_estimate_step, L.acco_reduce_commit_step
+    assert red(vp(g), out, 2, 0, 0, 0, cnt, tr, NONE, il, NONE) == 0
+    assert est(vp(th), vp(m), vp(v), vp(g), out, 2, 0, cnt, tr, NONE, vp(o16), 0, hp, 0, NONE, il,
+               NONE) == 0
+    assert com(vp(th), vp(m), vp(v), vp(g), out, 2, 0, cnt, tr, vp(o16), 0, hp, sr, NONE, il,
+               NONE) == 0
+    assert tot.value == 14 and step.value == 1      # n = 0 throughout: nothing is launched
+    # a blocked layout is for bf16 shards only
+    assert red(vp(g), out, 2, 1, 0, 0, cnt, tr, NONE, il, NONE) == B.ACCO_ERR_ARG
+    assert est(vp(th), vp(m), vp(v), vp(g), out, 2, 1, cnt, tr, NONE, vp(o16), 0, hp, 0, NONE, il,
+               NONE) == B.ACCO_ERR_ARG
+    assert com(vp(th), vp(m), vp(v), vp(g), out, 2, 1, cnt, tr, vp(o16), 0, hp, sr, NONE, il,
+               NONE) == B.ACCO_ERR_ARG
+    # the interleaved buffer's whole extent counts against the state and the outputs
+    assert red(vp(base + 64), out, 2, 0, n, 0, cnt, tr, NONE, il, NONE) == B.ACCO_ERR_ALIAS
+    assert com(vp(th), vp(m), vp(v), vp(g), out, 2, 0, cnt, tr, vp(base + 16 * blk), n, hp, sr,
+               NONE, il, NONE) == B.ACCO_ERR_ALIAS
+    assert red(vp(g), out, 2, 0, 0, 0, cnt, tr, NONE, lay(blk, 3), NONE) == B.ACCO_ERR_ARG

@@ -940,6 +940,110 @@ def test_batched_accumulation_steps_equal_the_single_calls(acco, shape, W):
         assert torch.all(a[0] == 1.0)
 
 
+@pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 1, 0), (256, 2, 0), (512, 4, 0)])
+@pytest.mark.parametrize("block", [8, 64, 1024, 16384])
+@pytest.mark.parametrize("W", [1, 3, 8, 20])
+def test_interleaved_communication_buffers_give_the_same_bits(acco, shape, block, W):
+    """The W communication buffers as the interleaved blocks of one buffer: every operation that
+    publishes into them (out_layout) and every reduction that reads them (shard_layout) against
+    the same calls on W separate planar buffers and against the oracle; nothing outside the
+    buffers' n logical elements is written."""
+    Bn = acco.binding
+    for e in ("accumulate_publish", "stash", "second", "cast", "reduce", "reduce_estimate",
+              "reduce_commit"):
+        acco.set_launch_shape(e, *shape)
+    rng = np.random.default_rng(60 + W + block)
+    h = HYPERS[0]
+    ohp = oracle.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    ghp = acco.make_hyper(h["lr"], h["b1"], h["b2"], h["eps"], h["wd"])
+    for n in (0, 1, 7, 8, 9, block - 1, block, block + 1, 3 * block + 5, 70_001):
+        if n < 0 or (block == 16384 and n > 2 * block + 100 and n != 70_001):
+            continue
+        log("interleaved comm", shape, block, W, n)
+        g = [[_rand_bf16(rng, n, 2e-4) for _ in range(W)] for _ in range(3)]
+        d = [[bf16_tensor(x) for x in row] for row in g]
+        # oracle: sums after 1, 2, 3 micro-batches, their publishes, the reduced gradient
+        acc_h = [np.empty(n, np.float32) for _ in range(W)]
+        pubs = []
+        for k in range(3):
+            for w in range(W):
+                oracle.accumulate(acc_h[w], g[k][w], init=(k == 0))
+            pubs.append([oracle.cast(a) for a in acc_h])
+        acc2 = [np.empty(n, np.float32) for _ in range(W)]
+        for w in range(W):
+            oracle.accumulate(acc2[w], g[0][w], init=True)
+            oracle.accumulate(acc2[w], g[1][w], init=False)
+        slab = acco.InterleavedShards(n, W, block)
+        slab.buf.fill_(7.0)                                   # padding must never be touched
+        comm = slab.shards
+        stash = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(W)]
+        acc = [dev(a) for a in acc2]
+
+        def published(k):
+            return all(np.array_equal(bits_of(slab.planar(w)), pubs[k][w]) for w in range(W))
+
+        def padding_intact():
+            rem = n - (slab.blocks - 1) * block if slab.blocks else 0
+            return slab.blocks == 0 or rem == block or bool(torch.all(slab.buf[-1, :, rem:] == 7.0))
+
+        acco.acco_accumulate_batch(Bn.BATCH_FIRST_PUBLISH, n, out_bf16=comm, grad_bf16=d[0])
+        assert published(0) and padding_intact()
+        acco.acco_accumulate_batch(Bn.BATCH_FIRST, n, out_bf16=stash, grad_bf16=d[0])
+        acco.acco_accumulate_batch(Bn.BATCH_SECOND_PUBLISH, n, out_bf16=comm, stash_bf16=stash,
+                                   grad_bf16=d[1])
+        assert published(1) and padding_intact()
+        acco.acco_accumulate_batch(Bn.BATCH_ACCUMULATE_PUBLISH, n, acc=acc, out_bf16=comm,
+                                   grad_bf16=d[2])
+        assert published(2) and padding_intact()
+        acco.acco_accumulate_batch(Bn.BATCH_PUBLISH, n, acc=acc, out_bf16=comm)
+        assert published(1) and padding_intact()
+        # a stash may be interleaved too (FIRST keeps the raw bits)
+        slab2 = acco.InterleavedShards(n, W, block)
+        acco.acco_accumulate_batch(Bn.BATCH_FIRST, n, out_bf16=slab2.shards, grad_bf16=d[0])
+        assert all(np.array_equal(bits_of(slab2.planar(w)), g[0][w]) for w in range(W))
+        # the reductions over the interleaved buffers (comm holds the sums of two micro-batches)
+        planar = [bf16_tensor(pubs[1][w]) for w in range(W)]
+        counts = [2] * W
+        g1 = torch.empty(n, dtype=torch.float32, device="cuda")
+        g2 = torch.empty(n, dtype=torch.float32, device="cuda")
+        acco.acco_reduce_shards(g1, comm, False, counts, acco.Counter(0))
+        acco.acco_reduce_shards(g2, planar, False, counts, acco.Counter(0))
+        g_h = np.empty(n, np.float32)
+        oracle.reduce(g_h, pubs[1], accumulate_=False)
+        assert bit_mismatches(g1.cpu().numpy(), g_h) == 0 and torch.equal(g1.view(torch.int32), g2.view(torch.int32))
+        acco.acco_reduce_shards(g1, comm, True, counts, acco.Counter(0))
+        oracle.reduce(g_h, pubs[1], accumulate_=True)
+        assert bit_mismatches(g1.cpu().numpy(), g_h) == 0
+        theta, m, v, _ = _state(rng, n, "warm")
+        for blocked_state in (False, True):
+            if blocked_state:
+                st = acco.BlockedState(n, 64)
+                for name, arr in (("theta", theta), ("m", m), ("v", v)):
+                    st.load(name, dev(arr))
+                td, md, vd, gd = st.theta, st.m, st.v, st.gsum
+            else:
+                td, md, vd = dev(theta), dev(m), dev(v)
+                gd = torch.empty(n, dtype=torch.float32, device="cuda")
+            o16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            tot, step = acco.Counter(0), acco.Counter(4)
+            acco.acco_reduce_estimate_step(td, md, vd, gd, comm, counts, tot, ghp, step.value,
+                                           theta_tilde_bf16=o16, n=n)
+            g_h = np.empty(n, np.float32)
+            oracle.reduce(g_h, pubs[1], accumulate_=False)
+            _, e16 = oracle.estimate(theta, m, v, g_h, ohp, 5, 2 * W, want_f32=False, precision="f32")
+            assert np.array_equal(bits_of(o16), e16)
+            acco.acco_reduce_commit_step(td, md, vd, gd, comm, counts, tot, ghp, step,
+                                         theta_bf16=o16, n=n)
+            oracle.reduce(g_h, pubs[1], accumulate_=True)
+            t_h, m_h, v_h = theta.copy(), m.copy(), v.copy()
+            b16 = oracle.commit(t_h, m_h, v_h, g_h, ohp, 5, 4 * W, precision="f32")
+            assert tot.value == 4 * W and step.value == 5
+            got_t = st.planar("theta") if blocked_state else td
+            assert bit_mismatches(got_t.cpu().numpy(), t_h) == 0
+            assert np.array_equal(bits_of(o16), b16)
+        assert padding_intact()
+
+
 def test_resident_wave_bounds_change_no_bits(acco):
     """The bound on resident wavefronts (an LDS reservation) is a scheduling knob only."""
     rng = np.random.default_rng(43)

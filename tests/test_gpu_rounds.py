@@ -32,7 +32,8 @@ def gpu_hyper(A, w):
 
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
-                 bf16_acc=False, schedules=None, adopt=False, batched=False):
+                 bf16_acc=False, schedules=None, adopt=False, batched=False, interleaved=False,
+                 comm_block=16384):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -43,7 +44,8 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
                          fused_reduce=fused_reduce, blocked_state=blocked, bf16_stash=stash,
                          bf16_accumulate=bf16_acc,
                          lr_schedule=None if schedules is None else schedules[0],
-                         adopt_first=adopt, batched=batched)
+                         adopt_first=adopt, batched=batched, interleaved_comm=interleaved,
+                         comm_block_elems=comm_block)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -210,6 +212,37 @@ def test_one_launch_for_all_workers_changes_no_bits():
     run_workload(wide, batched=True)
 
 
+def test_interleaved_communication_buffers_change_no_bits():
+    """interleaved_comm: the W communication buffers are the interleaved blocks of one buffer."""
+    tiny = synth.WORKLOADS["tiny"]
+    run_workload(tiny, interleaved=True)                           # base entry points otherwise
+    run_workload(tiny, interleaved=True, batched=True, stash=True, fused_publish=True,
+                 fused_reduce=True, blocked=True)
+    w = synth.Workload(name="ragged", n=300_000 + 37, workers=5, rounds=3, grad_std=1e-3,
+                       k_range=(2, 8), zero_frac=0.05, zero_run=64, outlier_frac=1e-2, seed=4)
+    run_workload(w, interleaved=True)
+    run_workload(w, interleaved=True, comm_block=8, fused_publish=True)
+    run_workload(w, interleaved=True, comm_block=4096, batched=True, stash=True)
+    run_workload(w, interleaved=True, batched=True, stash=True, fused_publish=True,
+                 fused_reduce=True, blocked=True)
+    run_workload(w, interleaved=True, comm_block=64, batched=True, stash=True, adopt=True,
+                 fused_publish=True, fused_reduce=True)
+    wide = synth.Workload(name="wide", n=70_001, workers=20, rounds=2, grad_std=1e-3,
+                          k_range=(2, 5), seed=8)                  # more shards than one launch sums
+    run_workload(wide, interleaved=True, batched=True, stash=True, fused_publish=True,
+                 fused_reduce=True)
+    # switching between the two kinds of buffers between rounds keeps the values
+    import paper_2406_02613_amd as A
+    own = A.ShardOwner(4096 + 5, 2, gpu_hyper(A, tiny), batched=True, interleaved_comm=True,
+                       bf16_accumulate=False)
+    own.set_options(interleaved_comm=False)
+    assert own.comm[0].dim() == 1
+    own.set_options(interleaved_comm=True)
+    assert own.comm[0].dim() == 2
+    with pytest.raises(ValueError):
+        A.ShardOwner(64, 2, gpu_hyper(A, tiny), bf16_accumulate=True, interleaved_comm=True)
+
+
 def test_tiny_with_blocked_state():
     w = synth.WORKLOADS["tiny"]
     run_workload(w, blocked=True)
@@ -249,17 +282,17 @@ def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
 
 def test_seven_billion_scale_shard_fused_path_as_benched():
     # the configuration bench.py times by default: bf16 stash, fused publish, fused reduce + step,
-    # interleaved state, one accumulate launch for all workers
+    # interleaved state, one accumulate launch for all workers, interleaved communication buffers
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
-                 stash=True, batched=True, rounds=3)
+                 stash=True, batched=True, interleaved=True, rounds=3)
 
 
 def test_seven_billion_hetero_blocked_state_fused_path():
     run_workload(synth.WORKLOADS["7b_hetero"], fused_publish=True, fused_reduce=True,
-                 blocked=True, stash=True, batched=True, rounds=2)
+                 blocked=True, stash=True, batched=True, interleaved=True, rounds=2)
 
 
 def test_smaller_workloads_on_the_benched_path():
     for name, rounds in (("gpt2s", 3), ("1b", 2)):
         run_workload(synth.WORKLOADS[name], fused_publish=True, fused_reduce=True, blocked=True,
-                     stash=True, batched=True, rounds=rounds)
+                     stash=True, batched=True, interleaved=True, rounds=rounds)
