@@ -97,9 +97,10 @@ def parse():
     ap.add_argument("--base-path", action="store_true",
                     help="the five base entry points only (= all three --unfused-* flags "
                          "except the fused bf16 output of the commit)")
-    ap.add_argument("--planar-comm", action="store_true",
-                    help="W separate communication buffers instead of the interleaved blocks of "
-                         "one buffer")
+    ap.add_argument("--interleaved-comm", action="store_true",
+                    help="the W communication buffers as the interleaved blocks of one buffer "
+                         "instead of W separate ones (same values; the reduce kernels get faster "
+                         "and steadier, the publishing kernels slower)")
     ap.add_argument("--comm-block-elems", type=int, default=16384,
                     help="elements per block of the interleaved communication buffers")
     ap.add_argument("--per-worker-launches", action="store_true",
@@ -731,9 +732,8 @@ def main():
                      fused_reduce=not (args.unfused_reduce or args.base_path),
                      bf16_stash=stash and not args.bf16_accumulate, adopt_first=False)
     batched = not args.per_worker_launches
-    # interleaved communication buffers are written by the batched launches only
-    main_opts["interleaved_comm"] = not (args.planar_comm or args.bf16_accumulate
-                                         or args.base_path or not batched)
+    main_opts["interleaved_comm"] = args.interleaved_comm and not (args.bf16_accumulate
+                                                                   or args.base_path)
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          blocked_state=blocked, block_elems=args.block_elems,

@@ -94,10 +94,12 @@ typedef struct acco_adamw_t {
  * interleaved block by block in ONE buffer - [worker 0 block][worker 1 block]...[worker W-1
  * block] repeated, shard w's pointer = base + w * block_elems, block_stride = W * block_elems.
  * acco_accumulate_batch writes such buffers (out_layout) and the reduction entry points read
- * them (shard_layout).  On MI355X, W = 8 buffers of 875M elements in 16384-element blocks,
- * alternating with eight separate buffers inside one process: reduce + estimate 4.51 ms against
- * 4.58-4.92 (depending on where the eight buffers happen to lie), reduce + commit 5.91 against
- * 6.05-6.47, second micro-batch + publish 6.53 against 6.32; the round 31.85 ms against 32.36.
+ * them (shard_layout).  An option, not what the benchmark uses: on MI355X, W = 8 buffers of
+ * 875M elements in 16384-element blocks make the two reduce + step kernels faster and
+ * independent of where W separate buffers would happen to lie (4.51 / 5.91 ms every time
+ * against 4.58-4.92 / 6.05-6.47), but the kernels that publish into them slower (second
+ * micro-batch + publish 6.53 against 6.32 ms; the fp32 accumulate + publish by 12-15 %):
+ * a round of equal counts comes out the same, one of unequal counts 3 % slower.
  * For a bf16 array block_elems must be >= 8; a blocked shard layout requires bf16 shards.
  */
 typedef struct acco_layout_t {

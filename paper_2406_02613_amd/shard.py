@@ -33,9 +33,10 @@ Options that give the same values with fewer bytes over HBM:
                  (acco_accumulate_batch) when their gradients are handed over together
                  (add_microbatches / add_microbatch_rows);
   interleaved_comm  the W bf16 communication buffers are the interleaved blocks of one buffer
-                 (state.InterleavedShards) instead of W separate ones: same values, placed so
-                 that the publish and reduce kernels stream them faster.  Every write to them
-                 then goes through acco_accumulate_batch, which takes the layout.
+                 (state.InterleavedShards) instead of W separate ones: same values; the reduce
+                 kernels stream them faster and at a speed that does not depend on where W
+                 separate buffers happen to lie, the publishing kernels write them slower.
+                 Every write to them goes through acco_accumulate_batch, which takes the layout.
 """
 from __future__ import annotations
 
