@@ -144,8 +144,6 @@ class EventLog:
         self.pairs.setdefault(name, []).append((s, e))
         return out
 
-    timed = __call__
-
     def summary(self):
         return {k: [s.elapsed_time(e) for s, e in v] for k, v in self.pairs.items()}
 

@@ -162,8 +162,9 @@ int acco_accumulate_second(float* acc, uint16_t* comm_bf16, const uint16_t* stas
                            const uint16_t* grad_bf16, int64_t n, int64_t* count, void* stream);
 
 /*
- * The accumulation calls above for SEVERAL workers' accumulators in one launch (grid.y = worker).
- * On a real node one process accumulates its whole gradient - all W shards of it - per
+ * The accumulation calls above (Alg. 1, computation stream: g_i <- g_i + grad F, N_i <- N_i + 1,
+ * and the hand-over Buffer_i <- g_i) for SEVERAL workers' accumulators in one launch
+ * (grid.y = worker).  On a real node one process accumulates its whole gradient - all W shards of it - per
  * micro-batch; with the W shards as W separate buffers that is W launches of the calls above,
  * or one of this.  Same values; what it saves is launches (a round of the GPT-2-small-scale
  * workload is 10 launches instead of 34) and the ramp-down / ramp-up between them.
