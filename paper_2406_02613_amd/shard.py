@@ -44,8 +44,7 @@ from typing import Callable, List, Optional
 
 from . import binding as B
 
-# names under which the calls of a round are reported to ShardOwner.trace, one per kernel
-# variant (they differ in the bytes they move): see _label()
+# what ShardOwner.set_options may switch between rounds
 OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first",
            "interleaved_comm")
 
