@@ -30,7 +30,9 @@
  *     counters are updated before return.  A call enqueues kernel launches only (no
  *     memset, copy, allocation or synchronisation) with its scalars passed by value, so
  *     it may be recorded by a stream capture; a replay repeats the device work with the
- *     scalars of the recorded call and touches no host counter.
+ *     scalars of the recorded call and touches no host counter (the *_dev step entry
+ *     points read their scalars from device memory instead, so that a replay can follow
+ *     the update index).
  *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
  *     is enqueued and no host counter is modified.
  *   - Thread-safe; no global mutable state besides cached device properties and the
@@ -326,6 +328,62 @@ int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
                             const acco_adamw_t* hp, int64_t* step,
                             const acco_layout_t* state_layout, const acco_layout_t* shard_layout,
                             void* stream);
+
+/*
+ * The four AdamW step entry points with their scalars read from DEVICE memory when the kernel
+ * runs, instead of being passed by value when the call is made.  What for: the update index,
+ * and with it the bias corrections of eq. (ACCO)'s Opt = AdamW, change with every committed
+ * update, so a launch recorded into a HIP graph with by-value scalars repeats update number t
+ * for ever.  With these forms a whole round (both stages of Alg. 1's communication stream) is
+ * recorded once; before each replay the host folds the scalars of that round's two steps
+ * (acco_fold_adamw), puts them into the device block (acco_stage_scalars) and replays.  Same
+ * kernels, same arithmetic, same values bit for bit as the by-value forms.
+ *
+ * acco_step_scalars_t: one step's folded scalars, 64 bytes, opaque (grad scale, betas, bias
+ *   corrections, step size, decay, epsilon as fp32, rounded once from double).
+ * acco_fold_adamw: host only.  Scalars of update number step + 1 on a gradient sum of
+ *   total_count micro-batches - exactly what the by-value entry points fold internally.
+ *   out: host.  Errors: NULL, invalid hyper-parameters, step < 0, total_count < 1.
+ * acco_stage_scalars: dst_dev[0 .. blocks) = src_host[0 .. blocks), enqueued on `stream` as one
+ *   small kernel that carries the blocks in its arguments (no memcpy; src_host may be reused as
+ *   soon as the call returns).  dst_dev: device, 16-byte aligned; 1 <= blocks <= 4.
+ * The *_dev step entry points: arguments as their by-value namesakes, with
+ *   scalars_dev  device, 16-byte aligned, in: read by the kernel when it runs; must not overlap
+ *                any buffer the call writes
+ * in place of hp / step / total_count / counts / total.  They update NO host counter: the
+ * caller that folds the scalars owns the update index and the totals.  The estimate forms write
+ * the bf16 output only (required).
+ * Errors: as the namesakes; scalars_dev NULL or misaligned.
+ */
+typedef struct acco_step_scalars_t {
+    float f[16];
+} acco_step_scalars_t;
+
+#define ACCO_STAGE_BLOCKS_MAX 4
+
+int acco_fold_adamw(const acco_adamw_t* hp, int64_t step, int64_t total_count,
+                    acco_step_scalars_t* out);
+int acco_stage_scalars(acco_step_scalars_t* dst_dev, const acco_step_scalars_t* src_host,
+                       int blocks, void* stream);
+int acco_estimate_step_dev(const float* theta, const float* m, const float* v, const float* gsum,
+                           uint16_t* theta_tilde_bf16, int64_t n,
+                           const acco_step_scalars_t* scalars_dev,
+                           const acco_layout_t* state_layout, void* stream);
+int acco_commit_step_dev(float* theta, float* m, float* v, const float* gsum, uint16_t* theta_bf16,
+                         int64_t n, const acco_step_scalars_t* scalars_dev,
+                         const acco_layout_t* state_layout, void* stream);
+int acco_reduce_estimate_step_dev(const float* theta, const float* m, const float* v, float* gsum,
+                                  const void* const* shards, int workers, int dtype,
+                                  uint16_t* theta_tilde_bf16, int64_t n,
+                                  const acco_step_scalars_t* scalars_dev,
+                                  const acco_layout_t* state_layout,
+                                  const acco_layout_t* shard_layout, void* stream);
+int acco_reduce_commit_step_dev(float* theta, float* m, float* v, float* gsum,
+                                const void* const* shards, int workers, int dtype,
+                                uint16_t* theta_bf16, int64_t n,
+                                const acco_step_scalars_t* scalars_dev,
+                                const acco_layout_t* state_layout,
+                                const acco_layout_t* shard_layout, void* stream);
 
 /*
  * Plain SGD with decoupled weight decay as Opt - the optimizer of the paper's convergence

@@ -27,7 +27,9 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_accumulate_second", "acco_accumulate_bf16", "acco_accumulate_batch",
            "acco_cast_params", "acco_reduce_shards",
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
-           "acco_reduce_commit_step", "acco_sgd_estimate_step", "acco_sgd_commit_step",
+           "acco_reduce_commit_step", "acco_fold_adamw", "acco_stage_scalars",
+           "acco_estimate_step_dev", "acco_commit_step_dev", "acco_reduce_estimate_step_dev",
+           "acco_reduce_commit_step_dev", "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
            "acco_set_resident_waves", "acco_reset_launch_settings")
 
@@ -46,6 +48,14 @@ class Layout(ctypes.Structure):
 class Sgd(ctypes.Structure):
     """acco_sgd_t"""
     _fields_ = [("lr", ctypes.c_double), ("weight_decay", ctypes.c_double)]
+
+
+class StepScalars(ctypes.Structure):
+    """acco_step_scalars_t: one step's folded scalars (opaque, 64 bytes)"""
+    _fields_ = [("f", ctypes.c_float * 16)]
+
+
+STAGE_BLOCKS_MAX = 4
 
 
 class AccoError(RuntimeError):
@@ -88,6 +98,15 @@ def lib() -> ctypes.CDLL:
                                                 p]
         L.acco_reduce_commit_step.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, pi64, pi64, p,
                                               i64, ctypes.POINTER(AdamW), pi64, play, play, p]
+        psc = ctypes.POINTER(StepScalars)
+        L.acco_fold_adamw.argtypes = [ctypes.POINTER(AdamW), i64, i64, psc]
+        L.acco_stage_scalars.argtypes = [p, psc, ci, p]
+        L.acco_estimate_step_dev.argtypes = [p, p, p, p, p, i64, p, play, p]
+        L.acco_commit_step_dev.argtypes = [p, p, p, p, p, i64, p, play, p]
+        L.acco_reduce_estimate_step_dev.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, p, i64,
+                                                    p, play, play, p]
+        L.acco_reduce_commit_step_dev.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, p, i64, p,
+                                                  play, play, p]
         L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
         L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
@@ -423,6 +442,106 @@ def acco_commit_step(theta, m, v, gsum, hp: AdamW, step: Counter, total_count: i
                                 ctypes.byref(hp), step.ref(), int(total_count), _lay(layout),
                                 _stream())
     _check(rc, "acco_commit_step")
+
+
+# ------------------------------------------------- step scalars in device memory (*_dev forms)
+
+
+def acco_fold_adamw(hp: AdamW, step: int, total_count: int) -> StepScalars:
+    """Folded scalars of update number step + 1 on a sum of total_count micro-batch gradients."""
+    out = StepScalars()
+    _check(lib().acco_fold_adamw(ctypes.byref(hp), int(step), int(total_count), ctypes.byref(out)),
+           "acco_fold_adamw")
+    return out
+
+
+def _scalars_ptr(scalars_dev, block: int) -> int:
+    """Address of block `block` of a device tensor of scalar blocks (float32, 16 per block)."""
+    import torch
+    nblk = scalars_dev.numel() // 16
+    if scalars_dev.numel() % 16 or not 0 <= int(block) < nblk:
+        raise ValueError("scalars_dev: expected 16 float32 per block and a block inside it")
+    return _dev(scalars_dev, torch.float32, scalars_dev.numel(), "scalars_dev") + 64 * int(block)
+
+
+def acco_stage_scalars(scalars_dev, blocks: Sequence[StepScalars], first_block: int = 0) -> None:
+    """scalars_dev[first_block ...] = blocks, by one small kernel on the current stream."""
+    k = len(blocks)
+    _scalars_ptr(scalars_dev, first_block + k - 1 if k else first_block)
+    src = (StepScalars * max(k, 1))(*blocks)
+    _check(lib().acco_stage_scalars(_scalars_ptr(scalars_dev, first_block), src, k, _stream()),
+           "acco_stage_scalars")
+
+
+class ScalarStager:
+    """acco_fold_adamw + acco_stage_scalars for the first `blocks` blocks of one device tensor,
+    with the tensor checked and the argument arrays built once: for loops that restage the
+    scalars before every replay of a recorded round."""
+
+    def __init__(self, scalars_dev, blocks: int):
+        if not 1 <= int(blocks) <= STAGE_BLOCKS_MAX:
+            raise ValueError(f"1 to {STAGE_BLOCKS_MAX} blocks per call")
+        _scalars_ptr(scalars_dev, int(blocks) - 1)
+        self._keep = scalars_dev
+        self._ptr = ctypes.c_void_p(_scalars_ptr(scalars_dev, 0))
+        self._k = int(blocks)
+        self._src = (StepScalars * self._k)()
+        self._lib = lib()
+
+    def __call__(self, hp: AdamW, step: int, totals: Sequence[int]) -> None:
+        """Block k <- the scalars of update number step + 1 on totals[k] micro-batches."""
+        if len(totals) != self._k:
+            raise ValueError("one total per block")
+        L, hp_ref = self._lib, ctypes.byref(hp)
+        for k, t in enumerate(totals):
+            _check(L.acco_fold_adamw(hp_ref, int(step), int(t), ctypes.byref(self._src[k])),
+                   "acco_fold_adamw")
+        _check(L.acco_stage_scalars(self._ptr, self._src, self._k, _stream()),
+               "acco_stage_scalars")
+
+
+def acco_estimate_step_dev(theta, m, v, gsum, scalars_dev, block: int, *, theta_tilde_bf16,
+                           n: Optional[int] = None) -> None:
+    import torch
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    rc = lib().acco_estimate_step_dev(st[0], st[1], st[2], st[3],
+                                      _dev(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"),
+                                      n, _scalars_ptr(scalars_dev, block), _lay(layout), _stream())
+    _check(rc, "acco_estimate_step_dev")
+
+
+def acco_commit_step_dev(theta, m, v, gsum, scalars_dev, block: int, *, theta_bf16=None,
+                         n: Optional[int] = None) -> None:
+    import torch
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    rc = lib().acco_commit_step_dev(st[0], st[1], st[2], st[3],
+                                    _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
+                                    _scalars_ptr(scalars_dev, block), _lay(layout), _stream())
+    _check(rc, "acco_commit_step_dev")
+
+
+def acco_reduce_estimate_step_dev(theta, m, v, gsum, shards: Sequence, scalars_dev, block: int, *,
+                                  theta_tilde_bf16, n: Optional[int] = None) -> None:
+    import torch
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    ptrs, W, dt, sl = _shard_ptrs(shards, n, "acco_reduce_estimate_step_dev")
+    rc = lib().acco_reduce_estimate_step_dev(
+        st[0], st[1], st[2], st[3], ptrs, W, dt,
+        _dev(theta_tilde_bf16, torch.bfloat16, n, "theta_tilde_bf16"), n,
+        _scalars_ptr(scalars_dev, block), _lay(layout), _lay(sl), _stream())
+    _check(rc, "acco_reduce_estimate_step_dev")
+
+
+def acco_reduce_commit_step_dev(theta, m, v, gsum, shards: Sequence, scalars_dev, block: int, *,
+                                theta_bf16=None, n: Optional[int] = None) -> None:
+    import torch
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    ptrs, W, dt, sl = _shard_ptrs(shards, n, "acco_reduce_commit_step_dev")
+    rc = lib().acco_reduce_commit_step_dev(
+        st[0], st[1], st[2], st[3], ptrs, W, dt,
+        _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n, _scalars_ptr(scalars_dev, block),
+        _lay(layout), _lay(sl), _stream())
+    _check(rc, "acco_reduce_commit_step_dev")
 
 
 def make_sgd(lr, weight_decay=0.0) -> Sgd:

@@ -685,6 +685,88 @@ int check_step_buffers(const float* theta, const float* m, const float* v, const
 
 }  // namespace
 
+namespace {
+
+template <class SC>
+constexpr bool from_device = std::is_same<SC, ScalarsFromDevice>::value;
+
+// The device-scalar forms exist for the outputs a recorded round uses: bf16 theta~ for the
+// estimate (no fp32 copy).
+template <class SC>
+int launch_estimate(const float* theta, const float* m, const float* v, const float* gsum,
+                    float* o32, uint16_t* o16, int64_t n, const StateLayout& L, const SC& sc,
+                    hipStream_t s)
+{
+    return with_layout(L, [&](auto at) {
+        constexpr bool B = is_blocked<decltype(at)>;
+        if constexpr (from_device<SC>) {
+            if (o32 != nullptr || o16 == nullptr) return (int)ACCO_ERR_ARG;
+        } else {
+            if (o32 != nullptr && o16 != nullptr)
+                return launch(kEstimate, AdamOp<false, true, true, B, SC>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, o16, sc, at}, n, s);
+            if (o32 != nullptr)
+                return launch(kEstimate, AdamOp<false, true, false, B, SC>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, nullptr, sc, at}, n, s);
+        }
+        return launch(kEstimate, AdamOp<false, false, true, B, SC>{theta, m, v, gsum, nullptr, nullptr, nullptr, nullptr, o16, sc, at}, n, s);
+    });
+}
+
+template <class SC>
+int launch_commit(float* theta, float* m, float* v, const float* gsum, uint16_t* o16, int64_t n,
+                  const StateLayout& L, const SC& sc, hipStream_t s)
+{
+    return with_layout(L, [&](auto at) {
+        constexpr bool B = is_blocked<decltype(at)>;
+        if (o16 != nullptr)
+            return launch(kCommit, AdamOp<true, false, true, B, SC>{theta, m, v, gsum, theta, m, v, nullptr, o16, sc, at}, n, s);
+        return launch(kCommit, AdamOp<true, false, false, B, SC>{theta, m, v, gsum, theta, m, v, nullptr, nullptr, sc, at}, n, s);
+    });
+}
+
+// the scalar block of the *_dev entry points: device memory, 16-byte aligned, clear of every
+// buffer the call writes (conservative for blocked arrays: their whole extent)
+int check_scalars_dev(const acco_step_scalars_t* p, const void* const* written,
+                      const int64_t* bytes, int count)
+{
+    if (p == nullptr) return ACCO_ERR_NULL;
+    if (!aligned16(p)) return ACCO_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (overlap(p, (int64_t)sizeof *p, written[k], bytes[k])) return ACCO_ERR_ALIAS;
+    return ACCO_OK;
+}
+
+static_assert(sizeof(AdamScalars) <= sizeof(acco_step_scalars_t), "scalar block too small");
+static_assert(sizeof(acco_step_scalars_t) == kWordsPerBlock * 4, "scalar block size");
+static_assert(sizeof(StagedBlocks) == ACCO_STAGE_BLOCKS_MAX * sizeof(acco_step_scalars_t),
+              "staging argument size");
+
+}  // namespace
+
+ACCO_API int acco_fold_adamw(const acco_adamw_t* hp, int64_t step, int64_t total_count,
+                             acco_step_scalars_t* out)
+{
+    if (out == nullptr) return ACCO_ERR_NULL;
+    if (int rc = check_hyper(hp, step, total_count)) return rc;
+    const AdamScalars sc = fold(*hp, step, total_count);
+    std::memset(out, 0, sizeof *out);
+    std::memcpy(out, &sc, sizeof sc);
+    return ACCO_OK;
+}
+
+ACCO_API int acco_stage_scalars(acco_step_scalars_t* dst_dev, const acco_step_scalars_t* src_host,
+                                int blocks, void* stream)
+{
+    if (dst_dev == nullptr || src_host == nullptr) return ACCO_ERR_NULL;
+    if (blocks < 1 || blocks > ACCO_STAGE_BLOCKS_MAX) return ACCO_ERR_SIZE;
+    if (!aligned16(dst_dev)) return ACCO_ERR_ALIGN;
+    StagedBlocks arg;
+    std::memset(&arg, 0, sizeof arg);
+    std::memcpy(arg.word, src_host, (size_t)blocks * sizeof *src_host);
+    hipLaunchKernelGGL(stage_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<uint32_t*>(dst_dev), arg, blocks * kWordsPerBlock);
+    return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
+}
+
 ACCO_API int acco_estimate_step(const float* theta, const float* m, const float* v,
                                 const float* gsum, float* theta_tilde_f32,
                                 uint16_t* theta_tilde_bf16, int64_t n, const acco_adamw_t* hp,
@@ -699,19 +781,28 @@ ACCO_API int acco_estimate_step(const float* theta, const float* m, const float*
         return rc;
     if (int rc = check_hyper(hp, step, total_count)) return rc;
     if (n == 0) return ACCO_OK;
+    return launch_estimate(theta, m, v, gsum, theta_tilde_f32, theta_tilde_bf16, n, L,
+                           ScalarsByValue{fold(*hp, step, total_count)},
+                           static_cast<hipStream_t>(stream));
+}
 
-    const AdamScalars sc = fold(*hp, step, total_count);
-    hipStream_t       s  = static_cast<hipStream_t>(stream);
-    float*            o32 = theta_tilde_f32;
-    uint16_t*         o16 = theta_tilde_bf16;
-    return with_layout(L, [&](auto at) {
-        constexpr bool B = is_blocked<decltype(at)>;
-        if (o32 != nullptr && o16 != nullptr)
-            return launch(kEstimate, AdamOp<false, true, true, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, o16, sc, at}, n, s);
-        if (o32 != nullptr)
-            return launch(kEstimate, AdamOp<false, true, false, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, o32, nullptr, sc, at}, n, s);
-        return launch(kEstimate, AdamOp<false, false, true, B>{theta, m, v, gsum, nullptr, nullptr, nullptr, nullptr, o16, sc, at}, n, s);
-    });
+ACCO_API int acco_estimate_step_dev(const float* theta, const float* m, const float* v,
+                                    const float* gsum, uint16_t* theta_tilde_bf16, int64_t n,
+                                    const acco_step_scalars_t* scalars_dev,
+                                    const acco_layout_t* state_layout, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (n > 0 && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_tilde_bf16, n, L)) return rc;
+    const void* written[1] = {theta_tilde_bf16};
+    const int64_t bytes[1] = {n * 2};
+    if (int rc = check_scalars_dev(scalars_dev, written, bytes, 1)) return rc;
+    if (n == 0) return ACCO_OK;
+    return launch_estimate(theta, m, v, gsum, nullptr, theta_tilde_bf16, n, L,
+                           ScalarsFromDevice{reinterpret_cast<const AdamScalars*>(scalars_dev)},
+                           static_cast<hipStream_t>(stream));
 }
 
 ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsum,
@@ -727,18 +818,31 @@ ACCO_API int acco_commit_step(float* theta, float* m, float* v, const float* gsu
     if (int rc = check_hyper(hp, *step, total_count)) return rc;
 
     int rc = ACCO_OK;
-    if (n > 0) {
-        const AdamScalars sc = fold(*hp, *step, total_count);
-        hipStream_t       s  = static_cast<hipStream_t>(stream);
-        rc = with_layout(L, [&](auto at) {
-            constexpr bool B = is_blocked<decltype(at)>;
-            if (theta_bf16 != nullptr)
-                return launch(kCommit, AdamOp<true, false, true, B>{theta, m, v, gsum, theta, m, v, nullptr, theta_bf16, sc, at}, n, s);
-            return launch(kCommit, AdamOp<true, false, false, B>{theta, m, v, gsum, theta, m, v, nullptr, nullptr, sc, at}, n, s);
-        });
-    }
+    if (n > 0)
+        rc = launch_commit(theta, m, v, gsum, theta_bf16, n, L,
+                           ScalarsByValue{fold(*hp, *step, total_count)},
+                           static_cast<hipStream_t>(stream));
     if (rc == ACCO_OK) *step += 1;
     return rc;
+}
+
+ACCO_API int acco_commit_step_dev(float* theta, float* m, float* v, const float* gsum,
+                                  uint16_t* theta_bf16, int64_t n,
+                                  const acco_step_scalars_t* scalars_dev,
+                                  const acco_layout_t* state_layout, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
+    const void* written[4] = {theta, m, v, theta_bf16};
+    const int64_t ext      = state_extent(L, n);
+    const int64_t bytes[4] = {ext, ext, ext, n * 2};
+    if (int rc = check_scalars_dev(scalars_dev, written, bytes, 4)) return rc;
+    if (n == 0) return ACCO_OK;
+    return launch_commit(theta, m, v, gsum, theta_bf16, n, L,
+                         ScalarsFromDevice{reinterpret_cast<const AdamScalars*>(scalars_dev)},
+                         static_cast<hipStream_t>(stream));
 }
 
 ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* comm_bf16,
@@ -778,13 +882,15 @@ ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint
 namespace {
 
 // Fused reduce + step over the last (up to kReduceChunk) shards; leading chunks of a larger
-// worker count go through the plain reduction first.
-template <bool BF16>
+// worker count go through the plain reduction first.  The device-scalar forms have the bf16
+// output only.
+template <bool BF16, class SC>
 int launch_reduce_estimate(const float* theta, const float* m, const float* v, float* gsum,
                            const StateLayout& L, const StateLayout& SL,
                            const void* const* shards, int workers, float* o32, uint16_t* o16,
-                           int64_t n, const AdamScalars& sc, hipStream_t s)
+                           int64_t n, const SC& sc, hipStream_t s)
 {
+    if (from_device<SC> && (o32 != nullptr || o16 == nullptr)) return ACCO_ERR_ARG;
     const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
     if (lead > 0)
         if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, s)) return rc;
@@ -795,21 +901,23 @@ int launch_reduce_estimate(const float* theta, const float* m, const float* v, f
             constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
             auto go = [&](auto acc_tag) {
                 constexpr bool ACC = decltype(acc_tag)::value;
-                if (o32 != nullptr && o16 != nullptr)
-                    return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at, sat}, n, s);
-                if (o32 != nullptr)
-                    return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at, sat}, n, s);
-                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B, S>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at, sat}, n, s);
+                if constexpr (!from_device<SC>) {
+                    if (o32 != nullptr && o16 != nullptr)
+                        return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at, sat}, n, s);
+                    if (o32 != nullptr)
+                        return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at, sat}, n, s);
+                }
+                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at, sat}, n, s);
             };
             return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
         });
     });
 }
 
-template <bool BF16>
+template <bool BF16, class SC>
 int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const StateLayout& L,
                          const StateLayout& SL, const void* const* shards, int workers,
-                         uint16_t* o16, int64_t n, const AdamScalars& sc, hipStream_t s)
+                         uint16_t* o16, int64_t n, const SC& sc, hipStream_t s)
 {
     const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
     if (lead > 0)
@@ -820,10 +928,28 @@ int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const St
         return with_shard_layout<BF16>(SL, [&](auto sat) {
             constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
             if (o16 != nullptr)
-                return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B, S>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at, sat}, n, s);
-            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B, S>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at, sat}, n, s);
+                return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at, sat}, n, s);
+            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B, S, SC>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at, sat}, n, s);
         });
     });
+}
+
+// validation shared by the by-value and the device-scalar forms of the two fused entry points
+int check_reduce_step(const float* theta, const float* m, const float* v, const float* gsum,
+                      const void* const* shards, int workers, int dtype, const void* out_f32,
+                      const void* out_bf16, int64_t n, const acco_layout_t* state_layout,
+                      const acco_layout_t* shard_layout, StateLayout* L, StateLayout* SL)
+{
+    if (int rc = parse_layout(state_layout, L)) return rc;
+    if (int rc = parse_shard_layout(shard_layout, dtype, SL)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, out_f32, out_bf16, n, *L)) return rc;
+    const void* st[4] = {theta, m, v, gsum};
+    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, *L, *SL)) return rc;
+    const int64_t ext = state_extent(*SL, n, dtype == ACCO_BF16 ? 2 : 4);
+    for (int w = 0; w < workers; ++w)
+        if (overlap(out_f32, n * 4, shards[w], ext) || overlap(out_bf16, n * 2, shards[w], ext))
+            return ACCO_ERR_ALIAS;
+    return ACCO_OK;
 }
 
 }  // namespace
@@ -840,31 +966,47 @@ ACCO_API int acco_reduce_estimate_step(const float* theta, const float* m, const
     if (shards == nullptr || counts == nullptr || total == nullptr) return ACCO_ERR_NULL;
     if (n > 0 && theta_tilde_f32 == nullptr && theta_tilde_bf16 == nullptr) return ACCO_ERR_NULL;
     StateLayout L, SL;
-    if (int rc = parse_layout(state_layout, &L)) return rc;
-    if (int rc = parse_shard_layout(shard_layout, dtype, &SL)) return rc;
-    if (int rc = check_step_buffers(theta, m, v, gsum, theta_tilde_f32, theta_tilde_bf16, n, L))
+    if (int rc = check_reduce_step(theta, m, v, gsum, shards, workers, dtype, theta_tilde_f32,
+                                   theta_tilde_bf16, n, state_layout, shard_layout, &L, &SL))
         return rc;
-    const void* st[4] = {theta, m, v, gsum};
-    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L, SL)) return rc;
-    const int64_t ext = state_extent(SL, n, dtype == ACCO_BF16 ? 2 : 4);
-    for (int w = 0; w < workers; ++w)
-        if (overlap(theta_tilde_f32, n * 4, shards[w], ext) ||
-            overlap(theta_tilde_bf16, n * 2, shards[w], ext))
-            return ACCO_ERR_ALIAS;
     int64_t new_total = 0;
     if (int rc = sum_counts(counts, workers, 0, &new_total)) return rc;
     if (int rc = check_hyper(hp, step, new_total)) return rc;
 
     int rc = ACCO_OK;
     if (n > 0) {
-        hipStream_t       s  = static_cast<hipStream_t>(stream);
-        const AdamScalars sc = fold(*hp, step, new_total);
+        hipStream_t          s  = static_cast<hipStream_t>(stream);
+        const ScalarsByValue sc = {fold(*hp, step, new_total)};
         rc = dtype == ACCO_BF16
                  ? launch_reduce_estimate<true>(theta, m, v, gsum, L, SL, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s)
                  : launch_reduce_estimate<false>(theta, m, v, gsum, L, SL, shards, workers, theta_tilde_f32, theta_tilde_bf16, n, sc, s);
     }
     if (rc == ACCO_OK) *total = new_total;
     return rc;
+}
+
+ACCO_API int acco_reduce_estimate_step_dev(const float* theta, const float* m, const float* v,
+                                           float* gsum, const void* const* shards, int workers,
+                                           int dtype, uint16_t* theta_tilde_bf16, int64_t n,
+                                           const acco_step_scalars_t* scalars_dev,
+                                           const acco_layout_t* state_layout,
+                                           const acco_layout_t* shard_layout, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (shards == nullptr || (n > 0 && theta_tilde_bf16 == nullptr)) return ACCO_ERR_NULL;
+    StateLayout L, SL;
+    if (int rc = check_reduce_step(theta, m, v, gsum, shards, workers, dtype, nullptr,
+                                   theta_tilde_bf16, n, state_layout, shard_layout, &L, &SL))
+        return rc;
+    const void* written[2] = {gsum, theta_tilde_bf16};
+    const int64_t bytes[2] = {state_extent(L, n), n * 2};
+    if (int rc = check_scalars_dev(scalars_dev, written, bytes, 2)) return rc;
+    if (n == 0) return ACCO_OK;
+    hipStream_t             s  = static_cast<hipStream_t>(stream);
+    const ScalarsFromDevice sc = {reinterpret_cast<const AdamScalars*>(scalars_dev)};
+    return dtype == ACCO_BF16
+               ? launch_reduce_estimate<true>(theta, m, v, gsum, L, SL, shards, workers, nullptr, theta_tilde_bf16, n, sc, s)
+               : launch_reduce_estimate<false>(theta, m, v, gsum, L, SL, shards, workers, nullptr, theta_tilde_bf16, n, sc, s);
 }
 
 ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,
@@ -878,22 +1020,17 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
     if (shards == nullptr || counts == nullptr || total == nullptr || step == nullptr)
         return ACCO_ERR_NULL;
     StateLayout L, SL;
-    if (int rc = parse_layout(state_layout, &L)) return rc;
-    if (int rc = parse_shard_layout(shard_layout, dtype, &SL)) return rc;
-    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
-    const void* st[4] = {theta, m, v, gsum};
-    if (int rc = check_shards_vs_state(shards, workers, dtype, n, st, 4, L, SL)) return rc;
-    const int64_t ext = state_extent(SL, n, dtype == ACCO_BF16 ? 2 : 4);
-    for (int w = 0; w < workers; ++w)
-        if (overlap(theta_bf16, n * 2, shards[w], ext)) return ACCO_ERR_ALIAS;
+    if (int rc = check_reduce_step(theta, m, v, gsum, shards, workers, dtype, nullptr, theta_bf16,
+                                   n, state_layout, shard_layout, &L, &SL))
+        return rc;
     int64_t new_total = 0;
     if (int rc = sum_counts(counts, workers, *total, &new_total)) return rc;
     if (int rc = check_hyper(hp, *step, new_total)) return rc;
 
     int rc = ACCO_OK;
     if (n > 0) {
-        hipStream_t       s  = static_cast<hipStream_t>(stream);
-        const AdamScalars sc = fold(*hp, *step, new_total);
+        hipStream_t          s  = static_cast<hipStream_t>(stream);
+        const ScalarsByValue sc = {fold(*hp, *step, new_total)};
         rc = dtype == ACCO_BF16
                  ? launch_reduce_commit<true>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s)
                  : launch_reduce_commit<false>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s);
@@ -903,6 +1040,31 @@ ACCO_API int acco_reduce_commit_step(float* theta, float* m, float* v, float* gs
         *step += 1;
     }
     return rc;
+}
+
+ACCO_API int acco_reduce_commit_step_dev(float* theta, float* m, float* v, float* gsum,
+                                         const void* const* shards, int workers, int dtype,
+                                         uint16_t* theta_bf16, int64_t n,
+                                         const acco_step_scalars_t* scalars_dev,
+                                         const acco_layout_t* state_layout,
+                                         const acco_layout_t* shard_layout, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (shards == nullptr) return ACCO_ERR_NULL;
+    StateLayout L, SL;
+    if (int rc = check_reduce_step(theta, m, v, gsum, shards, workers, dtype, nullptr, theta_bf16,
+                                   n, state_layout, shard_layout, &L, &SL))
+        return rc;
+    const void* written[5] = {theta, m, v, gsum, theta_bf16};
+    const int64_t ext      = state_extent(L, n);
+    const int64_t bytes[5] = {ext, ext, ext, ext, n * 2};
+    if (int rc = check_scalars_dev(scalars_dev, written, bytes, 5)) return rc;
+    if (n == 0) return ACCO_OK;
+    hipStream_t             s  = static_cast<hipStream_t>(stream);
+    const ScalarsFromDevice sc = {reinterpret_cast<const AdamScalars*>(scalars_dev)};
+    return dtype == ACCO_BF16
+               ? launch_reduce_commit<true>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s)
+               : launch_reduce_commit<false>(theta, m, v, gsum, L, SL, shards, workers, theta_bf16, n, sc, s);
 }
 
 namespace {
@@ -1034,7 +1196,7 @@ ACCO_API const char* acco_status_string(int status)
 
 ACCO_API int acco_version(void)
 {
-    return 400;  // 0.4.0
+    return 500;  // 0.5.0
 }
 
 ACCO_API void acco_reset_launch_settings(void)

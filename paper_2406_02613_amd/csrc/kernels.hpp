@@ -115,6 +115,41 @@ struct AdamScalars {
     float eps;
 };
 
+// Where a step kernel takes its scalars from: the kernel arguments (the usual case), or a block
+// in device memory that is read when the kernel RUNS - a launch recorded into a graph then
+// follows the scalars the host stages there before each replay (the update index, and with it
+// the bias corrections, change every round).
+struct ScalarsByValue {
+    AdamScalars s;
+    __device__ __forceinline__ const AdamScalars& get() const { return s; }
+};
+
+struct ScalarsFromDevice {
+    const AdamScalars* p;
+    __device__ __forceinline__ AdamScalars get() const { return *p; }
+};
+
+// Puts scalar blocks that travel in the kernel arguments into device memory (one wavefront;
+// 16 words per block).  Kernels later on the same stream read them there.
+constexpr int kWordsPerBlock   = 16;
+constexpr int kStagedWordsMax  = 64;
+
+struct StagedBlocks {
+    uint32_t word[kStagedWordsMax];
+};
+
+__global__ void __launch_bounds__(64) stage_kernel(uint32_t* dst, const StagedBlocks src,
+                                                   const int words)
+{
+    // lane i picks word i by a chain of selects: the argument words stay in scalar registers
+    // (indexing them by lane would spill the whole block to private memory)
+    const int i = (int)threadIdx.x;
+    uint32_t  x = 0;
+#pragma unroll
+    for (int k = 0; k < kStagedWordsMax; ++k) x = (i == k) ? src.word[k] : x;
+    if (i < words) dst[i] = x;
+}
+
 // AdamW with decoupled decay on theta(t), bias-corrected moments, eps added to the
 // bias-corrected root.  `/` and __builtin_sqrtf compile to the correctly rounded
 // sequences (the __fsqrt_rn intrinsic does not: it was measured 1 ulp off on gfx950).
@@ -539,7 +574,7 @@ __device__ __forceinline__ void adamw_vec(f4 t, f4 m, f4 v, f4 g, const AdamScal
 
 // COMMIT: write theta, m, v in place.  OUT_F32 / OUT_BF16: extra (planar) outputs of the
 // new theta.  BLOCKED: theta, m, v, gsum share a blocked layout.
-template <bool COMMIT, bool OUT_F32, bool OUT_BF16, bool BLOCKED>
+template <bool COMMIT, bool OUT_F32, bool OUT_BF16, bool BLOCKED, class SC = ScalarsByValue>
 struct AdamOp {
     static constexpr int kElems = 4;
     const float*       theta;
@@ -551,7 +586,7 @@ struct AdamOp {
     float*             v_w;
     float*             out_f32;
     uint16_t*          out_bf16;
-    AdamScalars        s;
+    SC                 s;
     StateAddr<BLOCKED> at;
     struct In {
         f4 t, m, v, g;
@@ -569,7 +604,7 @@ struct AdamOp {
     __device__ __forceinline__ void apply(int64_t i, const In& in) const
     {
         f4 t, mm, vv;
-        adamw_vec(in.t, in.m, in.v, in.g, s, t, mm, vv);
+        adamw_vec(in.t, in.m, in.v, in.g, s.get(), t, mm, vv);
         if (COMMIT) {
             const int64_t a = at.vec(i);
             st(reinterpret_cast<f4*>(theta_w) + a, t);
@@ -583,7 +618,7 @@ struct AdamOp {
     {
         const int64_t a = at.elem(j);
         float         t, mm, vv;
-        adamw_elem(theta[a], m[a], v[a], gsum[a], s, t, mm, vv);
+        adamw_elem(theta[a], m[a], v[a], gsum[a], s.get(), t, mm, vv);
         if (COMMIT) {
             theta_w[a] = t;
             m_w[a]     = mm;
@@ -600,7 +635,7 @@ struct AdamOp {
 // the gradient sum is formed in registers (same order as ReduceOp), optionally stored to
 // gsum (stage 1 keeps it for stage 2), and consumed by the update in the same pass.
 template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16,
-          bool BLOCKED, bool SB = false>
+          bool BLOCKED, bool SB = false, class SC = ScalarsByValue>
 struct ReduceAdamOp {
     static constexpr int kElems = 4;
     const float*       theta;
@@ -614,7 +649,7 @@ struct ReduceAdamOp {
     float*             v_w;
     float*             out_f32;
     uint16_t*          out_bf16;
-    AdamScalars        s;
+    SC                 s;
     StateAddr<BLOCKED> at;
     StateAddr<SB>      sat;   // layout of every shard
     struct In {
@@ -654,7 +689,7 @@ struct ReduceAdamOp {
         }
         if (WRITE_GSUM) st(reinterpret_cast<f4*>(gsum) + a, g);
         f4 t, mm, vv;
-        adamw_vec(in.t, in.m, in.v, g, s, t, mm, vv);
+        adamw_vec(in.t, in.m, in.v, g, s.get(), t, mm, vv);
         if (COMMIT) {
             st(reinterpret_cast<f4*>(theta_w) + a, t);
             st(reinterpret_cast<f4*>(m_w) + a, mm);
@@ -675,7 +710,7 @@ struct ReduceAdamOp {
         }
         if (WRITE_GSUM) gsum[a] = g;
         float t, mm, vv;
-        adamw_elem(theta[a], m[a], v[a], g, s, t, mm, vv);
+        adamw_elem(theta[a], m[a], v[a], g, s.get(), t, mm, vv);
         if (COMMIT) {
             theta_w[a] = t;
             m_w[a]     = mm;

@@ -37,6 +37,10 @@ Options that give the same values with fewer bytes over HBM:
                  kernels stream them faster and at a speed that does not depend on where W
                  separate buffers happen to lie, the publishing kernels write them slower.
                  Every write to them goes through acco_accumulate_batch, which takes the layout.
+  device_scalars the two AdamW steps read their folded scalars from a small device block that
+                 the owner fills before each stage (acco_fold_adamw, acco_stage_scalars, the
+                 *_dev step entry points): same values; what it allows is `record_round`, a whole
+                 round recorded once as a HIP graph and replayed while the update index moves on.
 """
 from __future__ import annotations
 
@@ -46,7 +50,7 @@ from . import binding as B
 
 # what ShardOwner.set_options may switch between rounds
 OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first",
-           "interleaved_comm")
+           "interleaved_comm", "device_scalars")
 
 
 class ShardOwner:
@@ -56,7 +60,7 @@ class ShardOwner:
                  block_elems: int = 8192, bf16_stash: bool = False,
                  bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False,
                  batched: bool = False, interleaved_comm: bool = False,
-                 comm_block_elems: int = 16384):
+                 comm_block_elems: int = 16384, device_scalars: bool = False):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
@@ -113,6 +117,16 @@ class ShardOwner:
         self._fresh = [True] * workers                        # next accumulate starts a new sum
         self._published = [False] * workers                   # comm[w] already written this stage
         self._stashed = [False] * workers                     # the sum so far sits in stash[w]
+        # block 0: the scalars of the estimate, block 1: those of the commit
+        self.scalars = None
+        self.device_scalars = False
+        self._select_scalars(bool(device_scalars))
+        self._recording = False
+
+    def _select_scalars(self, on: bool) -> None:
+        if on and self.scalars is None:
+            self.scalars = self.torch.zeros(2 * 16, dtype=self.torch.float32, device=self._dev)
+        self.device_scalars = on
 
     def _select_comm(self, interleaved: bool) -> None:
         if not self.comm_bf16:
@@ -142,8 +156,8 @@ class ShardOwner:
         return self.trace(label, fn, *args, **kw)
 
     def set_options(self, **opts) -> None:
-        """Switch fused_bf16_out / fused_publish / fused_reduce / bf16_stash / adopt_first between
-        rounds (no accumulation may be under way): the values of a round do not depend on them,
+        """Switch fused_bf16_out / fused_publish / fused_reduce / bf16_stash / adopt_first /
+        interleaved_comm / device_scalars between rounds (no accumulation may be under way): the values of a round do not depend on them,
         only the calls it is made of.  Buffers are those of the constructor: a stash can only be
         switched on if it was allocated then."""
         if not all(self._fresh):
@@ -153,6 +167,8 @@ class ShardOwner:
                 raise ValueError(f"unknown option {k!r}")
             if k == "interleaved_comm":
                 self._select_comm(bool(val))
+            elif k == "device_scalars":
+                self._select_scalars(bool(val))
             else:
                 setattr(self, k, bool(val))
         self.fused_publish = self.fused_publish and self.comm_bf16
@@ -337,9 +353,30 @@ class ShardOwner:
             self.stash = [None] * self.W          # the adopted buffers go back to the caller
 
     # communication stream
+    def _stage_scalars(self, block: int, total: int) -> None:
+        """Put the scalars of the pending update on `total` micro-batches into scalar block
+        `block` (not while a round is being recorded: a replay stages them itself)."""
+        if not self._recording:
+            self._call("stage_scalars", B.acco_stage_scalars, self.scalars,
+                       [B.acco_fold_adamw(self._hp(), self.step.value, total)], block)
+
     def stage1(self) -> None:
         shards = self._publish()
-        if self.fused_reduce:
+        if self.device_scalars:
+            # the library folds the scalars; the totals are this caller's to keep
+            total = sum(self._counts())
+            self._stage_scalars(0, total)
+            if self.fused_reduce:
+                self._call("reduce_estimate", B.acco_reduce_estimate_step_dev, self.theta, self.m,
+                           self.v, self.gsum, shards, self.scalars, 0,
+                           theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
+            else:
+                self._call("reduce_init", B.acco_reduce_shards, self.gsum, shards, False, n=self.n)
+                self._call("estimate", B.acco_estimate_step_dev, self.theta, self.m, self.v,
+                           self.gsum, self.scalars, 0, theta_tilde_bf16=self.theta_tilde_bf16,
+                           n=self.n)
+            self.total.value = total
+        elif self.fused_reduce:
             self._call("reduce_estimate", B.acco_reduce_estimate_step, self.theta, self.m, self.v,
                        self.gsum, shards, self._counts(), self.total, self._hp(), self.step.value,
                        theta_tilde_bf16=self.theta_tilde_bf16, n=self.n)
@@ -354,7 +391,22 @@ class ShardOwner:
     def stage2(self) -> None:
         shards = self._publish()
         out = self.theta_bf16 if self.fused_bf16_out else None
-        if self.fused_reduce:
+        if self.device_scalars:
+            total = self.total.value + sum(self._counts())
+            self._stage_scalars(1, total)
+            if self.fused_reduce:
+                self._call("reduce_commit_bf16" if out is not None else "reduce_commit",
+                           B.acco_reduce_commit_step_dev, self.theta, self.m, self.v, self.gsum,
+                           shards, self.scalars, 1, theta_bf16=out, n=self.n)
+            else:
+                self._call("reduce_accumulate", B.acco_reduce_shards, self.gsum, shards, True,
+                           n=self.n)
+                self._call("commit_bf16" if out is not None else "commit", B.acco_commit_step_dev,
+                           self.theta, self.m, self.v, self.gsum, self.scalars, 1, theta_bf16=out,
+                           n=self.n)
+            self.total.value = total
+            self.step.value += 1
+        elif self.fused_reduce:
             self._call("reduce_commit_bf16" if out is not None else "reduce_commit",
                        B.acco_reduce_commit_step, self.theta, self.m, self.v, self.gsum, shards,
                        self._counts(), self.total, self._hp(), self.step, theta_bf16=out, n=self.n)
@@ -369,3 +421,67 @@ class ShardOwner:
                 raise ValueError("the unfused parameter cast needs a planar theta")
             self._call("cast", B.acco_cast_params, self.theta_bf16, self.theta)
         self._end_stage()
+
+    def record_round(self, rows1, rows2) -> "RecordedRound":
+        """Record one whole round on fixed gradient buffers as a HIP graph; see RecordedRound."""
+        return RecordedRound(self, rows1, rows2)
+
+
+class RecordedRound:
+    """One round of a ShardOwner (both stages of Alg. 1's communication stream with the
+    accumulations that feed them) recorded once as a HIP graph.
+
+    rows1[w] / rows2[w]: worker w's micro-batch gradient buffers of the first / second half of
+    the round, in order.  The recording keeps their addresses and their number: before each
+    `replay` the caller refills the same buffers with the new gradients.  A replay is two
+    launches from the host (the scalars of that round's two updates into the owner's device
+    block, then the graph) whatever the number of kernels in the round; the update index, the
+    learning-rate schedule and the owner's host counters move on as in eager rounds, and the
+    values are those of eager rounds bit for bit.
+
+    Recording does no device work and leaves the owner's state and counters as they were.  Every
+    kernel of the round should have run once before (an eager round with the same options), so
+    that no code object is loaded for the first time inside the capture."""
+
+    def __init__(self, owner: ShardOwner, rows1, rows2):
+        torch = owner.torch
+        if not owner.device_scalars:
+            raise ValueError("record_round needs ShardOwner(device_scalars=True)")
+        if not all(owner._fresh):
+            raise ValueError("a round can only be recorded between rounds")
+        if len(rows1) != owner.W or len(rows2) != owner.W:
+            raise ValueError("one row per worker and stage")
+        self.owner = owner
+        self._rows = ([list(r) for r in rows1], [list(r) for r in rows2])   # keep them alive
+        saved = (owner.step.value, owner.total.value, [c.value for c in owner.count], owner.trace)
+        owner.trace, owner._recording = None, True
+        self.graph = torch.cuda.CUDAGraph()
+        try:
+            with torch.cuda.graph(self.graph):
+                owner.add_microbatch_rows(self._rows[0])
+                owner.stage1()
+                self.total1 = owner.total.value
+                owner.add_microbatch_rows(self._rows[1])
+                owner.stage2()
+                self.total2 = owner.total.value
+            self._end_counts = [c.value for c in owner.count]
+            self._totals = (self.total1, self.total2)
+            self._stage = B.ScalarStager(owner.scalars, 2)
+        finally:
+            owner._recording = False
+            owner.step.value, owner.total.value, owner.trace = saved[0], saved[1], saved[3]
+            for c, x in zip(owner.count, saved[2]):
+                c.value = x
+
+    def replay(self) -> None:
+        """Enqueue the recorded round on the current stream for the owner's next update."""
+        o = self.owner
+        if not all(o._fresh):
+            raise ValueError("an eager stage is under way")
+        step = o.step.value
+        self._stage(o._hp(), step, self._totals)
+        self.graph.replay()
+        for c, x in zip(o.count, self._end_counts):
+            c.value = x
+        o.total.value = self.total2
+        o.step.value = step + 1

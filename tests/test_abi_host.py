@@ -541,3 +541,84 @@ def test_layouts_of_interleaved_communication_buffers():
     assert com(vp(th), vp(m), vp(v), vp(g), out, 2, 0, cnt, tr, vp(base + 16 * blk), n, hp, sr,
                NONE, il, NONE) == B.ACCO_ERR_ALIAS
     assert red(vp(g), out, 2, 0, 0, 0, cnt, tr, NONE, lay(blk, 3), NONE) == B.ACCO_ERR_ARG
+
+
+def test_folded_scalars_are_the_double_precision_values_rounded_once():
+    """acco_fold_adamw against the scalars written out with Python's doubles and exact
+    fractions: grad scale, betas, their complements, step size with the first bias correction,
+    the second bias correction's reciprocal root, decay, epsilon."""
+    import math
+    from fractions import Fraction
+
+    import numpy as np
+    for lr, b1, b2, eps, wd in ((6e-4, 0.9, 0.95, 1e-8, 0.1), (1e-3, 0.0, 0.999, 1e-6, 0.0),
+                                (2e-5, 0.8, 0.9, 0.0, 0.05)):
+        hp = B.AdamW(lr, b1, b2, eps, wd)
+        for step, count in ((0, 1), (1, 3), (99, 32), (49_999, 7)):
+            got = list(B.acco_fold_adamw(hp, step, count).f)
+            t = step + 1
+            want = [1.0 / count, b1, b2, 1.0 - b1, 1.0 - b2, lr / (1.0 - b1 ** t),
+                    1.0 / math.sqrt(1.0 - b2 ** t), lr * wd, eps]
+            assert got[:9] == [float(np.float32(x)) for x in want], (hp, step, count)
+            assert got[9:] == [0.0] * 7
+            # the grad scale is the correctly rounded reciprocal (exact for powers of two)
+            assert abs(Fraction(got[0]) - Fraction(1, count)) <= Fraction(got[0]) * Fraction(1, 2 ** 24)
+    out = B.StepScalars()
+    L = B.lib()
+    good = ctypes.byref(GOOD)
+    assert L.acco_fold_adamw(good, 0, 1, NONE) == B.ACCO_ERR_NULL
+    assert L.acco_fold_adamw(NONE, 0, 1, ctypes.byref(out)) == B.ACCO_ERR_NULL
+    assert L.acco_fold_adamw(good, -1, 1, ctypes.byref(out)) == B.ACCO_ERR_ARG
+    assert L.acco_fold_adamw(good, 0, 0, ctypes.byref(out)) == B.ACCO_ERR_ARG
+    bad = B.AdamW(6e-4, 1.0, 0.95, 1e-8, 0.1)
+    assert L.acco_fold_adamw(ctypes.byref(bad), 0, 1, ctypes.byref(out)) == B.ACCO_ERR_ARG
+    assert ctypes.sizeof(B.StepScalars) == 64
+
+
+def test_device_scalar_entry_points_validation():
+    L = B.lib()
+    S = 0x90000                                    # the scalar block's "device" address
+    G = 0x70000
+    src = (B.StepScalars * 4)()
+    stage = L.acco_stage_scalars
+    assert stage(NONE, src, 1, NONE) == B.ACCO_ERR_NULL
+    assert stage(vp(S), NONE, 1, NONE) == B.ACCO_ERR_NULL
+    assert stage(vp(S), src, 0, NONE) == B.ACCO_ERR_SIZE
+    assert stage(vp(S), src, B.STAGE_BLOCKS_MAX + 1, NONE) == B.ACCO_ERR_SIZE
+    assert stage(vp(S + 8), src, 1, NONE) == B.ACCO_ERR_ALIGN
+
+    e, c = L.acco_estimate_step_dev, L.acco_commit_step_dev
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), NONE, 4, vp(S), NONE, NONE) == B.ACCO_ERR_NULL
+    assert e(NONE, vp(Bp), vp(C), vp(D), vp(E), 4, vp(S), NONE, NONE) == B.ACCO_ERR_NULL
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), -1, vp(S), NONE, NONE) == B.ACCO_ERR_SIZE
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, vp(S + 4), NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(A), 8, vp(S), NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), 64, vp(E + 32), NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert e(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, vp(S), NONE, NONE) == 0
+    assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), vp(Bp), vp(C), NONE, NONE, 4, vp(S), NONE, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), vp(A), vp(C), vp(D), NONE, 4, vp(S), NONE, NONE) == B.ACCO_ERR_ALIAS
+    # the scalar block may not lie inside anything the step writes; gsum is only read
+    for k, written in enumerate((A, Bp, C)):
+        assert c(vp(A), vp(Bp), vp(C), vp(D), NONE, 64, vp(written + 64), NONE, NONE) == B.ACCO_ERR_ALIAS, k
+    assert c(vp(A), vp(Bp), vp(C), vp(D), vp(E), 64, vp(E + 16), NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert c(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, vp(S), NONE, NONE) == 0
+
+    s2 = _shards(E, F)
+    re_, rc_ = L.acco_reduce_estimate_step_dev, L.acco_reduce_commit_step_dev
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), NONE, 2, 0, vp(G), 0, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, 4, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(G), 0, NONE, NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 65, 0, vp(G), 0, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 7, vp(G), 0, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_ARG
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), _shards(E, D), 2, 0, vp(G), 8, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(G), 64, vp(D + 16), NONE, NONE, NONE) == B.ACCO_ERR_ALIAS   # gsum is written
+    assert re_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(G), 0, vp(S), NONE, NONE, NONE) == 0
+    assert rc_(vp(A), vp(Bp), vp(C), vp(D), NONE, 2, 0, vp(G), 0, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_NULL
+    assert rc_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(G), 0, vp(S + 2), NONE, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert rc_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(E), 8, vp(S), NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert rc_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, vp(G), 64, vp(Bp + 128), NONE, NONE, NONE) == B.ACCO_ERR_ALIAS
+    lay = B.Layout(8, 32)
+    assert rc_(vp(A), vp(A + 32), vp(A + 64), vp(A + 96), s2, 2, 0, vp(G), 0, vp(S), ctypes.byref(lay), NONE, NONE) == 0
+    assert rc_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, 0, vp(S), NONE, NONE, NONE) == 0

@@ -33,7 +33,7 @@ def gpu_hyper(A, w):
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
                  bf16_acc=False, schedules=None, adopt=False, batched=False, interleaved=False,
-                 comm_block=16384):
+                 comm_block=16384, dev_scalars=False):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -45,7 +45,7 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
                          bf16_accumulate=bf16_acc,
                          lr_schedule=None if schedules is None else schedules[0],
                          adopt_first=adopt, batched=batched, interleaved_comm=interleaved,
-                         comm_block_elems=comm_block)
+                         comm_block_elems=comm_block, device_scalars=dev_scalars)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -132,6 +132,14 @@ def test_tiny_with_fused_publish_and_fused_reduce():
     run_workload(w, fused_reduce=True)
     run_workload(w, fused_publish=True, fused_reduce=True)
     run_workload(w, comm_bf16=False, fused_reduce=True, rounds=2)
+
+
+def test_tiny_with_step_scalars_in_device_memory():
+    w = synth.WORKLOADS["tiny"]
+    run_workload(w, dev_scalars=True)
+    run_workload(w, dev_scalars=True, fused_publish=True, fused_reduce=True, blocked=True,
+                 stash=True, batched=True)
+    run_workload(w, dev_scalars=True, comm_bf16=False, fused_reduce=True, rounds=2)
 
 
 def test_tiny_with_bf16_stash():
