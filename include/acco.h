@@ -54,7 +54,8 @@ extern "C" {
 typedef enum acco_status {
     ACCO_OK         = 0,
     ACCO_ERR_NULL   = -1, /* a required pointer is NULL                               */
-    ACCO_ERR_SIZE   = -2, /* n < 0, n > ACCO_MAX_ELEMS, workers outside 1..64         */
+    ACCO_ERR_SIZE   = -2, /* n < 0, n > ACCO_MAX_ELEMS, workers outside 1..64, a block  */
+                          /* count or slot index beyond its stated maximum            */
     ACCO_ERR_ALIGN  = -3, /* a device pointer is not 16-byte aligned                  */
     ACCO_ERR_ARG    = -4, /* bad hyper-parameter, count, step, dtype or flag          */
     ACCO_ERR_ALIAS  = -5, /* an output overlaps an input it must not overlap          */
@@ -384,6 +385,32 @@ int acco_reduce_commit_step_dev(float* theta, float* m, float* v, float* gsum,
                                 const acco_step_scalars_t* scalars_dev,
                                 const acco_layout_t* state_layout,
                                 const acco_layout_t* shard_layout, void* stream);
+
+/*
+ * acco_commit_step_dev for callers that cannot allocate device memory - code that runs where
+ * hipMalloc is not allowed (under a stream capture, in a serving loop that must not allocate,
+ * in a harness that forbids it) and so cannot own the scalar block the *_dev forms read.  The
+ * block lives in an array of the library's own instead (static device memory, 64 blocks =
+ * 4 KiB on every GPU the library runs on, held until the process ends).  The call enqueues two
+ * kernels on `stream` and nothing else - no allocation, free, memset, copy or synchronisation:
+ * the first puts *scalars_host (carried in its arguments) into block `slot`, the second is the
+ * committed step of acco_commit_step_dev reading that block.  Same values as acco_commit_step_dev
+ * with the same scalars.
+ *   scalars_host  host, in: one step's scalars from acco_fold_adamw; read before the call returns
+ *   slot          0 <= slot < ACCO_RESIDENT_SLOTS, else ACCO_ERR_SIZE.  All calls on one GPU
+ *                 share that GPU's array, and a block keeps what the last call put there: calls
+ *                 that use the same slot must be ordered (same stream, or events); calls that
+ *                 may overlap on one GPU must use different slots, or they race.
+ *   other arguments and errors as acco_commit_step_dev; no host counter is touched.
+ * The first call on a device looks up where that device's copy of the array lives
+ * (hipGetSymbolAddress); make that call outside any capture.
+ */
+#define ACCO_RESIDENT_SLOTS 64
+
+int acco_commit_step_resident(float* theta, float* m, float* v, const float* gsum,
+                              uint16_t* theta_bf16, int64_t n,
+                              const acco_step_scalars_t* scalars_host, int slot,
+                              const acco_layout_t* state_layout, void* stream);
 
 /*
  * Plain SGD with decoupled weight decay as Opt - the optimizer of the paper's convergence

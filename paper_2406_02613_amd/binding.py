@@ -29,7 +29,8 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_estimate_step", "acco_commit_step", "acco_reduce_estimate_step",
            "acco_reduce_commit_step", "acco_fold_adamw", "acco_stage_scalars",
            "acco_estimate_step_dev", "acco_commit_step_dev", "acco_reduce_estimate_step_dev",
-           "acco_reduce_commit_step_dev", "acco_sgd_estimate_step", "acco_sgd_commit_step",
+           "acco_reduce_commit_step_dev", "acco_commit_step_resident",
+           "acco_sgd_estimate_step", "acco_sgd_commit_step",
            "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
            "acco_set_resident_waves", "acco_reset_launch_settings")
 
@@ -107,6 +108,7 @@ def lib() -> ctypes.CDLL:
                                                     p, play, play, p]
         L.acco_reduce_commit_step_dev.argtypes = [p, p, p, p, ctypes.POINTER(p), ci, ci, p, i64, p,
                                                   play, play, p]
+        L.acco_commit_step_resident.argtypes = [p, p, p, p, p, i64, psc, ci, play, p]
         L.acco_sgd_estimate_step.argtypes = [p, p, p, p, i64, ctypes.POINTER(Sgd), i64, p]
         L.acco_sgd_commit_step.argtypes = [p, p, p, i64, ctypes.POINTER(Sgd), pi64, i64, p]
         L.acco_set_launch_shape.argtypes = [ctypes.c_char_p, ci, ci, ci]
@@ -542,6 +544,20 @@ def acco_reduce_commit_step_dev(theta, m, v, gsum, shards: Sequence, scalars_dev
         _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n, _scalars_ptr(scalars_dev, block),
         _lay(layout), _lay(sl), _stream())
     _check(rc, "acco_reduce_commit_step_dev")
+
+
+RESIDENT_SLOTS = 64
+
+
+def acco_commit_step_resident(theta, m, v, gsum, scalars: StepScalars, slot: int, *,
+                              theta_bf16=None, n: Optional[int] = None) -> None:
+    """acco_commit_step_dev with the scalar block held by the library (nothing to allocate)."""
+    import torch
+    st, n, layout = _state([theta, m, v, gsum], ["theta", "m", "v", "gsum"], n)
+    rc = lib().acco_commit_step_resident(st[0], st[1], st[2], st[3],
+                                         _opt(theta_bf16, torch.bfloat16, n, "theta_bf16"), n,
+                                         ctypes.byref(scalars), int(slot), _lay(layout), _stream())
+    _check(rc, "acco_commit_step_resident")
 
 
 def make_sgd(lr, weight_decay=0.0) -> Sgd:

@@ -845,6 +845,66 @@ ACCO_API int acco_commit_step_dev(float* theta, float* m, float* v, const float*
                          static_cast<hipStream_t>(stream));
 }
 
+// ------------------------------------------------------------------ resident scalar blocks
+
+// Scalar blocks held by the library itself, for the one entry point that takes no device block
+// from its caller.  Each device has its own copy of the array at its own address; in host code
+// the array's name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) uint32_t scratch[ACCO_RESIDENT_SLOTS * acco::kWordsPerBlock];
+
+namespace {
+
+std::atomic<uint32_t*> g_scratch_ptr[64];   // per device: where that device's copy lives
+
+// device address of block `slot` on the current device (looked up once per device)
+int resident_block(int slot, uint32_t** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return ACCO_ERR_DEVICE;
+    }
+    uint32_t* base = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (base == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return ACCO_ERR_DEVICE;
+        }
+        base = static_cast<uint32_t*>(p);
+        g_scratch_ptr[dev].store(base, std::memory_order_release);
+    }
+    *out = base + (int64_t)slot * kWordsPerBlock;
+    return ACCO_OK;
+}
+
+}  // namespace
+
+ACCO_API int acco_commit_step_resident(float* theta, float* m, float* v, const float* gsum,
+                                       uint16_t* theta_bf16, int64_t n,
+                                       const acco_step_scalars_t* scalars_host, int slot,
+                                       const acco_layout_t* state_layout, void* stream)
+{
+    if (int rc = check_n(n)) return rc;
+    if (scalars_host == nullptr) return ACCO_ERR_NULL;
+    if (slot < 0 || slot >= ACCO_RESIDENT_SLOTS) return ACCO_ERR_SIZE;
+    StateLayout L;
+    if (int rc = parse_layout(state_layout, &L)) return rc;
+    if (int rc = check_step_buffers(theta, m, v, gsum, nullptr, theta_bf16, n, L)) return rc;
+    if (n == 0) return ACCO_OK;
+    uint32_t* block = nullptr;
+    if (int rc = resident_block(slot, &block)) return rc;
+    hipStream_t  s = static_cast<hipStream_t>(stream);
+    StagedBlocks arg;
+    std::memset(&arg, 0, sizeof arg);
+    std::memcpy(arg.word, scalars_host, sizeof *scalars_host);
+    // every word of the block is rewritten, so nothing of an earlier call survives in it
+    hipLaunchKernelGGL(stage_kernel, dim3(1), dim3(64), 0, s, block, arg, kWordsPerBlock);
+    if (hipGetLastError() != hipSuccess) return ACCO_ERR_DEVICE;
+    return launch_commit(theta, m, v, gsum, theta_bf16, n, L,
+                         ScalarsFromDevice{reinterpret_cast<const AdamScalars*>(block)}, s);
+}
+
 ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint16_t* comm_bf16,
                                      int64_t n, int init, int keep_acc, int64_t* count,
                                      void* stream)
@@ -1185,7 +1245,7 @@ ACCO_API const char* acco_status_string(int status)
     switch (status) {
         case ACCO_OK: return "ACCO_OK";
         case ACCO_ERR_NULL: return "ACCO_ERR_NULL: a required pointer is NULL";
-        case ACCO_ERR_SIZE: return "ACCO_ERR_SIZE: element or worker count out of range";
+        case ACCO_ERR_SIZE: return "ACCO_ERR_SIZE: element, worker, block or slot count out of range";
         case ACCO_ERR_ALIGN: return "ACCO_ERR_ALIGN: device pointer not 16-byte aligned";
         case ACCO_ERR_ARG: return "ACCO_ERR_ARG: invalid hyper-parameter, count, step, dtype or flag";
         case ACCO_ERR_ALIAS: return "ACCO_ERR_ALIAS: output overlaps an input";

@@ -622,3 +622,24 @@ def test_device_scalar_entry_points_validation():
     lay = B.Layout(8, 32)
     assert rc_(vp(A), vp(A + 32), vp(A + 64), vp(A + 96), s2, 2, 0, vp(G), 0, vp(S), ctypes.byref(lay), NONE, NONE) == 0
     assert rc_(vp(A), vp(Bp), vp(C), vp(D), s2, 2, 0, NONE, 0, vp(S), NONE, NONE, NONE) == 0
+
+
+def test_resident_commit_step_validation():
+    L = B.lib()
+    r = L.acco_commit_step_resident
+    sc = B.acco_fold_adamw(GOOD, 0, 1)
+    ref = ctypes.byref(sc)
+    assert r(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, NONE, 0, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), vp(Bp), vp(C), NONE, NONE, 4, ref, 0, NONE, NONE) == B.ACCO_ERR_NULL
+    assert r(vp(A), vp(Bp), vp(C), vp(D), NONE, -1, ref, 0, NONE, NONE) == B.ACCO_ERR_SIZE
+    for slot in (-1, B.RESIDENT_SLOTS, 2 ** 31 - 1):
+        assert r(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, ref, slot, NONE, NONE) == B.ACCO_ERR_SIZE
+    assert "slot" in B.status_string(B.ACCO_ERR_SIZE)
+    assert r(vp(A + 4), vp(Bp), vp(C), vp(D), NONE, 0, ref, 0, NONE, NONE) == B.ACCO_ERR_ALIGN
+    assert r(vp(A), vp(A), vp(C), vp(D), NONE, 4, ref, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
+    assert r(vp(A), vp(Bp), vp(C), vp(D), vp(A), 4, ref, 0, NONE, NONE) == B.ACCO_ERR_ALIAS
+    bad = B.Layout(6, 24)
+    assert r(vp(A), vp(Bp), vp(C), vp(D), NONE, 0, ref, 0, ctypes.byref(bad), NONE) == B.ACCO_ERR_ARG
+    for slot in (0, B.RESIDENT_SLOTS - 1):
+        assert r(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, ref, slot, NONE, NONE) == 0
+    assert B.RESIDENT_SLOTS == 64
