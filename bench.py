@@ -179,6 +179,7 @@ def kernel_bytes_per_elem(name, workers):
         "reduce_commit": 12 + 4 + red + 12,        # theta,m,v,gsum + shards read; theta,m,v written
         "reduce_commit_bf16": 12 + 4 + red + 12 + 2,
     }
+    name = name.replace("@dev", "")                # the device-scalar form moves the same bytes
     if "*" in name:                                # "label*k": one launch over k workers
         base, k = name.split("*")
         return int(k) * kernel_bytes_per_elem(base, workers)
@@ -438,6 +439,8 @@ def _label_of(kernel_name, grid_size, n):
     """bench label of a dispatch; batched launches get their worker count from the grid."""
     for frag, label in KERNEL_LABELS:
         if frag in kernel_name:
+            if "ScalarsFromDevice" in kernel_name:            # the *_dev form of a step kernel
+                return label + "@dev"
             if label.endswith("*"):
                 per_lane = 8 if ("StashOp" in frag or "SecondPublishOp" in frag) else 4
                 one = -(-(n // per_lane) // 64) * 64          # work-items of one worker's row
@@ -471,10 +474,10 @@ def summarize_rocprof(raw):
                    f"workload: {cfg.get('workload', '?')}", "",
                    "Command (from /tmp with TMPDIR=/tmp on the MI355X box; $R = repository root):",
                    "  " + cmd(tag), "",
-                   f"{'kernel':72s} {'calls':>6s} {'avg_ns':>10s} {'min_ns':>10s} {'max_ns':>10s} {'%':>6s}"]
+                   f"{'kernel':96s} {'calls':>6s} {'avg_ns':>10s} {'min_ns':>10s} {'max_ns':>10s} {'%':>6s}"]
             rows = list(csv.DictReader(open(stats[0])))
             for r in rows[:28]:
-                out.append(f"{_short_kernel(r['Name'])[:72]:72s} {r['Calls']:>6s} "
+                out.append(f"{_short_kernel(r['Name'])[:96]:96s} {r['Calls']:>6s} "
                            f"{float(r['AverageNs']):10.0f} {r['MinNs']:>10s} {r['MaxNs']:>10s} "
                            f"{float(r['Percentage']):6.2f}")
             ks = line.get("kernels")
@@ -511,7 +514,8 @@ def summarize_rocprof(raw):
                     for k, v in tab.items():
                         out.append(f"  n={n_k:>11s} {k:12s} avg {v['avg_ms']:.4f} ms  {v['bytes_per_elem']:2d} B/elem"
                                    f"  {v['GB/s']:7.1f} GB/s  {100 * v['frac_of_peak']:.1f} % of 8 TB/s")
-            for key in ("two_stream", "base_entry_points_round", "adopted_first_gradient_round"):
+            for key in ("two_stream", "base_entry_points_round", "adopted_first_gradient_round",
+                        "recorded_graph_round"):
                 if isinstance(line.get(key), dict):
                     out += ["", f"{key}: " + json.dumps({k: v for k, v in line[key].items()
                                                          if k != "kernels"})]

@@ -35,9 +35,11 @@
  *     the update index).
  *   - Return value: ACCO_OK (0) or a negative acco_status.  On any error nothing
  *     is enqueued and no host counter is modified.
- *   - Thread-safe; no global mutable state besides cached device properties and the
+ *   - Thread-safe; no global mutable state besides cached device properties, the
  *     process-wide launch settings at the end of this header (each entry point's settings are
- *     one atomic word: a launch sees either the old set or the new one, never a mixture).
+ *     one atomic word: a launch sees either the old set or the new one, never a mixture), and
+ *     the 4 KiB device array that acco_commit_step_resident - and no other entry point -
+ *     stages its scalars in (its callers order or separate their calls by slot).
  */
 #ifndef ACCO_H
 #define ACCO_H

@@ -2,7 +2,8 @@
 bound on resident wavefronts, state layout, communication dtype, hyper-parameters, update index,
 micro-batch counts, which fused entry points are used, whether the first gradient is adopted in
 place, whether the workers' accumulation steps share launches, whether the communication
-buffers are interleaved) against the oracle's binary32 form: two
+buffers are interleaved, whether the step kernels take their scalars by value or from device
+memory) against the oracle's binary32 form: two
 rounds each, every output compared bit for bit."""
 import numpy as np
 import pytest
@@ -47,10 +48,11 @@ def test_random_configurations_are_bit_exact(seed):
             b16acc = (not f32comm) and rng.integers(0, 5) == 0
             ilv = (not b16acc) and bool(rng.integers(0, 2))
             cblk = int(rng.choice([8, 64, 4096, 16384]))
+            devsc = bool(np.random.default_rng(77 * seed + it).integers(0, 2))   # its own stream
             print(f"seed {seed} case {it}: n={n} W={W} shape={shape} bound={bound} "
                   f"blocked={blocked}/{block} f32comm={f32comm} hyper={hyper} step0={step0} "
                   f"stash={stash} adopt={adopt} publish={fp} reduce={fr} bf16acc={b16acc} "
-                  f"batched={batched} interleaved_comm={ilv}/{cblk}", flush=True)
+                  f"batched={batched} interleaved_comm={ilv}/{cblk} device_scalars={devsc}", flush=True)
             # every other case starts from a state no run of Adam need have produced (m and v
             # unrelated, |m|/sqrt(v) up to 1e3, zero and denormal v); all comparisons below are
             # bit for bit with the binary32 form, so no tolerance is involved
@@ -58,7 +60,8 @@ def test_random_configurations_are_bit_exact(seed):
             own = A.ShardOwner(n, W, A.make_hyper(*hyper), comm_bf16=not f32comm, fused_publish=fp,
                                fused_reduce=fr, blocked_state=blocked, block_elems=block,
                                bf16_stash=stash, bf16_accumulate=bool(b16acc), adopt_first=adopt,
-                               batched=batched, interleaved_comm=ilv, comm_block_elems=cblk)
+                               batched=batched, interleaved_comm=ilv, comm_block_elems=cblk,
+                               device_scalars=devsc)
             for name, x in (("theta", theta), ("m", m), ("v", v)):
                 own.set_state(name, torch.from_numpy(x.copy()).cuda())
             own.step.value = step0
