@@ -1,7 +1,8 @@
 """CPU oracle (TEST INFRASTRUCTURE ONLY) of the update schemes of the paper's Sec. 3.1-3.2 as
 one shard owner runs them: eq. (DDP), eq. (DPU), eq. (WP), eq. (ACCO), with Opt = AdamW or
 plain SGD.  ``params`` is what the computation stream differentiates next (fp32) and
-``params_bf16`` its bf16 copy."""
+``params_bf16`` its bf16 copy.  ``warmup_rounds``: undelayed (DDP) rounds before DPU's delayed
+updates start (the warm-up of the paper's delayed-update experiment, Sec. 4)."""
 from __future__ import annotations
 
 from typing import Optional
@@ -14,8 +15,10 @@ import oracle as O
 class OracleScheme:
     def __init__(self, theta: np.ndarray, workers: int, scheme: str, *, adamw: Optional[O.Hyper] = None,
                  sgd_lr: float = 0.0, sgd_wd: float = 0.0, comm_dtype: str = "bf16",
-                 precision: str = "f64"):
+                 precision: str = "f64", warmup_rounds: int = 0):
         assert scheme in ("acco", "ddp", "dpu", "wp")
+        assert warmup_rounds == 0 or scheme == "dpu"
+        self.warmup_rounds, self.rounds_done = warmup_rounds, 0
         n = theta.size
         self.scheme, self.W, self.precision, self.comm_dtype = scheme, workers, precision, comm_dtype
         self.adamw, self.sgd_lr, self.sgd_wd = adamw, sgd_lr, sgd_wd
@@ -78,7 +81,7 @@ class OracleScheme:
             self._reduce(True)
             self._commit()
             self._export_theta()
-        elif self.scheme == "ddp":
+        elif self.scheme == "ddp" or self.rounds_done < self.warmup_rounds:
             self._reduce(False)
             self._commit()
             self._export_theta()
@@ -90,3 +93,4 @@ class OracleScheme:
             self._reduce(False)
             self._commit()
             self._estimate()
+        self.rounds_done += 1

@@ -9,6 +9,10 @@
 with Opt = AdamW or plain SGD (the optimizer of the convergence propositions).  Host-side
 ordering of C-ABI calls only; ``params_f32`` / ``params_bf16`` are the parameters the
 computation stream differentiates next (theta~ in the paper's notation, or theta for ddp).
+
+``warmup_rounds`` (dpu only): the first rounds run undelayed, as ddp, before the delayed
+updates start - the warm-up the paper's experiment on the impact of delayed updates varies
+(Sec. 4, none / 40 / 500 steps).
 """
 from __future__ import annotations
 
@@ -21,10 +25,14 @@ SCHEMES = ("acco", "ddp", "dpu", "wp")
 
 class SchemeOwner:
     def __init__(self, n: int, workers: int, scheme: str, opt, *, comm_bf16: bool = True,
-                 device="cuda"):
+                 device="cuda", warmup_rounds: int = 0):
         import torch
         if scheme not in SCHEMES:
             raise ValueError(f"scheme must be one of {SCHEMES}")
+        if warmup_rounds < 0 or (warmup_rounds and scheme != "dpu"):
+            raise ValueError("warmup_rounds: a non-negative number of undelayed rounds, dpu only")
+        self.warmup_rounds = int(warmup_rounds)
+        self.rounds_done = 0
         if not isinstance(opt, (B.AdamW, B.Sgd)):
             raise TypeError("opt: an AdamW or Sgd hyper-parameter struct")
         self.torch, self.scheme, self.opt = torch, scheme, opt
@@ -114,7 +122,7 @@ class SchemeOwner:
             self._reduce(True)                            # onto the retained first-half sum
             self._commit()
             self._export_theta()
-        elif self.scheme == "ddp":
+        elif self.scheme == "ddp" or self.rounds_done < self.warmup_rounds:
             self._reduce(False)
             self._commit()
             self._export_theta()
@@ -126,3 +134,4 @@ class SchemeOwner:
             self._reduce(False)
             self._commit()
             self._estimate()                              # second Opt step on the same gradient
+        self.rounds_done += 1

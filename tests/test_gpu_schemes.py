@@ -82,6 +82,30 @@ def test_gd_schemes_follow_the_closed_forms_and_the_oracle(acco, scheme):
     assert np.max(np.abs(g.params_f32.cpu().numpy() - want_p)) <= 2e-6 * scale
 
 
+@pytest.mark.parametrize("warm", [1, 4, 40])
+def test_dpu_with_warm_up_rounds_matches_the_oracle_and_its_closed_form(acco, warm):
+    from test_oracle_schemes import dpu_warm_closed_form
+    a, x0 = quad_setup(n=60_007, seed=8)
+    eta, T = 0.2, 12
+    ad = dev(a)
+    g = acco.SchemeOwner(a.size, 1, "dpu", acco.make_sgd(eta), comm_bf16=False, warmup_rounds=warm)
+    g.set_theta(dev(x0))
+    o = OracleScheme(x0, 1, "dpu", sgd_lr=eta, comm_dtype="f32", precision="f32",
+                     warmup_rounds=warm)
+    run_quadratic(g, "dpu", a, T, lambda p: ad * p)
+    run_quadratic(o, "dpu", a, T, lambda p: (a * p).astype(np.float32))
+    torch.cuda.synchronize()
+    assert g.step.value == o.step == T
+    assert bit_mismatches(g.theta.cpu().numpy(), o.theta) == 0
+    assert bit_mismatches(g.params_f32.cpu().numpy(), o.params) == 0
+    want_t, want_p = dpu_warm_closed_form(a, x0, eta, T, warm)
+    scale = np.abs(x0).max()
+    assert np.max(np.abs(g.theta.cpu().numpy() - want_t)) <= 2e-6 * scale
+    assert np.max(np.abs(g.params_f32.cpu().numpy() - want_p)) <= 2e-6 * scale
+    with pytest.raises(ValueError):
+        acco.SchemeOwner(8, 1, "wp", acco.make_sgd(eta), warmup_rounds=2)
+
+
 def test_acco_gd_with_distinct_initial_estimate(acco):
     a, x0 = quad_setup(n=50_001, seed=3)
     rng = np.random.default_rng(4)

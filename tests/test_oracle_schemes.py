@@ -88,6 +88,43 @@ def test_gd_on_a_quadratic_follows_the_closed_form_recursion(scheme, precision):
     assert all(np.max(np.abs(w - mine)) > 1e-3 * scale for w in others)
 
 
+def dpu_warm_closed_form(a, x0, eta, T, warm):
+    """DPU after `warm` undelayed rounds: plain GD for `warm` rounds, then the first delayed round
+    still differentiates the parameters the last undelayed round handed out, and from there on
+    theta_{t+1} = theta_t - eta a theta_{t-1}."""
+    a = a.astype(np.float64)
+    out_t, out_p = np.empty(a.size), np.empty(a.size)
+    for k in range(a.size):
+        ea = eta * a[k]
+        th = (1 - ea) ** min(warm, T) * float(x0[k])
+        if T <= warm:
+            out_t[k] = out_p[k] = th
+            continue
+        s = np.array([(1 - ea) * th, th])              # after the first delayed round
+        s = np.linalg.matrix_power(np.array([[1.0, -ea], [1.0, 0.0]]), T - warm - 1) @ s
+        out_t[k], out_p[k] = s[0], s[1]
+    return out_t, out_p
+
+
+@pytest.mark.parametrize("warm", [0, 1, 5, 30])
+def test_dpu_with_undelayed_warm_up_rounds_follows_its_closed_form(warm):
+    a, x0 = quad_setup(seed=6)
+    eta, T = 0.2, 25
+    o = OracleScheme(x0, 1, "dpu", sgd_lr=eta, comm_dtype="f32", warmup_rounds=warm)
+    run_quadratic(o, "dpu", a, T, lambda p: (a * p).astype(np.float32))
+    want_t, want_p = dpu_warm_closed_form(a, x0, eta, T, warm)
+    scale = np.abs(x0).max()
+    assert np.max(np.abs(o.theta - want_t)) <= 2e-6 * scale
+    assert np.max(np.abs(o.params - want_p)) <= 2e-6 * scale
+    # no warm-up is the plain scheme; warm-up past the horizon is DDP
+    if warm == 0:
+        assert np.allclose(want_t, closed_form("dpu", a, x0, eta, T)[0], rtol=0, atol=1e-12)
+    if warm >= T:
+        assert np.allclose(want_t, closed_form("ddp", a, x0, eta, T)[0], rtol=0, atol=1e-12)
+    else:
+        assert np.max(np.abs(want_t - closed_form("ddp", a, x0, eta, T)[0])) > 1e-6 * scale
+
+
 def test_acco_gd_with_distinct_initial_estimate_and_the_propositions_bound():
     # Prop. GD allows theta~_0 != theta_0; its bound on the summed squared gradient norms holds
     a, x0 = quad_setup(seed=3)
