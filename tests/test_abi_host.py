@@ -643,3 +643,25 @@ def test_resident_commit_step_validation():
     for slot in (0, B.RESIDENT_SLOTS - 1):
         assert r(vp(A), vp(Bp), vp(C), vp(D), vp(E), 0, ref, slot, NONE, NONE) == 0
     assert B.RESIDENT_SLOTS == 64
+
+
+def test_header_is_plain_c_and_the_library_is_callable_from_c(tmp_path):
+    """include/acco.h as a strict C99 (and C++17) translation unit, and a C program linked
+    against libacco.so that walks one round's host bookkeeping with n == 0."""
+    import subprocess
+    from paper_2406_02613_amd import build
+    inc = os.path.join(ROOT, "include")
+    src = os.path.join(ROOT, "tests", "c", "abi_from_c.c")
+    libdir = os.path.dirname(build.ACCO_SO)
+    exe = str(tmp_path / "abi_from_c")
+    rocm = "/opt/rocm/lib"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, src,
+                    "-o", exe, "-L", libdir, "-lacco", f"-Wl,-rpath,{libdir}",
+                    f"-Wl,-rpath-link,{rocm}", f"-Wl,-rpath,{rocm}"], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stderr
+    assert "acco C ABI ok" in out.stdout
+    cpp = tmp_path / "hdr.cpp"
+    cpp.write_text('#include "acco.h"\nint main() { return acco_version() > 0 ? 0 : 1; }\n')
+    subprocess.run(["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc,
+                    "-fsyntax-only", str(cpp)], check=True)
