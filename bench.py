@@ -103,6 +103,10 @@ def parse():
                          "and steadier, the publishing kernels slower)")
     ap.add_argument("--comm-block-elems", type=int, default=16384,
                     help="elements per block of the interleaved communication buffers")
+    ap.add_argument("--no-arena", action="store_true",
+                    help="plain allocations instead of one arena with the buffers placed by "
+                         "memory class (what the kernels read together in one class of the HBM, "
+                         "their outputs in another)")
     ap.add_argument("--per-worker-launches", action="store_true",
                     help="one accumulate launch per worker and micro-batch instead of one launch "
                          "for all workers that are at the same point of their accumulation")
@@ -572,8 +576,9 @@ def summarize_rocprof(raw):
     return 0 if wrote else 1
 
 
-def make_grads(torch, synth, w):
-    """Every micro-batch gradient of one round, resident in HBM: grads[stage][worker][mb]."""
+def make_grads(torch, synth, w, owner=None):
+    """Every micro-batch gradient of one round, resident in HBM: grads[stage][worker][mb].
+    With an owner that places its buffers (an arena), the gradients come from it too."""
     grads = {}
     n_bufs = 0
     for st in (synth.STAGE_TILDE, synth.STAGE_FULL):
@@ -581,7 +586,8 @@ def make_grads(torch, synth, w):
         for wk in range(w.workers):
             row = []
             for mb in range(w.stage_counts(0, st)[wk]):
-                g = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+                g = (torch.empty(w.n, dtype=torch.bfloat16, device="cuda") if owner is None
+                     else owner.new_gradient_buffer(first=(mb == 0)))
                 synth.device_grad_bf16(g, w.grad_spec(0, st, wk, mb), 0)
                 row.append(g)
                 n_bufs += 1
@@ -736,8 +742,16 @@ def main():
     batched = not args.per_worker_launches
     main_opts["interleaved_comm"] = args.interleaved_comm and not (args.bf16_accumulate
                                                                    or args.base_path)
+    n_grad_bufs = sum(w.microbatches(0, k) for k in range(w.workers))
+    arena = None
+    if not args.no_arena:
+        # one allocation for every buffer of the round, large enough to span the memory classes
+        need = w.n * (16 + 4 + w.workers * (2 + 2 + 4) + 2 * n_grad_bufs)
+        free = torch.cuda.mem_get_info()[0]
+        arena = A.HbmArena(min(int(0.82 * free), max(int(2.2 * need), 100 << 30)))
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
+                         arena=arena, gradient_buffers=n_grad_bufs,
                          blocked_state=blocked, block_elems=args.block_elems,
                          bf16_stash=not args.bf16_accumulate,        # allocate the stash buffers
                          bf16_accumulate=args.bf16_accumulate, batched=batched,
@@ -749,7 +763,7 @@ def main():
     w.device_theta(scratch[0])                        # a planar scratch the round overwrites
     owner.set_state("theta", scratch[0])
 
-    grads, n_bufs = make_grads(torch, synth, w)
+    grads, n_bufs = make_grads(torch, synth, w, owner)
 
     if args.calibrate_copy:
         scratch[1].copy_(scratch[0])           # planar fp32: 4n bytes read, 4n bytes written
@@ -968,6 +982,9 @@ def main():
                    "communication_buffers": (f"interleaved in blocks of {args.comm_block_elems} "
                                              "elements" if main_opts["interleaved_comm"]
                                              else "planar, one allocation per worker"),
+                   "placement": ("one arena, buffers placed by memory class: " + arena.describe()
+                                 + "; classes of the roles: " + json.dumps(owner._roles)
+                                 if arena is not None else "plain allocations"),
                    "launches_per_step": sum(k["calls_per_step"] for k in kernels.values()),
                    "bytes_per_elem_per_step": bytes_per_round,
                    "host_wall_ms_per_step": wall * 1e3 / args.steps,

@@ -11,6 +11,7 @@ from .binding import (ACCO_BF16, ACCO_F32, AccoError, AdamW, Counter, acco_accum
                       version)
 from .shard import RecordedRound, ShardOwner
 from .state import BlockedState, InterleavedShards
+from .arena import HbmArena
 from .two_stream import TwoStreamOwner
 from .schemes import SchemeOwner, SCHEMES
 from . import layout
@@ -21,4 +22,4 @@ __all__ = ["ACCO_BF16", "ACCO_F32", "AccoError", "AdamW", "Counter", "acco_accum
            "acco_cast_params", "acco_commit_step", "acco_estimate_step",
            "acco_lr_cosine", "acco_reduce_commit_step", "acco_reduce_estimate_step", "acco_reduce_shards",
            "acco_sgd_commit_step", "acco_sgd_estimate_step", "make_sgd", "Sgd", "SchemeOwner", "SCHEMES", "BlockedState", "InterleavedShards", "TwoStreamOwner",
-           "make_hyper", "set_launch_shape", "set_resident_waves", "reset_launch_settings", "status_string", "version", "ShardOwner", "RecordedRound", "layout"]
+           "make_hyper", "set_launch_shape", "set_resident_waves", "reset_launch_settings", "status_string", "version", "ShardOwner", "RecordedRound", "HbmArena", "layout"]

@@ -31,7 +31,7 @@ EXPORTS = ("acco_accumulate", "acco_accumulate_publish", "acco_accumulate_first"
            "acco_estimate_step_dev", "acco_commit_step_dev", "acco_reduce_estimate_step_dev",
            "acco_reduce_commit_step_dev", "acco_commit_step_resident",
            "acco_sgd_estimate_step", "acco_sgd_commit_step",
-           "acco_lr_cosine", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
+           "acco_lr_cosine", "acco_hbm_classify", "acco_probe_copy", "acco_probe_triad", "acco_status_string", "acco_version", "acco_set_launch_shape",
            "acco_set_resident_waves", "acco_reset_launch_settings")
 
 
@@ -117,6 +117,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).restype = ci
         L.acco_reset_launch_settings.argtypes = []
         L.acco_reset_launch_settings.restype = None
+        L.acco_hbm_classify.argtypes = [p, i64, i64, i64, p, ctypes.POINTER(ctypes.c_int32), i64,
+                                        ctypes.POINTER(ctypes.c_int32), p]
         L.acco_probe_copy.argtypes = [p, p, i64, p]
         L.acco_probe_triad.argtypes = [p, p, p, p, i64, p]
         L.acco_lr_cosine.restype = ctypes.c_double
@@ -591,6 +593,22 @@ def acco_lr_cosine(base_lr: float, min_lr: float, step: int, warmup_steps: int,
                    total_steps: int) -> float:
     return float(lib().acco_lr_cosine(float(base_lr), float(min_lr), int(step), int(warmup_steps),
                                       int(total_steps)))
+
+
+def acco_hbm_classify(region, step_bytes: int, probe_bytes: int, scratch):
+    """Memory class of every position of `region` (a contiguous uint8 device tensor):
+    (classes, n_classes), classes[k] for the probe_bytes at offset k * step_bytes."""
+    import torch
+    nbytes = region.numel()
+    base = _dev(region, torch.uint8, nbytes, "region")
+    count = (nbytes - int(probe_bytes)) // int(step_bytes) + 1 if nbytes >= probe_bytes else 0
+    out = (ctypes.c_int32 * max(count, 1))()
+    ncls = ctypes.c_int32(0)
+    rc = lib().acco_hbm_classify(base, nbytes, int(step_bytes), int(probe_bytes),
+                                 _dev(scratch, torch.uint8, int(probe_bytes), "scratch"), out,
+                                 count, ctypes.byref(ncls), _stream())
+    _check(rc, "acco_hbm_classify")
+    return list(out[:count]), int(ncls.value)
 
 
 def acco_probe_copy(dst, src) -> None:

@@ -2,6 +2,7 @@
 // counter bookkeeping, folding of the AdamW scalars, launch geometry.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdint>
@@ -1224,6 +1225,127 @@ ACCO_API int acco_probe_triad(float* a, float* b, float* c, const float* d, int6
             if (overlap(arr[i], n * 4, arr[j], n * 4)) return ACCO_ERR_ALIAS;
     if (n == 0) return ACCO_OK;
     return launch(kProbe, ProbeTriadOp{a, b, c, d}, n, static_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------ memory classes
+
+namespace {
+
+struct PairTimer {
+    hipEvent_t  e0 = nullptr, e1 = nullptr;
+    hipStream_t stream;
+    uint32_t*   out;
+    int64_t     words;
+    bool        ok = true;
+
+    PairTimer(hipStream_t s, uint32_t* o, int64_t w) : stream(s), out(o), words(w)
+    {
+        ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+    }
+    ~PairTimer()
+    {
+        if (e0 != nullptr) (void)hipEventDestroy(e0);
+        if (e1 != nullptr) (void)hipEventDestroy(e1);
+    }
+    // fastest of `reps` timed launches reading at a and b (ms); < 0 on a runtime error
+    float time(const uint32_t* a, const uint32_t* b, int reps)
+    {
+        float best = -1.0f;
+        for (int r = 0; r <= reps && ok; ++r) {   // launch 0 is a warm-up
+            ok = ok && hipEventRecord(e0, stream) == hipSuccess;
+            ok = ok && launch(kSecond, ProbePairOp{out, a, b}, words, stream) == ACCO_OK;
+            ok = ok && hipEventRecord(e1, stream) == hipSuccess;
+            ok = ok && hipEventSynchronize(e1) == hipSuccess;
+            float ms = 0.0f;
+            ok       = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (ok && r > 0 && (best < 0.0f || ms < best)) best = ms;
+        }
+        return ok ? best : -1.0f;
+    }
+};
+
+constexpr float kSlowPair = 1.045f;   // the two populations measured 8-10 % apart on MI355X
+
+}  // namespace
+
+ACCO_API int acco_hbm_classify(const void* base, int64_t bytes, int64_t step_bytes,
+                               int64_t probe_bytes, void* scratch, int32_t* classes,
+                               int64_t count, int32_t* n_classes, void* stream)
+{
+    if (base == nullptr || scratch == nullptr || classes == nullptr || n_classes == nullptr)
+        return ACCO_ERR_NULL;
+    if (!aligned16(base) || !aligned16(scratch)) return ACCO_ERR_ALIGN;
+    if (probe_bytes < 4096 || probe_bytes % 4096 != 0 || probe_bytes > ((int64_t)1 << 34) ||
+        step_bytes < 4096 || step_bytes % 4096 != 0 || bytes < probe_bytes)
+        return ACCO_ERR_SIZE;
+    if (count != (bytes - probe_bytes) / step_bytes + 1 || count > ((int64_t)1 << 20))
+        return ACCO_ERR_SIZE;
+    if (overlap(base, bytes, scratch, probe_bytes)) return ACCO_ERR_ALIAS;
+
+    const char* p0 = static_cast<const char*>(base);
+    auto        at = [&](int64_t k) { return reinterpret_cast<const uint32_t*>(p0 + k * step_bytes); };
+    PairTimer   timer(static_cast<hipStream_t>(stream), static_cast<uint32_t*>(scratch),
+                      probe_bytes / 4);
+    if (!timer.ok) return ACCO_ERR_DEVICE;
+    for (int64_t k = 0; k < count; ++k) classes[k] = -1;
+    if (count == 1) {
+        classes[0] = 0;
+        *n_classes = 1;
+        return ACCO_OK;
+    }
+    // what a pair in ONE class takes: the median over pairs of neighbouring positions (classes
+    // are tens of GiB long, so nearly all neighbours share one)
+    float   cal[12];
+    int     ncal = 0;
+    const int64_t stride = count > 24 ? (count - 1) / 12 : 1;
+    for (int64_t k = 0; k + 1 < count && ncal < 12; k += stride) {
+        const float t = timer.time(at(k), at(k + 1), 3);
+        if (t < 0.0f) return ACCO_ERR_DEVICE;
+        cal[ncal++] = t;
+    }
+    for (int i = 1; i < ncal; ++i)
+        for (int j = i; j > 0 && cal[j] < cal[j - 1]; --j) std::swap(cal[j], cal[j - 1]);
+    const float fast = cal[ncal / 2];
+
+    // first fit against one reference position per class found so far
+    int64_t refs[64];
+    int     nref = 0;
+    for (int64_t k = 0; k < count; ++k) {
+        int found = -1;
+        for (int c = 0; c < nref && found < 0; ++c) {
+            if (refs[c] == k) {
+                found = c;
+                break;
+            }
+            const float t = timer.time(at(refs[c]), at(k), 3);
+            if (t < 0.0f) return ACCO_ERR_DEVICE;
+            if (t < fast * kSlowPair) found = c;
+        }
+        if (found < 0) {
+            if (nref == 64) return ACCO_ERR_DEVICE;   // timings too erratic to classify
+            refs[nref] = k;
+            found      = nref++;
+        }
+        classes[k] = found;
+    }
+    // a lone position between two neighbours of one class is a timing hiccup
+    for (int64_t k = 1; k + 1 < count; ++k)
+        if (classes[k - 1] == classes[k + 1] && classes[k] != classes[k - 1]) classes[k] = classes[k - 1];
+    // number the classes by size, largest first
+    int64_t size[64] = {0};
+    int     order[64], rank[64];
+    for (int64_t k = 0; k < count; ++k) size[classes[k]] += 1;
+    for (int c = 0; c < nref; ++c) order[c] = c;
+    for (int i = 1; i < nref; ++i)
+        for (int j = i; j > 0 && size[order[j]] > size[order[j - 1]]; --j) std::swap(order[j], order[j - 1]);
+    int used = 0;
+    for (int i = 0; i < nref; ++i) {
+        rank[order[i]] = i;
+        if (size[order[i]] > 0) used = i + 1;
+    }
+    for (int64_t k = 0; k < count; ++k) classes[k] = rank[classes[k]];
+    *n_classes = used;
+    return ACCO_OK;
 }
 
 ACCO_API double acco_lr_cosine(double base_lr, double min_lr, int64_t step, int64_t warmup_steps,

@@ -798,6 +798,30 @@ struct ProbeCopyOp {
     __device__ __forceinline__ void scalar(int64_t j) const { dst[j] = src[j]; }
 };
 
+// two streams read, one written (out = a ^ b, 16 bytes per lane): the access pattern of a
+// second micro-batch, with no floating point; what acco_hbm_classify times
+struct ProbePairOp {
+    static constexpr int kElems = 4;   // "elements" here are 4-byte words: one u4 per lane
+    uint32_t*            out;
+    const uint32_t*      a;
+    const uint32_t*      b;
+    struct In {
+        u4 a, b;
+    };
+    __device__ __forceinline__ In load(int64_t i) const
+    {
+        In in;
+        in.a = ld(reinterpret_cast<const u4*>(a) + i);
+        in.b = ld(reinterpret_cast<const u4*>(b) + i);
+        return in;
+    }
+    __device__ __forceinline__ void apply(int64_t i, const In& in) const
+    {
+        st(reinterpret_cast<u4*>(out) + i, in.a ^ in.b);
+    }
+    __device__ __forceinline__ void scalar(int64_t j) const { out[j] = a[j] ^ b[j]; }
+};
+
 // four fp32 arrays read, three of them written back in place (a += d, b += d, c += d)
 struct ProbeTriadOp {
     static constexpr int kElems = 4;

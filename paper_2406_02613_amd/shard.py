@@ -37,6 +37,11 @@ Options that give the same values with fewer bytes over HBM:
                  kernels stream them faster and at a speed that does not depend on where W
                  separate buffers happen to lie, the publishing kernels write them slower.
                  Every write to them goes through acco_accumulate_batch, which takes the layout.
+  arena          an arena.HbmArena to take every buffer from, placed by memory class: what the
+                 step kernels read together (state, communication buffers) in one class, what
+                 the accumulation kernels read together (accumulators, stashes, and the
+                 gradients the caller gets from ``new_gradient_buffer``) in another, the bf16
+                 outputs in a third.  Placement only: same values.
   device_scalars the two AdamW steps read their folded scalars from a small device block that
                  the owner fills before each stage (acco_fold_adamw, acco_stage_scalars, the
                  *_dev step entry points): same values; what it allows is `record_round`, a whole
@@ -60,10 +65,21 @@ class ShardOwner:
                  block_elems: int = 8192, bf16_stash: bool = False,
                  bf16_accumulate: bool = False, lr_schedule=None, adopt_first: bool = False,
                  batched: bool = False, interleaved_comm: bool = False,
-                 comm_block_elems: int = 16384, device_scalars: bool = False):
+                 comm_block_elems: int = 16384, device_scalars: bool = False, arena=None,
+                 gradient_buffers: int = 0):
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
+        # gradient_buffers: how many n-element bf16 gradient buffers the caller will ask
+        # new_gradient_buffer for (only used to decide which class gets which role)
+        self.arena = arena
+        if arena is not None:
+            from .arena import plan_roles
+            n_, W_ = int(n), int(workers)
+            self._roles = plan_roles(arena, {
+                "owner": 16 * n_ + (2 * n_ * W_ if comm_bf16 else 0),
+                "compute": (0 if bf16_accumulate else 4 * n_ * W_) + 2 * n_ * W_
+                + 2 * n_ * int(gradient_buffers)})
         # optional: lr_schedule(step) -> learning rate of update number `step` (0-based), e.g.
         # lambda t: acco_lr_cosine(6e-4, 0.0, t, 0, 50000); both stages of a round use the
         # rate of the update they estimate / commit
@@ -81,32 +97,33 @@ class ShardOwner:
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self.state = None
+        self._dev, self._comm_block = dev, int(comm_block_elems)
         if blocked_state:
             # theta, m, v, gsum interleaved block by block in one buffer (see state.py)
             from .state import BlockedState
-            self.state = BlockedState(n, block_elems, dev)
+            self.state = BlockedState(n, block_elems, dev, alloc=None if arena is None else (
+                lambda numel, dt: self._alloc("owner", numel, dt, zero=True)))
             self.theta, self.m, self.v, self.gsum = (self.state.theta, self.state.m,
                                                      self.state.v, self.state.gsum)
         else:
-            self.theta = torch.empty(n, dtype=f32, device=dev)
-            self.m = torch.zeros(n, dtype=f32, device=dev)
-            self.v = torch.zeros(n, dtype=f32, device=dev)
-            self.gsum = torch.empty(n, dtype=f32, device=dev)
-        self.acc: List = ([] if bf16_accumulate else
-                          [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)])
+            self.theta = self._alloc("owner", n, f32)
+            self.m = self._alloc("owner", n, f32, zero=True)
+            self.v = self._alloc("owner", n, f32, zero=True)
+            self.gsum = self._alloc("owner", n, f32)
         # the communication buffers: W separate ones and / or the interleaved blocks of one
         # buffer, each allocated when first selected
-        self._dev, self._comm_block = dev, int(comm_block_elems)
         self._comm_planar: Optional[List] = None
         self._comm_slab = None
         self.interleaved_comm = False
         self.comm: List = []
         self._select_comm(bool(interleaved_comm))
-        self._own_stash: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
+        self._own_stash: List = ([self._alloc("compute", n, bf16) for _ in range(workers)]
                                  if self.bf16_stash and not self.adopt_first else [None] * workers)
         self.stash: List = list(self._own_stash)
-        self.theta_tilde_bf16 = torch.empty(n, dtype=bf16, device=dev)
-        self.theta_bf16 = torch.empty(n, dtype=bf16, device=dev)
+        self.acc: List = ([] if bf16_accumulate else
+                          [self._alloc("compute", n, f32) for _ in range(workers)])
+        self.theta_tilde_bf16 = self._alloc("out", n, bf16)
+        self.theta_bf16 = self._alloc("out", n, bf16)
         self.count = [B.Counter(0) for _ in range(workers)]   # N_i of the running accumulation
         self.total = B.Counter(0)                             # micro-batches summed in gsum
         self.step = B.Counter(0)                              # committed updates
@@ -123,6 +140,23 @@ class ShardOwner:
         self._select_scalars(bool(device_scalars))
         self._recording = False
 
+    def _alloc(self, role: str, numel: int, dtype, zero: bool = False):
+        """A flat buffer for `role` ("owner", "compute", "out"): from the arena, in that role's
+        memory class, or a plain allocation without one."""
+        if self.arena is None:
+            make = self.torch.zeros if zero else self.torch.empty
+            return make(int(numel), dtype=dtype, device=self._dev)
+        return self.arena.alloc(numel, dtype, self._roles[role], zero=zero)
+
+    def new_gradient_buffer(self, first: bool = False):
+        """An n-element bf16 buffer for a micro-batch gradient, placed where the accumulation
+        kernels read it fastest when there is an arena: next to the stashes and accumulators
+        it is added to.  ``first``: the buffer will only ever hold the first micro-batch of an
+        accumulation; with the bf16 stash that one is merely copied, read together with nothing,
+        so it need not take room in that class."""
+        role = "out" if first and self.bf16_stash and not self.adopt_first else "compute"
+        return self._alloc(role, self.n, self.torch.bfloat16)
+
     def _select_scalars(self, on: bool) -> None:
         if on and self.scalars is None:
             self.scalars = self.torch.zeros(2 * 16, dtype=self.torch.float32, device=self._dev)
@@ -138,12 +172,15 @@ class ShardOwner:
         if interleaved:
             if self._comm_slab is None:
                 from .state import InterleavedShards
-                self._comm_slab = InterleavedShards(self.n, self.W, self._comm_block, self._dev)
+                self._comm_slab = InterleavedShards(
+                    self.n, self.W, self._comm_block, self._dev,
+                    alloc=None if self.arena is None else (
+                        lambda numel, dt: self._alloc("owner", numel, dt, zero=True)))
             self.comm = list(self._comm_slab.shards)
         else:
             if self._comm_planar is None:
-                self._comm_planar = [self.torch.empty(self.n, dtype=self.torch.bfloat16,
-                                                      device=self._dev) for _ in range(self.W)]
+                self._comm_planar = [self._alloc("owner", self.n, self.torch.bfloat16)
+                                     for _ in range(self.W)]
             self.comm = self._comm_planar
 
     def comm_planar(self, w: int):

@@ -12,13 +12,18 @@ DEFAULT_BLOCK_ELEMS = 8192      # 32 KiB per component: the fastest of 1 Ki .. 1
 
 
 class BlockedState:
-    def __init__(self, n: int, block_elems: int = DEFAULT_BLOCK_ELEMS, device="cuda"):
+    def __init__(self, n: int, block_elems: int = DEFAULT_BLOCK_ELEMS, device="cuda", alloc=None):
+        """alloc(numel, dtype) -> zeroed flat tensor, for a caller that places the buffer itself."""
         import torch
         if block_elems < 4 or block_elems & (block_elems - 1):
             raise ValueError("block_elems must be a power of two >= 4")
         self.n, self.block = int(n), int(block_elems)
         self.blocks = (self.n + self.block - 1) // self.block
-        self.buf = torch.zeros(self.blocks, 4, self.block, dtype=torch.float32, device=device)
+        if alloc is None:
+            self.buf = torch.zeros(self.blocks, 4, self.block, dtype=torch.float32, device=device)
+        else:
+            self.buf = alloc(self.blocks * 4 * self.block, torch.float32).view(self.blocks, 4,
+                                                                                 self.block)
         self.theta, self.m, self.v, self.gsum = (self.buf[:, c, :] for c in range(4))
 
     def load(self, name: str, planar) -> None:
@@ -49,13 +54,18 @@ class InterleavedShards:
     Allocation only - no arithmetic."""
 
     def __init__(self, n: int, workers: int, block_elems: int = DEFAULT_COMM_BLOCK_ELEMS,
-                 device="cuda"):
+                 device="cuda", alloc=None):
         import torch
         if block_elems < 8 or block_elems & (block_elems - 1):
             raise ValueError("block_elems must be a power of two >= 8")
         self.n, self.W, self.block = int(n), int(workers), int(block_elems)
         self.blocks = (self.n + self.block - 1) // self.block
-        self.buf = torch.zeros(self.blocks, self.W, self.block, dtype=torch.bfloat16, device=device)
+        if alloc is None:
+            self.buf = torch.zeros(self.blocks, self.W, self.block, dtype=torch.bfloat16,
+                                   device=device)
+        else:
+            self.buf = alloc(self.blocks * self.W * self.block, torch.bfloat16).view(
+                self.blocks, self.W, self.block)
         self.shards = [self.buf[:, w, :] for w in range(self.W)]
 
     def shard(self, w: int):

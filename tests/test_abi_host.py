@@ -665,3 +665,61 @@ def test_header_is_plain_c_and_the_library_is_callable_from_c(tmp_path):
     cpp.write_text('#include "acco.h"\nint main() { return acco_version() > 0 ? 0 : 1; }\n')
     subprocess.run(["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc,
                     "-fsyntax-only", str(cpp)], check=True)
+
+
+def test_memory_class_probe_validation():
+    L = B.lib()
+    c = L.acco_hbm_classify
+    out = (ctypes.c_int32 * 8)()
+    ncls = ctypes.c_int32(-1)
+    o, nr = out, ctypes.byref(ncls)
+    MiB = 1 << 20
+    S = 0x7f0000000000                                   # scratch well away from the region
+    assert c(NONE, 64 * MiB, 8 * MiB, 8 * MiB, vp(S), o, 8, nr, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), 64 * MiB, 8 * MiB, 8 * MiB, NONE, o, 8, nr, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), 64 * MiB, 8 * MiB, 8 * MiB, vp(S), None, 8, nr, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A), 64 * MiB, 8 * MiB, 8 * MiB, vp(S), o, 8, None, NONE) == B.ACCO_ERR_NULL
+    assert c(vp(A + 4), 64 * MiB, 8 * MiB, 8 * MiB, vp(S), o, 8, nr, NONE) == B.ACCO_ERR_ALIGN
+    assert c(vp(A), 64 * MiB, 8 * MiB + 1, 8 * MiB, vp(S), o, 8, nr, NONE) == B.ACCO_ERR_SIZE
+    assert c(vp(A), 64 * MiB, 8 * MiB, 100, vp(S), o, 8, nr, NONE) == B.ACCO_ERR_SIZE
+    assert c(vp(A), 4 * MiB, 8 * MiB, 8 * MiB, vp(S), o, 1, nr, NONE) == B.ACCO_ERR_SIZE   # region < probe
+    assert c(vp(A), 64 * MiB, 8 * MiB, 8 * MiB, vp(S), o, 7, nr, NONE) == B.ACCO_ERR_SIZE  # count is 8
+    assert c(vp(A), 64 * MiB, 8 * MiB, 8 * MiB, vp(A + 16 * MiB), o, 8, nr, NONE) == B.ACCO_ERR_ALIAS
+    assert ncls.value == -1
+
+
+def test_arena_bookkeeping_on_a_given_classification():
+    from paper_2406_02613_amd.arena import ALIGN, HbmArena, plan_roles
+    GiB = 1 << 30
+    # 12 GiB, a position per GiB, probes of 512 MiB: classes 0 0 0 1 1 0 0 2 2 2 2 2
+    cls = [0, 0, 0, 1, 1, 0, 0, 2, 2, 2, 2, 2]
+    a = HbmArena(12 * GiB, step_bytes=GiB, probe_bytes=GiB // 2, classes=cls)
+    assert a.n_classes == 3
+    H = GiB // 4                                          # half a probe: the guard at a boundary
+    assert [(c, s, e) for c, s, e, _ in a.runs] == [
+        (0, 0, 2 * GiB + H), (1, 3 * GiB + H, 4 * GiB + H), (0, 5 * GiB + H, 6 * GiB + H),
+        (2, 7 * GiB + H, 12 * GiB)]
+    assert a.free_bytes() == {0: 3 * GiB + H, 1: GiB, 2: 5 * GiB - H}
+    off, c = a.take(GiB + 5, 0)
+    assert (off, c) == (0, 0)
+    off, c = a.take(GiB, 0)
+    assert (off, c) == (GiB + ALIGN, 0)                   # hand-outs start on 2 MiB boundaries
+    off, c = a.take(GiB, 0)                               # does not fit the rest of run 0: next run of class 0
+    assert (off, c) == (5 * GiB + H, 0)
+    off, c = a.take(GiB, 0)                               # class 0 has no stretch of 1 GiB left: spills
+    assert c == 2 and off == 7 * GiB + H
+    with pytest.raises(MemoryError):
+        a.take(GiB, 0, spill=False)
+    with pytest.raises(MemoryError):
+        a.take(6 * GiB, 1)
+    with pytest.raises(RuntimeError):
+        a.alloc(16, None, 0)
+    # roles: the bigger reader gets the class with more room, the outputs a third class
+    b = HbmArena(12 * GiB, step_bytes=GiB, probe_bytes=GiB // 2, classes=cls)
+    plan = plan_roles(b, {"owner": 2 * GiB, "compute": 3 * GiB})
+    assert plan == {"compute": 2, "owner": 0, "out": 1}
+    one = HbmArena(4 * GiB, step_bytes=GiB, probe_bytes=GiB // 2, classes=[0, 0, 0, 0])
+    assert plan_roles(one, {"owner": 1, "compute": 2}) == {"compute": 0, "owner": 0, "out": 0}
+    assert plan_roles(None, {}) == {}
+    with pytest.raises(ValueError):
+        HbmArena(4 * GiB, step_bytes=GiB, probe_bytes=GiB // 2, classes=[0, 0])

@@ -33,7 +33,7 @@ def gpu_hyper(A, w):
 def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, rounds=None,
                  fused_publish=False, fused_reduce=False, blocked=False, stash=False,
                  bf16_acc=False, schedules=None, adopt=False, batched=False, interleaved=False,
-                 comm_block=16384, dev_scalars=False):
+                 comm_block=16384, dev_scalars=False, arena=None):
     import paper_2406_02613_amd as A
     slices = w.sample_slices()
     rounds = w.rounds if rounds is None else rounds
@@ -45,7 +45,7 @@ def run_workload(w: synth.Workload, *, comm_bf16=True, fused=True, warm=None, ro
                          bf16_accumulate=bf16_acc,
                          lr_schedule=None if schedules is None else schedules[0],
                          adopt_first=adopt, batched=batched, interleaved_comm=interleaved,
-                         comm_block_elems=comm_block, device_scalars=dev_scalars)
+                         comm_block_elems=comm_block, device_scalars=dev_scalars, arena=arena)
     if warm is None:
         tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
         w.device_theta(tmp)
@@ -290,9 +290,20 @@ def test_seven_billion_heterogeneous_ragged_shard_five_rounds():
 
 def test_seven_billion_scale_shard_fused_path_as_benched():
     # the configuration bench.py times by default: bf16 stash, fused publish, fused reduce + step,
-    # interleaved state, one accumulate launch for all workers
+    # interleaved state, one accumulate launch for all workers, every buffer of the owner placed
+    # by memory class in one arena
+    import gc
+
+    import paper_2406_02613_amd as A
+    gc.collect()
+    torch.cuda.empty_cache()
+    arena = A.HbmArena(int(0.75 * torch.cuda.mem_get_info()[0]))
+    log("arena:", arena.describe())
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
-                 stash=True, batched=True, rounds=3)
+                 stash=True, batched=True, rounds=3, arena=arena)
+    del arena
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def test_seven_billion_hetero_blocked_state_fused_path():
