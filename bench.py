@@ -871,7 +871,8 @@ def main():
     sizes = [w.n]
     if w.n in HEADLINE_SIZES and blocked:
         sizes = list(HEADLINE_SIZES)
-    out_bf16 = torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda")
+    out_bf16 = (torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda") if arena is None
+                else arena.alloc(max(sizes), torch.bfloat16, owner._roles["out"]))
     standalone = {}
     for n_k in sizes:
         solo = EventLog(torch)
