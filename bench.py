@@ -748,7 +748,9 @@ def main():
         # one allocation for every buffer of the round, large enough to span the memory classes
         need = w.n * (16 + 4 + w.workers * (2 + 2 + 4) + 2 * n_grad_bufs)
         free = torch.cuda.mem_get_info()[0]
-        arena = A.HbmArena(min(int(0.82 * free), max(int(2.2 * need), 100 << 30)))
+        size = min(int(0.82 * free), max(int(2.2 * need), 100 << 30))
+        # too little free memory for an arena with room to choose from: plain allocations
+        arena = A.HbmArena(size) if size >= 1.25 * need + (8 << 30) else None
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          arena=arena, gradient_buffers=n_grad_bufs,
