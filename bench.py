@@ -750,7 +750,13 @@ def main():
         free = torch.cuda.mem_get_info()[0]
         size = min(int(0.82 * free), max(int(2.2 * need), 100 << 30))
         # too little free memory for an arena with room to choose from: plain allocations
-        arena = A.HbmArena(size) if size >= 1.25 * need + (8 << 30) else None
+        if size >= 1.25 * need + (8 << 30):
+            try:
+                arena = A.HbmArena(size)
+            except (A.AccoError, MemoryError, RuntimeError) as e:      # measure anyway, unplaced
+                print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
+                arena = None
+                torch.cuda.empty_cache()
     owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                       h.weight_decay),
                          arena=arena, gradient_buffers=n_grad_bufs,
