@@ -236,19 +236,25 @@ def bench_two_stream(args, torch, A, w):
     the communication stream publishes, reduces over W shards and runs the estimate / commit."""
     import synth
     h = w.hyper
+    arena = None
+    if not args.no_arena:
+        try:
+            arena = A.HbmArena(min(int(0.7 * torch.cuda.mem_get_info()[0]), 200 << 30))
+        except (A.AccoError, MemoryError, RuntimeError, ValueError) as e:
+            print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
     own = A.TwoStreamOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
-                                                        h.weight_decay))
+                                                        h.weight_decay), arena=arena)
     tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
     w.device_theta(tmp)
     own.set_theta(tmp)
     del tmp
     peers = []
     for wk in range(1, w.workers):
-        p = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+        p = own.new_buffer("owner", w.n, torch.bfloat16)
         synth.device_grad_bf16(p, w.grad_spec(0, 1, wk, 0), 0)
         peers.append(p)
     peer_counts = [2] * (w.workers - 1)
-    buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    buf = own.new_buffer("compute", w.n, torch.bfloat16)
     a = b = None
     if args.gemm > 0:
         a = torch.randn(args.gemm, args.gemm, dtype=torch.bfloat16, device="cuda")
@@ -320,7 +326,9 @@ def bench_two_stream(args, torch, A, w):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "mode": "two-stream", "n": w.n, "workers": w.workers,
-                   "gemm": args.gemm, "link_ms_per_stage": args.link_ms},
+                   "gemm": args.gemm, "link_ms_per_stage": args.link_ms,
+                   "placement": ("one arena, buffers placed by memory class: " + arena.describe()
+                                 if arena is not None else "plain allocations")},
         "two_stream": {
             "microbatch_ms_alone": mb_alone,
             "microbatch_ms_overlapped": mean([r.comp_ms / r.microbatches for r in log.stages]),

@@ -46,35 +46,54 @@ class TwoStreamLog:
 
 class TwoStreamOwner:
     def __init__(self, n: int, workers: int, hp: B.AdamW, *, blocked_state: bool = True,
-                 device="cuda"):
+                 device="cuda", arena=None):
+        """arena: an arena.HbmArena to place the buffers by memory class (what the owner's
+        kernels read together in one class, what the accumulation reads together in another,
+        the parameter output in a third); the peers' buffers and the gradients then come from
+        ``new_buffer``."""
         import torch
         self.torch = torch
         self.n, self.W, self.hp = int(n), int(workers), hp
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
+        self._dev, self.arena = dev, arena
+        if arena is not None:
+            from .arena import plan_roles
+            self._roles = plan_roles(arena, {"owner": 16 * self.n + 2 * self.n * self.W,
+                                             "compute": 14 * self.n})
         if blocked_state:
-            self.state = BlockedState(n, device=dev)
+            self.state = BlockedState(n, device=dev, alloc=None if arena is None else (
+                lambda numel, dt: self.new_buffer("owner", numel, dt, zero=True)))
             self.theta, self.m, self.v, self.gsum = (self.state.theta, self.state.m,
                                                      self.state.v, self.state.gsum)
         else:
             self.state = None
-            self.theta = torch.empty(n, dtype=f32, device=dev)
-            self.m = torch.zeros(n, dtype=f32, device=dev)
-            self.v = torch.zeros(n, dtype=f32, device=dev)
-            self.gsum = torch.empty(n, dtype=f32, device=dev)
+            self.theta = self.new_buffer("owner", n, f32)
+            self.m = self.new_buffer("owner", n, f32, zero=True)
+            self.v = self.new_buffer("owner", n, f32, zero=True)
+            self.gsum = self.new_buffer("owner", n, f32)
         # worker 0: the two gradient accumulators of Alg. 1 (g and g~) and its comm buffer
-        self.acc = {1: torch.empty(n, dtype=f32, device=dev),      # g~ (consumed by stage 1)
-                    2: torch.empty(n, dtype=f32, device=dev)}      # g  (consumed by stage 2)
+        self.acc = {1: self.new_buffer("compute", n, f32),         # g~ (consumed by stage 1)
+                    2: self.new_buffer("compute", n, f32)}         # g  (consumed by stage 2)
         self.count = {1: B.Counter(0), 2: B.Counter(0)}
         # the first micro-batch of each accumulation is kept as bf16 (exact), see binding
-        self.stash = {1: torch.empty(n, dtype=bf16, device=dev),
-                      2: torch.empty(n, dtype=bf16, device=dev)}
-        self.comm0 = torch.empty(n, dtype=bf16, device=dev)
-        self.params_bf16 = torch.empty(n, dtype=bf16, device=dev)   # Buffer_i as the compute side sees it
+        self.stash = {1: self.new_buffer("compute", n, bf16),
+                      2: self.new_buffer("compute", n, bf16)}
+        self.comm0 = self.new_buffer("owner", n, bf16)
+        self.params_bf16 = self.new_buffer("out", n, bf16)   # Buffer_i as the compute side sees it
         self.total = B.Counter(0)
         self.step = B.Counter(0)
         self.comp_stream = torch.cuda.Stream()
         self.comm_stream = torch.cuda.Stream()
+
+    def new_buffer(self, role: str, numel: int, dtype, zero: bool = False):
+        """A flat buffer for `role`: "owner" (read by the owner's stage: state, published
+        buffers of all workers), "compute" (read by the accumulation: accumulators, stashes,
+        micro-batch gradients) or "out"; from the arena in that role's class if there is one."""
+        if self.arena is None:
+            make = self.torch.zeros if zero else self.torch.empty
+            return make(int(numel), dtype=dtype, device=self._dev)
+        return self.arena.alloc(numel, dtype, self._roles[role], zero=zero)
 
     def set_theta(self, planar) -> None:
         if self.state is not None:
