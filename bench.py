@@ -7,7 +7,10 @@ accumulated, each worker's sum is published to its bf16 communication buffer, th
 the W buffers and runs the speculative estimate step, then the second half is accumulated,
 published and reduced onto the retained sum and the committed AdamW step runs with its fused
 bf16 parameter output.  All inputs (parameters, optimizer state, every micro-batch gradient of
-the round) are resident in HBM before the timed region starts.
+the round) are resident in HBM before the timed region starts.  By default every buffer comes
+from one arena in which the owner's buffers and the gradients are placed by memory class of the
+HBM (paper_2406_02613_amd.arena; `--no-arena` for plain allocations); config.placement says
+which it was.
 
 Prints ONE JSON line.
   value        shard elements per second through one whole round
