@@ -243,6 +243,8 @@ def bench_two_stream(args, torch, A, w):
     if not args.no_arena:
         try:
             arena = A.HbmArena(min(int(0.7 * torch.cuda.mem_get_info()[0]), 200 << 30))
+            if arena.n_classes > 4 or len(arena.runs) > 16:      # timings too erratic to trust
+                arena = None
         except (A.AccoError, MemoryError, RuntimeError, ValueError) as e:
             print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
     own = A.TwoStreamOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
@@ -754,35 +756,58 @@ def main():
     main_opts["interleaved_comm"] = args.interleaved_comm and not (args.bf16_accumulate
                                                                    or args.base_path)
     n_grad_bufs = sum(w.microbatches(0, k) for k in range(w.workers))
-    arena = None
-    if not args.no_arena:
-        # one allocation for every buffer of the round, large enough to span the memory classes
+
+    def make_arena():
+        """One allocation for every buffer of the round, large enough to span the memory
+        classes; None when the device has too little free memory for it, or when the timings
+        the classification rests on are too erratic to trust (e.g. under a counter-collecting
+        profiler): then the buffers are plain allocations."""
         need = w.n * (16 + 4 + w.workers * (2 + 2 + 4) + 2 * n_grad_bufs)
         free = torch.cuda.mem_get_info()[0]
         size = min(int(0.82 * free), max(int(2.2 * need), 100 << 30))
-        # too little free memory for an arena with room to choose from: plain allocations
-        if size >= 1.25 * need + (8 << 30):
-            try:
-                arena = A.HbmArena(size)
-            except (A.AccoError, MemoryError, RuntimeError) as e:      # measure anyway, unplaced
-                print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
-                arena = None
-                torch.cuda.empty_cache()
-    owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
-                                                      h.weight_decay),
-                         arena=arena, gradient_buffers=n_grad_bufs,
-                         blocked_state=blocked, block_elems=args.block_elems,
-                         bf16_stash=not args.bf16_accumulate,        # allocate the stash buffers
-                         bf16_accumulate=args.bf16_accumulate, batched=batched,
-                         interleaved_comm=main_opts["interleaved_comm"],
-                         comm_block_elems=args.comm_block_elems)
-    owner.set_options(**main_opts)
-    scratch = (owner.acc if owner.acc else
-               [torch.empty(w.n, dtype=torch.float32, device="cuda") for _ in range(2)])
-    w.device_theta(scratch[0])                        # a planar scratch the round overwrites
-    owner.set_state("theta", scratch[0])
+        if size < 1.25 * need + (8 << 30):
+            return None
+        try:
+            made = A.HbmArena(size)
+        except (A.AccoError, MemoryError, RuntimeError) as e:
+            print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
+            return None
+        if made.n_classes > 4 or len(made.runs) > 16:
+            print(f"bench.py: memory classes not measurable here ({made.n_classes} classes in "
+                  f"{len(made.runs)} runs); plain allocations", file=sys.stderr)
+            return None
+        return made
 
-    grads, n_bufs = make_grads(torch, synth, w, owner)
+    def build(arena):
+        owner = A.ShardOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
+                                                          h.weight_decay),
+                             arena=arena, gradient_buffers=n_grad_bufs,
+                             blocked_state=blocked, block_elems=args.block_elems,
+                             bf16_stash=not args.bf16_accumulate,        # allocate the stash buffers
+                             bf16_accumulate=args.bf16_accumulate, batched=batched,
+                             interleaved_comm=main_opts["interleaved_comm"],
+                             comm_block_elems=args.comm_block_elems)
+        owner.set_options(**main_opts)
+        scratch = (owner.acc if owner.acc else
+                   [torch.empty(w.n, dtype=torch.float32, device="cuda") for _ in range(2)])
+        w.device_theta(scratch[0])                        # a planar scratch the round overwrites
+        owner.set_state("theta", scratch[0])
+        grads, n_bufs = make_grads(torch, synth, w, owner)
+        return owner, scratch, grads, n_bufs
+
+    arena = None if args.no_arena else make_arena()
+    try:
+        owner, scratch, grads, n_bufs = build(arena)
+    except MemoryError as e:
+        if arena is None:
+            raise
+        print(f"bench.py: the arena cannot hold the round ({e}); plain allocations",
+              file=sys.stderr)
+        arena = None
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        owner, scratch, grads, n_bufs = build(None)
 
     if args.calibrate_copy:
         scratch[1].copy_(scratch[0])           # planar fp32: 4n bytes read, 4n bytes written
@@ -890,8 +915,11 @@ def main():
     sizes = [w.n]
     if w.n in HEADLINE_SIZES and blocked:
         sizes = list(HEADLINE_SIZES)
-    out_bf16 = (torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda") if arena is None
-                else arena.alloc(max(sizes), torch.bfloat16, owner._roles["out"]))
+    try:
+        out_bf16 = (torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda") if arena is None
+                    else arena.alloc(max(sizes), torch.bfloat16, owner._roles["out"]))
+    except MemoryError:
+        out_bf16 = torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda")
     standalone = {}
     for n_k in sizes:
         solo = EventLog(torch)
