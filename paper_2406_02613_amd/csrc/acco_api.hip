@@ -1293,8 +1293,9 @@ ACCO_API int acco_hbm_classify(const void* base, int64_t bytes, int64_t step_byt
         *n_classes = 1;
         return ACCO_OK;
     }
-    // what a pair in ONE class takes: the median over pairs of neighbouring positions (classes
-    // are tens of GiB long, so nearly all neighbours share one)
+    // what a pair in ONE class takes: the fastest of some pairs of neighbouring positions
+    // (classes are tens of GiB long, so nearly all neighbours share one; disturbances only
+    // ever add time)
     float   cal[12];
     int     ncal = 0;
     const int64_t stride = count > 24 ? (count - 1) / 12 : 1;
@@ -1303,24 +1304,21 @@ ACCO_API int acco_hbm_classify(const void* base, int64_t bytes, int64_t step_byt
         if (t < 0.0f) return ACCO_ERR_DEVICE;
         cal[ncal++] = t;
     }
-    for (int i = 1; i < ncal; ++i)
-        for (int j = i; j > 0 && cal[j] < cal[j - 1]; --j) std::swap(cal[j], cal[j - 1]);
-    const float fast = cal[ncal / 2];
+    const float fast = *std::min_element(cal, cal + ncal);
 
     // first fit against one reference position per class found so far
     int64_t refs[64];
     int     nref = 0;
     for (int64_t k = 0; k < count; ++k) {
         int found = -1;
-        for (int c = 0; c < nref && found < 0; ++c) {
-            if (refs[c] == k) {
-                found = c;
-                break;
+        // a disturbance can only make a pair look slow, never fast: a position that matches no
+        // class gets a second round of probes before it founds a new one
+        for (int attempt = 0; attempt < 2 && found < 0; ++attempt)
+            for (int c = 0; c < nref && found < 0; ++c) {
+                const float t = timer.time(at(refs[c]), at(k), 3);
+                if (t < 0.0f) return ACCO_ERR_DEVICE;
+                if (t < fast * kSlowPair) found = c;
             }
-            const float t = timer.time(at(refs[c]), at(k), 3);
-            if (t < 0.0f) return ACCO_ERR_DEVICE;
-            if (t < fast * kSlowPair) found = c;
-        }
         if (found < 0) {
             if (nref == 64) return ACCO_ERR_DEVICE;   // timings too erratic to classify
             refs[nref] = k;
