@@ -297,8 +297,13 @@ def test_seven_billion_scale_shard_fused_path_as_benched():
     import paper_2406_02613_amd as A
     gc.collect()
     torch.cuda.empty_cache()
-    arena = A.HbmArena(int(0.75 * torch.cuda.mem_get_info()[0]))
-    log("arena:", arena.describe())
+    free = torch.cuda.mem_get_info()[0]
+    arena = None
+    if free >= 170 << 30:            # the owner's buffers take 74 GB, the test's own another 20
+        arena = A.HbmArena(int(0.75 * free))
+        log("arena:", arena.describe())
+    else:
+        log(f"only {free >> 30} GiB free: plain allocations")
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
                  stash=True, batched=True, rounds=3, arena=arena)
     del arena
