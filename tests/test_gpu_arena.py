@@ -1,6 +1,5 @@
 """Buffers placed by memory class: the classification call, the arena that hands out tensors by
 class, and whole rounds on arena-placed buffers (placement changes no bit)."""
-import numpy as np
 import pytest
 
 import synth

@@ -9,8 +9,7 @@ import pytest
 
 import oracle
 import synth
-from parity import (OracleSlices, adam_state, bf16_tensor, bit_mismatches, bits_of, gather,
-                    oracle_hyper)
+from parity import OracleSlices, adam_state, bf16_tensor, bit_mismatches, bits_of, gather
 
 pytestmark = pytest.mark.gpu
 

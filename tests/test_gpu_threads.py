@@ -6,7 +6,6 @@ import threading
 import numpy as np
 import pytest
 
-import oracle
 import synth
 from parity import OracleSlices, bit_mismatches, bits_of
 
