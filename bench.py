@@ -917,7 +917,7 @@ def main():
         sizes = list(HEADLINE_SIZES)
     try:
         out_bf16 = (torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda") if arena is None
-                    else arena.alloc(max(sizes), torch.bfloat16, owner._roles["out"]))
+                    else arena.alloc(max(sizes), torch.bfloat16, owner.roles["out"]))
     except MemoryError:
         out_bf16 = torch.empty(max(sizes), dtype=torch.bfloat16, device="cuda")
     standalone = {}
@@ -1031,7 +1031,7 @@ def main():
                                              "elements" if main_opts["interleaved_comm"]
                                              else "planar, one allocation per worker"),
                    "placement": ("one arena, buffers placed by memory class: " + arena.describe()
-                                 + "; classes of the roles: " + json.dumps(owner._roles)
+                                 + "; classes of the roles: " + json.dumps(owner.roles)
                                  if arena is not None else "plain allocations"),
                    "launches_per_step": sum(k["calls_per_step"] for k in kernels.values()),
                    "bytes_per_elem_per_step": bytes_per_round,

@@ -73,10 +73,11 @@ class ShardOwner:
         # gradient_buffers: how many n-element bf16 gradient buffers the caller will ask
         # new_gradient_buffer for (only used to decide which class gets which role)
         self.arena = arena
+        self.roles = {}              # with an arena: memory class of each role's buffers
         if arena is not None:
             from .arena import plan_roles
             n_, W_ = int(n), int(workers)
-            self._roles = plan_roles(arena, {
+            self.roles = plan_roles(arena, {
                 "owner": 16 * n_ + (2 * n_ * W_ if comm_bf16 else 0),
                 "compute": (0 if bf16_accumulate else 4 * n_ * W_) + 2 * n_ * W_
                 + 2 * n_ * int(gradient_buffers)})
@@ -146,7 +147,7 @@ class ShardOwner:
         if self.arena is None:
             make = self.torch.zeros if zero else self.torch.empty
             return make(int(numel), dtype=dtype, device=self._dev)
-        return self.arena.alloc(numel, dtype, self._roles[role], zero=zero)
+        return self.arena.alloc(numel, dtype, self.roles[role], zero=zero)
 
     def new_gradient_buffer(self, first: bool = False):
         """An n-element bf16 buffer for a micro-batch gradient, placed where the accumulation

@@ -57,9 +57,10 @@ class TwoStreamOwner:
         f32, bf16 = torch.float32, torch.bfloat16
         dev = torch.device(device)
         self._dev, self.arena = dev, arena
+        self.roles = {}              # with an arena: memory class of each role's buffers
         if arena is not None:
             from .arena import plan_roles
-            self._roles = plan_roles(arena, {"owner": 16 * self.n + 2 * self.n * self.W,
+            self.roles = plan_roles(arena, {"owner": 16 * self.n + 2 * self.n * self.W,
                                              "compute": 14 * self.n})
         if blocked_state:
             self.state = BlockedState(n, device=dev, alloc=None if arena is None else (
@@ -93,7 +94,7 @@ class TwoStreamOwner:
         if self.arena is None:
             make = self.torch.zeros if zero else self.torch.empty
             return make(int(numel), dtype=dtype, device=self._dev)
-        return self.arena.alloc(numel, dtype, self._roles[role], zero=zero)
+        return self.arena.alloc(numel, dtype, self.roles[role], zero=zero)
 
     def set_theta(self, planar) -> None:
         if self.state is not None:
