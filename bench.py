@@ -205,10 +205,26 @@ def scheme_round(owner, w, grads):
     owner.finish_round()
 
 
-def bench_scheme(args, torch, A, w, grads):
+def small_arena(args, torch, A):
+    """An arena for the side benches (two-stream, schemes), or None: --no-arena, too little
+    memory, or timings too erratic to classify by."""
+    if args.no_arena:
+        return None
+    try:
+        arena = A.HbmArena(min(int(0.7 * torch.cuda.mem_get_info()[0]), 200 << 30))
+    except (A.AccoError, MemoryError, RuntimeError, ValueError) as e:
+        print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
+        return None
+    return None if arena.n_classes > 4 or len(arena.runs) > 16 else arena
+
+
+def bench_scheme(args, torch, A, w, synth):
     h = w.hyper
+    arena = small_arena(args, torch, A)
     owner = A.SchemeOwner(w.n, w.workers, args.scheme,
-                          A.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay))
+                          A.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay),
+                          arena=arena)
+    grads = make_grads(torch, synth, w, owner if arena is not None else None, hint_first=False)[0]
     tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
     w.device_theta(tmp)
     owner.set_theta(tmp)
@@ -229,7 +245,9 @@ def bench_scheme(args, torch, A, w, grads):
         "value": w.n / (ms * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "scheme": args.scheme, "n": w.n, "workers": w.workers}}))
+        "config": {"workload": w.name, "scheme": args.scheme, "n": w.n, "workers": w.workers,
+                   "placement": ("one arena, buffers placed by memory class: " + arena.describe()
+                                 if arena is not None else "plain allocations")}}))
     return 0
 
 
@@ -239,14 +257,7 @@ def bench_two_stream(args, torch, A, w):
     the communication stream publishes, reduces over W shards and runs the estimate / commit."""
     import synth
     h = w.hyper
-    arena = None
-    if not args.no_arena:
-        try:
-            arena = A.HbmArena(min(int(0.7 * torch.cuda.mem_get_info()[0]), 200 << 30))
-            if arena.n_classes > 4 or len(arena.runs) > 16:      # timings too erratic to trust
-                arena = None
-        except (A.AccoError, MemoryError, RuntimeError, ValueError) as e:
-            print(f"bench.py: no arena ({e}); plain allocations", file=sys.stderr)
+    arena = small_arena(args, torch, A)
     own = A.TwoStreamOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
                                                         h.weight_decay), arena=arena)
     tmp = torch.empty(w.n, dtype=torch.float32, device="cuda")
@@ -589,7 +600,7 @@ def summarize_rocprof(raw):
     return 0 if wrote else 1
 
 
-def make_grads(torch, synth, w, owner=None):
+def make_grads(torch, synth, w, owner=None, hint_first=True):
     """Every micro-batch gradient of one round, resident in HBM: grads[stage][worker][mb].
     With an owner that places its buffers (an arena), the gradients come from it too."""
     grads = {}
@@ -600,7 +611,8 @@ def make_grads(torch, synth, w, owner=None):
             row = []
             for mb in range(w.stage_counts(0, st)[wk]):
                 g = (torch.empty(w.n, dtype=torch.bfloat16, device="cuda") if owner is None
-                     else owner.new_gradient_buffer(first=(mb == 0)))
+                     else owner.new_gradient_buffer(first=(mb == 0)) if hint_first
+                     else owner.new_gradient_buffer())
                 synth.device_grad_bf16(g, w.grad_spec(0, st, wk, mb), 0)
                 row.append(g)
                 n_bufs += 1
@@ -745,7 +757,7 @@ def main():
     if args.two_stream:
         return bench_two_stream(args, torch, A, w)
     if args.scheme is not None:
-        return bench_scheme(args, torch, A, w, make_grads(torch, synth, w)[0])
+        return bench_scheme(args, torch, A, w, synth)
     blocked = not args.planar_state and not args.unfused_cast
     stash = not (args.no_bf16_stash or args.base_path)
     main_opts = dict(fused_bf16_out=not args.unfused_cast,

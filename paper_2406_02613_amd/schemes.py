@@ -25,7 +25,10 @@ SCHEMES = ("acco", "ddp", "dpu", "wp")
 
 class SchemeOwner:
     def __init__(self, n: int, workers: int, scheme: str, opt, *, comm_bf16: bool = True,
-                 device="cuda", warmup_rounds: int = 0):
+                 device="cuda", warmup_rounds: int = 0, arena=None):
+        """arena: an arena.HbmArena to place the buffers by memory class (state and
+        communication buffers in one class, accumulators and the gradients from
+        ``new_gradient_buffer`` in another, the parameter outputs in a third)."""
         import torch
         if scheme not in SCHEMES:
             raise ValueError(f"scheme must be one of {SCHEMES}")
@@ -39,20 +42,35 @@ class SchemeOwner:
         self.adam = isinstance(opt, B.AdamW)
         self.n, self.W, self.comm_bf16 = int(n), int(workers), comm_bf16
         f32, bf16 = torch.float32, torch.bfloat16
-        dev = torch.device(device)
-        self.theta = torch.empty(n, dtype=f32, device=dev)
-        self.m = torch.zeros(n, dtype=f32, device=dev) if self.adam else None
-        self.v = torch.zeros(n, dtype=f32, device=dev) if self.adam else None
-        self.gsum = torch.empty(n, dtype=f32, device=dev)
-        self.acc: List = [torch.empty(n, dtype=f32, device=dev) for _ in range(workers)]
-        self.comm: List = ([torch.empty(n, dtype=bf16, device=dev) for _ in range(workers)]
+        self._dev, self.arena, self.roles = torch.device(device), arena, {}
+        if arena is not None:
+            from .arena import plan_roles
+            self.roles = plan_roles(arena, {
+                "owner": 16 * self.n + (2 * self.n * self.W if comm_bf16 else 0),
+                "compute": 4 * self.n * self.W + 2 * self.n * 4 * self.W})
+        self.theta = self._alloc("owner", n, f32)
+        self.m = self._alloc("owner", n, f32, zero=True) if self.adam else None
+        self.v = self._alloc("owner", n, f32, zero=True) if self.adam else None
+        self.gsum = self._alloc("owner", n, f32)
+        self.acc: List = [self._alloc("compute", n, f32) for _ in range(workers)]
+        self.comm: List = ([self._alloc("owner", n, bf16) for _ in range(workers)]
                            if comm_bf16 else [])
-        self.params_f32 = torch.empty(n, dtype=f32, device=dev)
-        self.params_bf16 = torch.empty(n, dtype=bf16, device=dev)
+        self.params_f32 = self._alloc("out", n, f32)
+        self.params_bf16 = self._alloc("out", n, bf16)
         self.count = [B.Counter(0) for _ in range(workers)]
         self.total = B.Counter(0)
         self.step = B.Counter(0)
         self._fresh = [True] * workers
+
+    def _alloc(self, role: str, numel: int, dtype, zero: bool = False):
+        if self.arena is None:
+            make = self.torch.zeros if zero else self.torch.empty
+            return make(int(numel), dtype=dtype, device=self._dev)
+        return self.arena.alloc(numel, dtype, self.roles[role], zero=zero)
+
+    def new_gradient_buffer(self):
+        """An n-element bf16 buffer for a micro-batch gradient, in the accumulators' class."""
+        return self._alloc("compute", self.n, self.torch.bfloat16)
 
     @property
     def params(self):
