@@ -266,7 +266,7 @@ def bench_two_stream(args, torch, A, w):
     del tmp
     peers = []
     for wk in range(1, w.workers):
-        p = own.new_buffer("owner", w.n, torch.bfloat16)
+        p = own.new_peer_buffer(wk)
         synth.device_grad_bf16(p, w.grad_spec(0, 1, wk, 0), 0)
         peers.append(p)
     peer_counts = [2] * (w.workers - 1)

@@ -53,8 +53,12 @@ class SchemeOwner:
         self.v = self._alloc("owner", n, f32, zero=True) if self.adam else None
         self.gsum = self._alloc("owner", n, f32)
         self.acc: List = [self._alloc("compute", n, f32) for _ in range(workers)]
-        self.comm: List = ([self._alloc("owner", n, bf16) for _ in range(workers)]
-                           if comm_bf16 else [])
+        # the W buffers staggered by 4 KiB each, as in shard.ShardOwner
+        from .shard import COMM_SKEW_BYTES
+        skew = COMM_SKEW_BYTES // 2
+        self.comm: List = ([self._alloc("owner", n + (w % 8) * skew, bf16)[(w % 8) * skew:
+                                                                         (w % 8) * skew + n]
+                            for w in range(workers)] if comm_bf16 else [])
         self.params_f32 = self._alloc("out", n, f32)
         self.params_bf16 = self._alloc("out", n, bf16)
         self.count = [B.Counter(0) for _ in range(workers)]

@@ -54,6 +54,8 @@ from typing import Callable, List, Optional
 from . import binding as B
 
 # what ShardOwner.set_options may switch between rounds
+COMM_SKEW_BYTES = 4096     # stagger between the workers' planar communication buffers
+
 OPTIONS = ("fused_bf16_out", "fused_publish", "fused_reduce", "bf16_stash", "adopt_first",
            "interleaved_comm", "device_scalars")
 
@@ -180,8 +182,17 @@ class ShardOwner:
             self.comm = list(self._comm_slab.shards)
         else:
             if self._comm_planar is None:
-                self._comm_planar = [self._alloc("owner", self.n, self.torch.bfloat16)
-                                     for _ in range(self.W)]
+                # W separate buffers, each started COMM_SKEW_BYTES further into its allocation
+                # than the one before: allocations start on 2 MiB boundaries, and W streams read
+                # at the same index with identical low address bits queue up on the same DRAM
+                # channels (MI355X, W = 8, 875M elements: reduce + estimate 4.46 -> 4.37 ms,
+                # reduce + commit 5.98 -> 5.90 with 4 KiB per worker; any multiple of 1 KiB up to
+                # 1 MiB helps, 4 and 8 KiB the most)
+                skew = COMM_SKEW_BYTES // 2
+                self._comm_planar = [
+                    self._alloc("owner", self.n + (w % 8) * skew,
+                                self.torch.bfloat16)[(w % 8) * skew:(w % 8) * skew + self.n]
+                    for w in range(self.W)]
             self.comm = self._comm_planar
 
     def comm_planar(self, w: int):

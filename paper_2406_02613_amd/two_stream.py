@@ -96,6 +96,13 @@ class TwoStreamOwner:
             return make(int(numel), dtype=dtype, device=self._dev)
         return self.arena.alloc(numel, dtype, self.roles[role], zero=zero)
 
+    def new_peer_buffer(self, worker: int):
+        """The published bf16 buffer of another worker (1 .. W-1), placed with the owner's
+        buffers and staggered by 4 KiB per worker like shard.ShardOwner's."""
+        from .shard import COMM_SKEW_BYTES
+        skew = (worker % 8) * (COMM_SKEW_BYTES // 2)
+        return self.new_buffer("owner", self.n + skew, self.torch.bfloat16)[skew:skew + self.n]
+
     def set_theta(self, planar) -> None:
         if self.state is not None:
             self.state.load("theta", planar)
