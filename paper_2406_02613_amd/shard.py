@@ -157,7 +157,12 @@ class ShardOwner:
         it is added to.  ``first``: the buffer will only ever hold the first micro-batch of an
         accumulation; with the bf16 stash that one is merely copied, read together with nothing,
         so it need not take room in that class."""
-        role = "out" if first and self.bf16_stash and not self.adopt_first else "compute"
+        if self.bf16_accumulate:
+            # the bf16 running sum is the communication buffer itself: the gradients added to
+            # it are read together with it; the first one is merely copied
+            role = "out" if first else "owner"
+        else:
+            role = "out" if first and self.bf16_stash and not self.adopt_first else "compute"
         return self._alloc(role, self.n, self.torch.bfloat16)
 
     def _select_scalars(self, on: bool) -> None:
