@@ -522,7 +522,7 @@ int acco_set_launch_shape(const char* entry, int threads, int vectors_in_flight,
  * only so many workgroups fit.  Fewer resident wavefronts mean fewer distinct DRAM pages open
  * at a time, which pays for the kernels that stream many arrays at once.  At least 3
  * workgroups must fit (one workgroup can reserve at most 64 KiB).  Process-wide.  The
- * library's defaults are per entry point (from 9 for the committed step to none for the
+ * library's defaults are per entry point (from 8 for the committed step to none for the
  * cast); the variants that start a new sum (init != 0), which write more than they read,
  * always run unbounded.
  * Returns ACCO_ERR_ARG for an unknown name or a bound outside 0, 3..32.

@@ -70,7 +70,7 @@ constexpr LaunchShape kDefaults[kEntries] = {
     {64, 1, 0, 0},   // cast                (any bound is slower)
     {64, 1, 0, 16},  // reduce              (+3 %)
     {64, 1, 0, 12},  // estimate            (+8 %)
-    {64, 1, 0, 9},   // commit              (+4 %)
+    {64, 1, 0, 8},   // commit              (+5 %; 7 is over the edge: -5 %)
     {64, 1, 0, 24},  // accumulate_publish  (+1 %)
     {64, 1, 0, 10},  // reduce_estimate     (+6 %)
     {64, 1, 0, 9},   // reduce_commit       (+3 %)
