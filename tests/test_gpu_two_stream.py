@@ -51,20 +51,26 @@ def spec(w, rnd, acc, k):
     return w.grad_spec(rnd + 1, acc, 0, k)          # round -1 is the initialisation gradient
 
 
-@pytest.mark.parametrize("blocked", [True, False])
-def test_two_stream_rounds_equal_the_oracle_replay(blocked):
+@pytest.mark.parametrize("blocked,placed", [(True, False), (False, False), (True, True)])
+def test_two_stream_rounds_equal_the_oracle_replay(blocked, placed):
     import paper_2406_02613_amd as A
     w = synth.Workload(name="ts", n=400_000 + 37, workers=3, rounds=4, grad_std=1e-3, seed=17)
     h = w.hyper
+    # placed: every buffer from an arena, by memory class (placement changes no bit)
+    arena = A.HbmArena(2 << 30, step_bytes=512 << 20, probe_bytes=256 << 20) if placed else None
     own = A.TwoStreamOwner(w.n, w.workers, A.make_hyper(h.lr, h.beta1, h.beta2, h.eps,
-                                                        h.weight_decay), blocked_state=blocked)
+                                                        h.weight_decay), blocked_state=blocked,
+                           arena=arena)
     th0 = w.host_theta(0, w.n)
     own.set_theta(torch.from_numpy(th0).cuda())
     peer_counts = [2, 3]
     peers_bits = [synth.host_grad_bf16(w.grad_spec(0, 1, wk, 0), 0, w.n) for wk in (1, 2)]
-    peers = [torch.from_numpy(b.view(np.int16).copy()).view(torch.bfloat16).cuda()
-             for b in peers_bits]
-    buf = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    peers = []
+    for wk, b in zip((1, 2), peers_bits):
+        p = own.new_peer_buffer(wk)
+        p.copy_(torch.from_numpy(b.view(np.int16).copy()).view(torch.bfloat16))
+        peers.append(p)
+    buf = own.new_buffer("compute", w.n, torch.bfloat16)
 
     def grad_source(rnd, acc, k):
         synth.device_grad_bf16(buf, spec(w, rnd, acc, k), 0)     # runs on the computation stream
