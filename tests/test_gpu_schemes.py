@@ -167,3 +167,43 @@ def test_adamw_schemes_match_the_oracle_on_synthetic_gradients(acco, scheme, com
                              abs_=1e-30 if name == "v" else 1e-9 * (r + 1))
         assert bit_mismatches(g.params_f32.cpu().numpy(), o.params) == 0
         assert np.array_equal(bits_of(g.params_bf16), o.params_bf16)
+
+
+@pytest.mark.parametrize("scheme", ["acco", "wp"])
+def test_schemes_on_arena_placed_buffers_change_no_bits(acco, scheme):
+    """The same rounds with every buffer of the scheme owner taken from an arena (state and
+    communication buffers, accumulators and gradients, outputs by memory class)."""
+    w = synth.Workload(name="sch_arena", n=150_000 + 5, workers=3, rounds=2, grad_std=1e-3,
+                       k_range=(2, 4), seed=14)
+    h = w.hyper
+    arena = acco.HbmArena(2 << 30, step_bytes=512 << 20, probe_bytes=256 << 20)
+    g = acco.SchemeOwner(w.n, w.workers, scheme,
+                         acco.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay),
+                         arena=arena)
+    th0 = w.host_theta(0, w.n)
+    g.set_theta(dev(th0))
+    o = OracleScheme(th0, w.workers, scheme,
+                     adamw=oracle.make_hyper(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay),
+                     precision="f32")
+    buf = g.new_gradient_buffer()
+    for r in range(w.rounds):
+        for stage in (synth.STAGE_TILDE, synth.STAGE_FULL):
+            counts = w.stage_counts(r, stage)
+            for wk in range(w.workers):
+                for mb in range(counts[wk]):
+                    sp = w.grad_spec(r, stage, wk, mb)
+                    synth.device_grad_bf16(buf, sp, 0)
+                    g.add_microbatch(wk, buf)
+                    o.add_microbatch(wk, synth.host_grad_bf16(sp, 0, w.n))
+            if stage == synth.STAGE_TILDE:
+                if scheme == "acco":
+                    g.finish_half()
+                    o.finish_half()
+            else:
+                g.finish_round()
+                o.finish_round()
+        torch.cuda.synchronize()
+        for name in ("theta", "m", "v"):
+            assert bit_mismatches(getattr(g, name).cpu().numpy(), getattr(o, name)) == 0, name
+        assert bit_mismatches(g.params_f32.cpu().numpy(), o.params) == 0
+        assert np.array_equal(bits_of(g.params_bf16), o.params_bf16)
