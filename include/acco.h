@@ -89,11 +89,11 @@ typedef struct acco_adamw_t {
  *   starts are block_stride elements apart.  This lets the four arrays be interleaved block by
  *   block in ONE buffer - [theta block][m block][v block][gsum block] repeated, with
  *   block_stride = 4 * block_elems and the four pointers one block apart - which keeps the
- *   addresses streamed at any moment a fixed few tens of KiB apart (on MI355X the committed
- *   step then runs at 6.4-6.6 TB/s every time; with four distant planar arrays at 5.4-6.4
- *   depending on where they happen to be allocated: arrays read together should lie in one
- *   memory class, see acco_hbm_classify, which one buffer does by construction).  All four
- *   arrays share the one layout.
+ *   addresses streamed at any moment a fixed few tens of KiB apart (on MI355X, before the
+ *   resident wavefronts were bounded, the committed step then ran at 6.4-6.6 TB/s every time;
+ *   with four distant planar arrays at 5.4-6.4 depending on where they happened to be
+ *   allocated: arrays read together should lie in one memory class, see acco_hbm_classify,
+ *   which one buffer does by construction).  All four arrays share the one layout.
  *   block_elems: a power of two >= 4; block_stride: a multiple of 4, >= block_elems.
  * The fp32 and bf16 outputs of the step entry points stay planar.
  *
