@@ -302,6 +302,12 @@ def test_seven_billion_scale_shard_fused_path_as_benched():
     if free >= 170 << 30:            # the owner's buffers take 74 GB, the test's own another 20
         arena = A.HbmArena(int(0.75 * free))
         log("arena:", arena.describe())
+        if arena.n_classes > 4 or len(arena.runs) > 16 or \
+                max(arena.largest_free().values()) < 30 << 30:
+            # the classification is a timing measurement; one that was disturbed leaves pieces
+            # too small for these buffers.  What this test checks is the arithmetic.
+            log("arena too fragmented for the 875M-element buffers: plain allocations")
+            arena = None
     else:
         log(f"only {free >> 30} GiB free: plain allocations")
     run_workload(synth.WORKLOADS["7b"], fused_publish=True, fused_reduce=True, blocked=True,
