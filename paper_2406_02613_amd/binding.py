@@ -72,11 +72,12 @@ def lib() -> ctypes.CDLL:
     """The loaded C-ABI library.  Raises if it has not been built."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.ACCO_SO):
+        so = _build.selected_so()
+        if not os.path.exists(so):
             raise RuntimeError(
-                f"{_build.ACCO_SO} not found: build it with paper_2406_02613_amd/build.py "
+                f"{so} not found: build it with paper_2406_02613_amd/build.py "
                 "(there is no fallback implementation)")
-        L = ctypes.CDLL(_build.ACCO_SO)
+        L = ctypes.CDLL(so)
         p, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         pi64 = ctypes.POINTER(ctypes.c_int64)
         play = ctypes.POINTER(Layout)

@@ -117,3 +117,46 @@ def test_oracle_pins_and_generator_tests_under_the_sanitizers():
     out = _run(["-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider", *files],
                _sanitizer_env())
     assert " passed" in out and "failed" not in out
+
+
+def _hip_host_sanitizer_env():
+    """Environment of a child interpreter that loads the HIP library's host-sanitized build.
+    That build comes from clang (hipcc), so it needs clang's runtime, not gcc's: the two cannot
+    share a process, hence a child of its own with the oracle in its plain build."""
+    from paper_2406_02613_amd import build as ab
+    runtime = ab.sanitizer_runtime()
+    if runtime is None:
+        pytest.skip("clang's shared AddressSanitizer runtime is not installed")
+    ab.ensure_host_sanitized()
+    env = dict(os.environ)
+    env.pop("ACCO_SANITIZE", None)
+    env["ACCO_SANITIZE_HOST"] = "1"
+    env["LD_PRELOAD"] = " ".join(filter(None, [runtime, env.get("LD_PRELOAD")]))
+    env["ASAN_OPTIONS"] = "detect_leaks=0:verify_asan_link_order=0:abort_on_error=0:exitcode=66"
+    env["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1:exitcode=66"
+    env["PYTHONPATH"] = os.pathsep.join(filter(None, [ROOT, os.path.join(ROOT, "tests"),
+                                                      env.get("PYTHONPATH")]))
+    return env
+
+
+def test_host_half_of_the_hip_library_under_the_sanitizers():
+    """Validation, host counters, folded scalars and launch settings of the C-ABI library with
+    its host code instrumented (no device work: every call here stops before a launch)."""
+    env = _hip_host_sanitizer_env()
+    from paper_2406_02613_amd import build as ab
+    out = _run(["-c", "import paper_2406_02613_amd.binding as B; B.lib(); "
+                      "maps = open('/proc/self/maps').read(); "
+                      f"print(int({ab.ACCO_HOST_SAN_SO!r} in maps), int({ab.ACCO_SO!r} in maps))"], env)
+    assert out.split()[-2:] == ["1", "0"]
+    # a planted overrun in the CALLER (64 counts announced, 63 there) must be reported
+    bad = ("import ctypes, paper_2406_02613_amd.binding as B; L = B.lib(); "
+           "counts = (ctypes.c_int64 * 80)(*([1] * 80)); total = ctypes.c_int64(0); "
+           "shards = (ctypes.c_void_p * 64)(*([0x100000] * 64)); "
+           "p = ctypes.cast(ctypes.addressof(counts) + 8 * 17, ctypes.POINTER(ctypes.c_int64)); "
+           "L.acco_reduce_shards(0x200000, shards, 64, 0, 0, 0, p, ctypes.byref(total), None, "
+           "None, None)")
+    r = subprocess.run([sys.executable, "-c", bad], cwd=ROOT, env=env, capture_output=True,
+                       text=True, timeout=300)
+    assert r.returncode != 0 and "AddressSanitizer" in r.stderr, (r.returncode, r.stderr[-2000:])
+    out = _run(["-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "tests/test_abi_host.py"], env)
+    assert " passed" in out and "failed" not in out
