@@ -453,6 +453,8 @@ KERNEL_LABELS = (
     ("Single<acco::AdamOp<false, false, true", "estimate"),
     ("ReduceOp<8, true, false", "reduce_init"),
     ("ReduceOp<8, true, true", "reduce_accumulate"),
+    ("ReduceOp<16, true, false", "reduce_init"),              # more than 8 bf16 shards
+    ("ReduceOp<16, true, true", "reduce_accumulate"),
 )
 
 

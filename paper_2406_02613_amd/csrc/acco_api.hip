@@ -564,12 +564,31 @@ ACCO_API int acco_accumulate_batch(int op, int workers, float* const* acc,
 
 namespace {
 
-ShardPtrs chunk_ptrs(const void* const* shards, int begin, int end)
+template <int WMAX>
+ShardPtrs<WMAX> chunk_ptrs(const void* const* shards, int begin, int end)
 {
-    ShardPtrs ptrs;
+    ShardPtrs<WMAX> ptrs;
     std::memset(&ptrs, 0, sizeof ptrs);
     for (int w = begin; w < end; ++w) ptrs.p[w - begin] = shards[w];
     return ptrs;
+}
+
+// Shards taken per launch: 8, or 16 bf16 shards when there are more than 8 (each pass over
+// fewer than all shards costs a round trip of gsum: 8 bytes per element).
+template <bool BF16>
+int reduce_chunk(int workers)
+{
+    return BF16 && workers > kReduceChunk ? kReduceChunkWide : kReduceChunk;
+}
+
+// f(integral_constant<int, WMAX>) with the kernel width that holds `cnt` shards
+template <bool BF16, class F>
+int with_width(int cnt, F&& f)
+{
+    if constexpr (BF16) {
+        if (cnt > kReduceChunk) return f(std::integral_constant<int, kReduceChunkWide>{});
+    }
+    return f(std::integral_constant<int, kReduceChunk>{});
 }
 
 // The shards' own layout: only bf16 shards (the communication buffers) may be blocked.
@@ -582,22 +601,25 @@ int with_shard_layout(const StateLayout& SL, F&& f)
     return f(StateAddr<false>{});
 }
 
-// plain reduction of shards [0, workers) into gsum, kReduceChunk at a time
+// plain reduction of shards [0, workers) into gsum, `chunk` at a time
 template <bool BF16>
 int launch_reduce(float* gsum, const StateLayout& L, const StateLayout& SL,
-                  const void* const* shards, int workers, int64_t n, bool accumulate,
+                  const void* const* shards, int workers, int64_t n, bool accumulate, int chunk,
                   hipStream_t stream)
 {
-    for (int w0 = 0; w0 < workers; w0 += kReduceChunk) {
-        const int       end  = w0 + kReduceChunk < workers ? w0 + kReduceChunk : workers;
-        const bool      acc  = accumulate || w0 > 0;
-        const ShardPtrs ptrs = chunk_ptrs(shards, w0, end);
-        const int       rc   = with_layout(L, [&](auto at) {
-            return with_shard_layout<BF16>(SL, [&](auto sat) {
-                constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
-                if (acc)
-                    return launch(kReduce, ReduceOp<kReduceChunk, BF16, true, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
-                return launch(kReduce, ReduceOp<kReduceChunk, BF16, false, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
+    for (int w0 = 0; w0 < workers; w0 += chunk) {
+        const int  end = w0 + chunk < workers ? w0 + chunk : workers;
+        const bool acc = accumulate || w0 > 0;
+        const int  rc  = with_width<BF16>(end - w0, [&](auto width) {
+            constexpr int WM   = decltype(width)::value;
+            const auto    ptrs = chunk_ptrs<WM>(shards, w0, end);
+            return with_layout(L, [&](auto at) {
+                return with_shard_layout<BF16>(SL, [&](auto sat) {
+                    constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+                    if (acc)
+                        return launch(kReduce, ReduceOp<WM, BF16, true, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
+                    return launch(kReduce, ReduceOp<WM, BF16, false, B, S>{gsum, ptrs, end - w0, at, sat}, n, stream);
+                });
             });
         });
         if (rc != ACCO_OK) return rc;
@@ -655,8 +677,9 @@ ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int work
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        rc = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, L, SL, shards, workers, n, accumulate, s)
-                                : launch_reduce<false>(gsum, L, SL, shards, workers, n, accumulate, s);
+        rc = dtype == ACCO_BF16
+                 ? launch_reduce<true>(gsum, L, SL, shards, workers, n, accumulate, reduce_chunk<true>(workers), s)
+                 : launch_reduce<false>(gsum, L, SL, shards, workers, n, accumulate, reduce_chunk<false>(workers), s);
     }
     if (rc == ACCO_OK && total != nullptr) *total = new_total;
     return rc;
@@ -942,7 +965,7 @@ ACCO_API int acco_accumulate_publish(float* acc, const uint16_t* grad_bf16, uint
 
 namespace {
 
-// Fused reduce + step over the last (up to kReduceChunk) shards; leading chunks of a larger
+// Fused reduce + step over the last (up to `chunk`) shards; leading chunks of a larger
 // worker count go through the plain reduction first.  The device-scalar forms have the bf16
 // output only.
 template <bool BF16, class SC>
@@ -952,25 +975,29 @@ int launch_reduce_estimate(const float* theta, const float* m, const float* v, f
                            int64_t n, const SC& sc, hipStream_t s)
 {
     if (from_device<SC> && (o32 != nullptr || o16 == nullptr)) return ACCO_ERR_ARG;
-    const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
+    const int chunk = reduce_chunk<BF16>(workers);
+    const int lead  = ((workers - 1) / chunk) * chunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, s)) return rc;
-    const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
-    const int       cnt  = workers - lead;
-    return with_layout(L, [&](auto at) {
-        return with_shard_layout<BF16>(SL, [&](auto sat) {
-            constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
-            auto go = [&](auto acc_tag) {
-                constexpr bool ACC = decltype(acc_tag)::value;
-                if constexpr (!from_device<SC>) {
-                    if (o32 != nullptr && o16 != nullptr)
-                        return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at, sat}, n, s);
-                    if (o32 != nullptr)
-                        return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at, sat}, n, s);
-                }
-                return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at, sat}, n, s);
-            };
-            return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, chunk, s)) return rc;
+    const int cnt = workers - lead;
+    return with_width<BF16>(cnt, [&](auto width) {
+        constexpr int WM   = decltype(width)::value;
+        const auto    ptrs = chunk_ptrs<WM>(shards, lead, workers);
+        return with_layout(L, [&](auto at) {
+            return with_shard_layout<BF16>(SL, [&](auto sat) {
+                constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+                auto go = [&](auto acc_tag) {
+                    constexpr bool ACC = decltype(acc_tag)::value;
+                    if constexpr (!from_device<SC>) {
+                        if (o32 != nullptr && o16 != nullptr)
+                            return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, true, B, S, SC, WM>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, o16, sc, at, sat}, n, s);
+                        if (o32 != nullptr)
+                            return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, true, false, B, S, SC, WM>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, o32, nullptr, sc, at, sat}, n, s);
+                    }
+                    return launch(kReduceEstimate, ReduceAdamOp<false, BF16, ACC, true, false, true, B, S, SC, WM>{theta, m, v, gsum, ptrs, cnt, nullptr, nullptr, nullptr, nullptr, o16, sc, at, sat}, n, s);
+                };
+                return lead > 0 ? go(std::true_type{}) : go(std::false_type{});
+            });
         });
     });
 }
@@ -980,17 +1007,21 @@ int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const St
                          const StateLayout& SL, const void* const* shards, int workers,
                          uint16_t* o16, int64_t n, const SC& sc, hipStream_t s)
 {
-    const int lead = ((workers - 1) / kReduceChunk) * kReduceChunk;
+    const int chunk = reduce_chunk<BF16>(workers);
+    const int lead  = ((workers - 1) / chunk) * chunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, true, s)) return rc;
-    const ShardPtrs ptrs = chunk_ptrs(shards, lead, workers);
-    const int       cnt  = workers - lead;
-    return with_layout(L, [&](auto at) {
-        return with_shard_layout<BF16>(SL, [&](auto sat) {
-            constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
-            if (o16 != nullptr)
-                return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B, S, SC>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at, sat}, n, s);
-            return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B, S, SC>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at, sat}, n, s);
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, true, chunk, s)) return rc;
+    const int cnt = workers - lead;
+    return with_width<BF16>(cnt, [&](auto width) {
+        constexpr int WM   = decltype(width)::value;
+        const auto    ptrs = chunk_ptrs<WM>(shards, lead, workers);
+        return with_layout(L, [&](auto at) {
+            return with_shard_layout<BF16>(SL, [&](auto sat) {
+                constexpr bool B = is_blocked<decltype(at)>, S = is_blocked<decltype(sat)>;
+                if (o16 != nullptr)
+                    return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, true, B, S, SC, WM>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, o16, sc, at, sat}, n, s);
+                return launch(kReduceCommit, ReduceAdamOp<true, BF16, true, false, false, false, B, S, SC, WM>{theta, m, v, gsum, ptrs, cnt, theta, m, v, nullptr, nullptr, sc, at, sat}, n, s);
+            });
         });
     });
 }

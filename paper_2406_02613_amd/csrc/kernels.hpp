@@ -29,7 +29,8 @@ typedef float    f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
-constexpr int kReduceChunk = 8;   // worker shards summed per launch
+constexpr int kReduceChunk     = 8;   // worker shards summed per launch
+constexpr int kReduceChunkWide = 16;  // the same for bf16 shards when there are more than 8
 constexpr int kBatchMax    = 16;  // workers' accumulations served by one batched launch
 constexpr int kMaxThreads = 512;  // per workgroup: leaves 256 VGPRs per lane for loads in flight
 
@@ -515,8 +516,9 @@ struct CastOp {
 
 // ------------------------------------------------------------------ reduce
 
+template <int WMAX>
 struct ShardPtrs {
-    const void* p[kReduceChunk];
+    const void* p[WMAX];
 };
 
 // Sum of up to WMAX worker shards per launch, ascending worker order.  ACC: start
@@ -526,7 +528,7 @@ template <int WMAX, bool BF16, bool ACC, bool BLOCKED, bool SB = false>
 struct ReduceOp {
     static constexpr int kElems = 4;
     float*             gsum;
-    ShardPtrs          shards;
+    ShardPtrs<WMAX>    shards;
     int                workers;  // 1 .. WMAX
     StateAddr<BLOCKED> at;       // layout of gsum
     StateAddr<SB>      sat;      // layout of every shard
@@ -648,18 +650,18 @@ struct AdamOp {
 
 // ------------------------------------------------------------------ reduce fused with the step
 
-// The owner-side reduction of up to kReduceChunk worker shards folded into the AdamW step:
+// The owner-side reduction of up to WMAX worker shards folded into the AdamW step:
 // the gradient sum is formed in registers (same order as ReduceOp), optionally stored to
 // gsum (stage 1 keeps it for stage 2), and consumed by the update in the same pass.
 template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool OUT_BF16,
-          bool BLOCKED, bool SB = false, class SC = ScalarsByValue>
+          bool BLOCKED, bool SB = false, class SC = ScalarsByValue, int WMAX = kReduceChunk>
 struct ReduceAdamOp {
     static constexpr int kElems = 4;
     const float*       theta;
     const float*       m;
     const float*       v;
     float*             gsum;  // read when ACC, written when WRITE_GSUM
-    ShardPtrs          shards;
+    ShardPtrs<WMAX>    shards;
     int                workers;
     float*             theta_w;
     float*             m_w;
@@ -671,8 +673,8 @@ struct ReduceAdamOp {
     StateAddr<SB>      sat;   // layout of every shard
     struct In {
         f4 t, m, v, g;
-        f4 x[BF16 ? 1 : kReduceChunk];
-        u2 b[BF16 ? kReduceChunk : 1];
+        f4 x[BF16 ? 1 : WMAX];
+        u2 b[BF16 ? WMAX : 1];
     };
     __device__ __forceinline__ In load(int64_t i) const
     {
@@ -683,7 +685,7 @@ struct ReduceAdamOp {
         in.v = ld(reinterpret_cast<const f4*>(v) + a);
         if (ACC) in.g = ld(reinterpret_cast<const f4*>(gsum) + a);
 #pragma unroll
-        for (int w = 0; w < kReduceChunk; ++w) {
+        for (int w = 0; w < WMAX; ++w) {
             if (w < workers) {
                 if (BF16)
                     in.b[w] = ld(reinterpret_cast<const u2*>(shards.p[w]) + sat.vec(i));
@@ -698,7 +700,7 @@ struct ReduceAdamOp {
         const int64_t a = at.vec(i);
         f4            g = in.g;
 #pragma unroll
-        for (int w = 0; w < kReduceChunk; ++w) {
+        for (int w = 0; w < WMAX; ++w) {
             if (w < workers) {
                 const f4 x = BF16 ? unpack_bf16x4(in.b[w]) : in.x[w];
                 g          = (!ACC && w == 0) ? x : g + x;
