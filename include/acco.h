@@ -323,8 +323,9 @@ int acco_reduce_estimate_step(const float* theta, const float* m, const float* v
  *   (theta, m, v) <- AdamW(theta, m, v; g / *total; update index = *step + 1);  *step += 1.
  * Same values as the two separate calls; saves writing and re-reading gsum.
  *   gsum    device, fp32[n], in/out: the retained stage-1 sum.  With workers <= 8 (<= 16 bf16
- *           shards) it is not written; with more workers it receives the partial sum over all
- *           but the shards of the last pass.  Its contents are not needed after this call.
+ *           shards under the default launch shape) it is not written; with more workers it
+ *           receives the partial sum over all but the shards of the last pass.  Its contents
+ *           are not needed after this call.
  *   counts  host, required;  total  host, in/out, required.
  */
 int acco_reduce_commit_step(float* theta, float* m, float* v, float* gsum,

@@ -128,13 +128,15 @@ unsigned lds_for_groups(int groups)
     return (unsigned)(kLdsPerCu / groups / kLdsGranule * kLdsGranule);
 }
 
-Geometry geometry(Entry e, int64_t nvec, bool bounded, int rows = 1)
+Geometry geometry(Entry e, int64_t nvec, bool bounded, int rows = 1, int max_vectors = 4)
 {
     const LaunchShape shape = unpack_shape(g_shape[e].load(std::memory_order_relaxed));
     Geometry          g;
     g.threads = shape.threads;
-    g.vectors = shape.vectors;
-    const int     per_cu = shape.wg_per_cu;
+    // max_vectors == 0: an Op that only exists as the flat kernel - one vector per thread and no
+    // cap on the workgroups, whatever the entry's shape says
+    g.vectors = max_vectors == 0 ? 1 : shape.vectors > max_vectors ? max_vectors : shape.vectors;
+    const int     per_cu = max_vectors == 0 ? 0 : shape.wg_per_cu;
     const int64_t tile   = (int64_t)g.threads * g.vectors;
     g.tiles              = (nvec + tile - 1) / tile;
     const int64_t want   = g.tiles < 1 ? 1 : g.tiles;  // the scalar tail still needs workgroup 0
@@ -154,32 +156,50 @@ Geometry geometry(Entry e, int64_t nvec, bool bounded, int rows = 1)
 // the device from a pointer table) over n elements per row.
 // bounded = false: ignore the entry's bound on resident wavefronts (kernels that write more
 // than they read want the full occupancy)
+template <class Op, class = void>
+struct MaxVectors {
+    static constexpr int value = 4;
+};
+template <class Op>
+struct MaxVectors<Op, std::void_t<decltype(Op::kMaxVectors)>> {
+    static constexpr int value = Op::kMaxVectors;
+};
+
 template <class Src>
 int launch_source(Entry e, const Src& src, int rows, int64_t n, hipStream_t stream, bool bounded)
 {
     typedef typename Src::Op Op;
-    const int64_t  nvec = n / Op::kElems;
-    const Geometry g    = geometry(e, nvec, bounded, rows);
+    constexpr int  kMaxV = MaxVectors<Op>::value;
+    const int64_t  nvec  = n / Op::kElems;
+    const Geometry g     = geometry(e, nvec, bounded, rows, kMaxV);
     if (g.vectors == 1 && (int64_t)g.grid.x >= g.tiles) {
         hipLaunchKernelGGL((flat_kernel<Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
                            n);
         return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
     }
-    switch (g.vectors) {
-        case 1:
-            hipLaunchKernelGGL((stream_kernel<1, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
-                               g.tiles, n);
-            break;
-        case 2:
-            hipLaunchKernelGGL((stream_kernel<2, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
-                               g.tiles, n);
-            break;
-        default:
-            hipLaunchKernelGGL((stream_kernel<4, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src, nvec,
-                               g.tiles, n);
-            break;
+    if constexpr (kMaxV == 0) return ACCO_ERR_DEVICE;  // flat only, and too long for one dispatch
+    if (g.vectors == 1) {
+        if constexpr (kMaxV >= 1)
+            hipLaunchKernelGGL((stream_kernel<1, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src,
+                               nvec, g.tiles, n);
+    } else if (g.vectors == 2) {
+        if constexpr (kMaxV >= 2)
+            hipLaunchKernelGGL((stream_kernel<2, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src,
+                               nvec, g.tiles, n);
+    } else {
+        if constexpr (kMaxV >= 4)
+            hipLaunchKernelGGL((stream_kernel<4, Src>), g.grid, dim3(g.threads), g.lds_bytes, stream, src,
+                               nvec, g.tiles, n);
     }
     return hipGetLastError() == hipSuccess ? ACCO_OK : ACCO_ERR_DEVICE;
+}
+
+// Would a launch of entry e over n elements (4 per vector) run as flat_kernel?  With the
+// entry's default shape it does, for any n the library accepts per dispatch.
+bool flat_applies(Entry e, int64_t n)
+{
+    const Geometry g = geometry(e, n / 4, true);
+    return g.vectors == 1 && (int64_t)g.grid.x >= g.tiles;
 }
 
 template <class Op>
@@ -573,12 +593,13 @@ ShardPtrs<WMAX> chunk_ptrs(const void* const* shards, int begin, int end)
     return ptrs;
 }
 
-// Shards taken per launch: 8, or 16 bf16 shards when there are more than 8 (each pass over
-// fewer than all shards costs a round trip of gsum: 8 bytes per element).
+// Shards taken per launch by entry e: 8, or 16 bf16 shards when there are more than 8 (each
+// pass over fewer than all shards costs a round trip of gsum: 8 bytes per element).  The
+// 16-shard kernels exist in the flat shape only; with another shape selected it stays at 8.
 template <bool BF16>
-int reduce_chunk(int workers)
+int reduce_chunk(Entry e, int workers, int64_t n)
 {
-    return BF16 && workers > kReduceChunk ? kReduceChunkWide : kReduceChunk;
+    return BF16 && workers > kReduceChunk && flat_applies(e, n) ? kReduceChunkWide : kReduceChunk;
 }
 
 // f(integral_constant<int, WMAX>) with the kernel width that holds `cnt` shards
@@ -601,12 +622,13 @@ int with_shard_layout(const StateLayout& SL, F&& f)
     return f(StateAddr<false>{});
 }
 
-// plain reduction of shards [0, workers) into gsum, `chunk` at a time
+// plain reduction of shards [0, workers) into gsum, 8 or 16 at a time
 template <bool BF16>
 int launch_reduce(float* gsum, const StateLayout& L, const StateLayout& SL,
-                  const void* const* shards, int workers, int64_t n, bool accumulate, int chunk,
+                  const void* const* shards, int workers, int64_t n, bool accumulate,
                   hipStream_t stream)
 {
+    const int chunk = reduce_chunk<BF16>(kReduce, workers, n);
     for (int w0 = 0; w0 < workers; w0 += chunk) {
         const int  end = w0 + chunk < workers ? w0 + chunk : workers;
         const bool acc = accumulate || w0 > 0;
@@ -677,9 +699,8 @@ ACCO_API int acco_reduce_shards(float* gsum, const void* const* shards, int work
     int rc = ACCO_OK;
     if (n > 0) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        rc = dtype == ACCO_BF16
-                 ? launch_reduce<true>(gsum, L, SL, shards, workers, n, accumulate, reduce_chunk<true>(workers), s)
-                 : launch_reduce<false>(gsum, L, SL, shards, workers, n, accumulate, reduce_chunk<false>(workers), s);
+        rc = dtype == ACCO_BF16 ? launch_reduce<true>(gsum, L, SL, shards, workers, n, accumulate, s)
+                                : launch_reduce<false>(gsum, L, SL, shards, workers, n, accumulate, s);
     }
     if (rc == ACCO_OK && total != nullptr) *total = new_total;
     return rc;
@@ -975,10 +996,10 @@ int launch_reduce_estimate(const float* theta, const float* m, const float* v, f
                            int64_t n, const SC& sc, hipStream_t s)
 {
     if (from_device<SC> && (o32 != nullptr || o16 == nullptr)) return ACCO_ERR_ARG;
-    const int chunk = reduce_chunk<BF16>(workers);
+    const int chunk = reduce_chunk<BF16>(kReduceEstimate, workers, n);
     const int lead  = ((workers - 1) / chunk) * chunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, chunk, s)) return rc;
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, false, s)) return rc;
     const int cnt = workers - lead;
     return with_width<BF16>(cnt, [&](auto width) {
         constexpr int WM   = decltype(width)::value;
@@ -1007,10 +1028,10 @@ int launch_reduce_commit(float* theta, float* m, float* v, float* gsum, const St
                          const StateLayout& SL, const void* const* shards, int workers,
                          uint16_t* o16, int64_t n, const SC& sc, hipStream_t s)
 {
-    const int chunk = reduce_chunk<BF16>(workers);
+    const int chunk = reduce_chunk<BF16>(kReduceCommit, workers, n);
     const int lead  = ((workers - 1) / chunk) * chunk;
     if (lead > 0)
-        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, true, chunk, s)) return rc;
+        if (int rc = launch_reduce<BF16>(gsum, L, SL, shards, lead, n, true, s)) return rc;
     const int cnt = workers - lead;
     return with_width<BF16>(cnt, [&](auto width) {
         constexpr int WM   = decltype(width)::value;

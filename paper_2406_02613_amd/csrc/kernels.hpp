@@ -204,7 +204,9 @@ __device__ __forceinline__ void st_through(T* p, T x)
         asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(x) : "memory");
 }
 
-// Op supplies: kElems (elements per vector: 4, or 8 for all-bf16 kernels); struct In;
+// Op supplies: kElems (elements per vector: 4, or 8 for all-bf16 kernels); optionally
+//              kMaxVectors (most vectors in flight per thread in stream_kernel, default 4;
+//              0: the Op is only ever run by flat_kernel); struct In;
 //              In load(int64_t vec) const; void apply(int64_t vec, const In&) const;
 //              void scalar(int64_t elem) const;
 //              struct Shared; static Op make(const BatchPtrs&, int worker, const Shared&)
@@ -527,6 +529,9 @@ struct ShardPtrs {
 template <int WMAX, bool BF16, bool ACC, bool BLOCKED, bool SB = false>
 struct ReduceOp {
     static constexpr int kElems = 4;
+    // vectors in flight per thread in the looping kernel: fp32 shards hold too many loads for
+    // more than 2 (they would spill); the wide form exists as the flat kernel only (0)
+    static constexpr int kMaxVectors = WMAX > kReduceChunk ? 0 : BF16 ? 4 : 2;
     float*             gsum;
     ShardPtrs<WMAX>    shards;
     int                workers;  // 1 .. WMAX
@@ -568,11 +573,16 @@ struct ReduceOp {
     {
         const int64_t a = at.elem(j), b = sat.elem(j);
         float         s = ACC ? gsum[a] : 0.0f;
-        for (int w = 0; w < workers; ++w) {
-            const float x =
-                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
-                     : static_cast<const float*>(shards.p[w])[b];
-            s = (!ACC && w == 0) ? x : s + x;
+        // unrolled, so that the pointer table is indexed by constants (it lives in the kernel
+        // arguments; a run-time index would copy it to private memory)
+#pragma unroll
+        for (int w = 0; w < WMAX; ++w) {
+            if (w < workers) {
+                const float x =
+                    BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
+                         : static_cast<const float*>(shards.p[w])[b];
+                s = (!ACC && w == 0) ? x : s + x;
+            }
         }
         gsum[a] = s;
     }
@@ -657,6 +667,7 @@ template <bool COMMIT, bool BF16, bool ACC, bool WRITE_GSUM, bool OUT_F32, bool 
           bool BLOCKED, bool SB = false, class SC = ScalarsByValue, int WMAX = kReduceChunk>
 struct ReduceAdamOp {
     static constexpr int kElems = 4;
+    static constexpr int kMaxVectors = WMAX > kReduceChunk ? 0 : BF16 ? 4 : 2;
     const float*       theta;
     const float*       m;
     const float*       v;
@@ -721,11 +732,14 @@ struct ReduceAdamOp {
     {
         const int64_t a = at.elem(j), b = sat.elem(j);
         float         g = ACC ? gsum[a] : 0.0f;
-        for (int w = 0; w < workers; ++w) {
-            const float x =
-                BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
-                     : static_cast<const float*>(shards.p[w])[b];
-            g = (!ACC && w == 0) ? x : g + x;
+#pragma unroll
+        for (int w = 0; w < WMAX; ++w) {
+            if (w < workers) {
+                const float x =
+                    BF16 ? __uint_as_float((uint32_t)static_cast<const uint16_t*>(shards.p[w])[b] << 16)
+                         : static_cast<const float*>(shards.p[w])[b];
+                g = (!ACC && w == 0) ? x : g + x;
+            }
         }
         if (WRITE_GSUM) gsum[a] = g;
         float t, mm, vv;

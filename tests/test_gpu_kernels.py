@@ -118,7 +118,7 @@ def test_cast_sizes(acco, shape):
 
 @pytest.mark.parametrize("shape", SHAPES[:4])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("W", [1, 2, 8, 9, 17])
+@pytest.mark.parametrize("W", [1, 2, 8, 9, 16, 17, 32, 33, 64])
 def test_reduce_is_bit_exact_in_worker_order(acco, shape, dtype, W):
     acco.set_launch_shape("reduce", *shape)
     rng = np.random.default_rng(3 + W)
@@ -422,7 +422,7 @@ def test_accumulate_publish_equals_accumulate_then_cast(acco, shape):
 
 @pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 2, 1), (512, 4, 0)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("W", [1, 3, 8, 9, 20])
+@pytest.mark.parametrize("W", [1, 3, 8, 9, 16, 20, 32, 33, 64])
 def test_fused_reduce_steps_equal_the_separate_calls_and_the_oracle(acco, shape, dtype, W):
     acco.set_launch_shape("reduce_estimate", *shape)
     acco.set_launch_shape("reduce_commit", *shape)
@@ -942,7 +942,7 @@ def test_batched_accumulation_steps_equal_the_single_calls(acco, shape, W):
 
 @pytest.mark.parametrize("shape", [DEFAULT_SHAPE, (128, 1, 0), (256, 2, 0), (512, 4, 0)])
 @pytest.mark.parametrize("block", [8, 64, 1024, 16384])
-@pytest.mark.parametrize("W", [1, 3, 8, 20])
+@pytest.mark.parametrize("W", [1, 3, 8, 20, 32, 40])
 def test_interleaved_communication_buffers_give_the_same_bits(acco, shape, block, W):
     """The W communication buffers as the interleaved blocks of one buffer: every operation that
     publishes into them (out_layout) and every reduction that reads them (shard_layout) against
